@@ -1,0 +1,185 @@
+/*
+ * vvs.h - C ABI of the MI355X (gfx950) target-model verification pass for speculative decoding of
+ * visual autoregressive models.
+ *
+ * One call of vvs_verify is one "target forward pass" in the sense of the paper's tokens-per-forward
+ * metric (Section 5, "Metrics"): a KV-cached decoder-only transformer scores the pending token and N
+ * drafted VQ tokens (a chain, or a tree under an ancestor mask: Section 3, "Verification
+ * Redundancy") for B prompts, each as a conditional / unconditional row pair, mixes the two logit
+ * rows, applies softmax, and runs the accept / resample rule of Section 2 ("Speculative Decoding").
+ * vvs_kv_commit then keeps the K/V of the accepted path (Section 4.1: restoring the KV entries
+ * re-establishes exact AR conditioning).
+ *
+ * Notation: p = target distribution, q = draft distribution (the paper prints the two letters the
+ * other way round; the rule is the same: accept with probability min(1, target/draft)).
+ * B prompts; R = 2B rows, row 2b conditional, row 2b+1 unconditional; N draft nodes numbered 1..N,
+ * node 0 = root = the pending token (emitted, K/V not cached yet); T = N + 1; V_eff = logit_hi -
+ * logit_lo; S_b = cached length of prompt b.
+ *
+ * Ownership: the caller allocates every device buffer (KV cache, workspace, packed weights, inputs,
+ * outputs), sized by vvs_query_sizes; the library never allocates or frees device memory and never
+ * synchronises the stream, except vvs_create (synchronous: it zero-fills the KV cache and uploads
+ * small tables).  Pointers named d_* are DEVICE pointers, h_* are HOST pointers.  Device buffers
+ * must stay valid until the work queued on the stream has finished.  Calls on one context must be
+ * issued on one stream (or be ordered by the caller).
+ *
+ * Errors: every function returns a vvs_status; nothing is launched when the status is not VVS_OK
+ * (arguments and call order are checked on the host first).  vvs_last_error gives the message.
+ */
+#ifndef VVS_H
+#define VVS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct vvs_ctx vvs_ctx;        /* opaque host object; owns no device memory */
+typedef void* vvs_stream;              /* a hipStream_t (NULL = the default stream) */
+
+typedef enum {
+  VVS_OK = 0,
+  VVS_EINVAL = -1,   /* bad argument (NULL pointer, malformed tree, value out of range) */
+  VVS_ESTATE = -2,   /* call order: verify before prefill, commit without verify, ... */
+  VVS_ESIZE = -3,    /* shape not supported / exceeds the sizes the context was created for */
+  VVS_EHIP = -4      /* a HIP call failed */
+} vvs_status;
+
+enum { VVS_FP32 = 0, VVS_BF16 = 1 };               /* vvs_config.dtype */
+enum { VVS_PREFIX_CLASS = 0, VVS_PREFIX_DENSE = 1 }; /* vvs_config.prefix_kind */
+enum { VVS_STRICT = 0, VVS_RELAXED = 1 };           /* acceptance mode */
+#define VVS_MAX_T 64                                 /* max query tokens per row in one verify call */
+
+typedef struct {
+  int32_t n_layers, d_model, n_heads, d_ff;
+  int32_t vocab;                 /* rows of the token embedding table */
+  int32_t logit_lo, logit_hi;    /* allowed id slice [lo, hi): only these ids get logits */
+  int32_t grid_h, grid_w;        /* image token grid; G = grid_h * grid_w tokens per image */
+  int32_t prefix_len;            /* P condition tokens in front of the image tokens */
+  int32_t prefix_kind;           /* VVS_PREFIX_CLASS: ids into a class table whose last row (id
+                                    n_classes) is the null class; VVS_PREFIX_DENSE: [P, d] vectors */
+  int32_t n_classes;
+  int32_t n_prompts;             /* B */
+  int32_t max_nodes;             /* largest N of any verify call, <= VVS_MAX_T - 1 */
+  int32_t dtype;                 /* VVS_FP32: fp32 weights, activations and KV cache;
+                                    VVS_BF16: bf16 weights, GEMM/attention operands and KV cache,
+                                    fp32 accumulation, fp32 residual stream and logits */
+  float cfg_scale;               /* s in l_u + s (l_c - l_u) */
+  float rms_eps;
+  float rope_base;
+  int32_t relax_k;               /* neighbours per id in the table given to vvs_set_neighbors */
+  float relax_delta;             /* budget of target mass the relaxed rule may absorb */
+} vvs_config;
+
+/* Sizes in bytes of the three device buffers a context needs.  VVS_ESIZE if the shape is not
+ * supported (bf16 needs d_model % 64 == 0, d_ff % 64 == 0, V_eff % 64 == 0, head size 64 or 128;
+ * any dtype needs head size % 4 == 0, max_nodes < VVS_MAX_T). */
+vvs_status vvs_query_sizes(const vvs_config* cfg, size_t* kv_bytes, size_t* workspace_bytes,
+                           size_t* packed_weight_bytes);
+
+/* Creates a context over caller-allocated device buffers (256-byte aligned).  Synchronous. */
+vvs_status vvs_create(const vvs_config* cfg, void* d_kv, void* d_workspace, void* d_packed_weights,
+                      vvs_ctx** out);
+void vvs_destroy(vvs_ctx* ctx);
+const char* vvs_last_error(const vvs_ctx* ctx);   /* ctx may be NULL: error of the last failed create/query */
+
+/* Number of canonical weight tensors (2 + 9 * n_layers + 2) in this order:
+ *   embed [vocab, d]; prefix_embed [n_classes + 1, d] (may be NULL for dense prefixes);
+ *   per layer: g1 [d], wq [d,d], wk [d,d], wv [d,d], wo [d,d], g2 [d], wg [d,F], wu [d,F], wd [F,d];
+ *   gf [d]; wout [d, vocab].
+ * Matrices are row-major [in, out] (activations multiply from the left); element type = dtype. */
+int32_t vvs_num_weight_tensors(const vvs_config* cfg);
+
+/* Repacks the canonical tensors (device pointers, host array of n pointers) into d_packed_weights.
+ * The canonical tensors may be freed once the stream has passed this point. */
+vvs_status vvs_load_weights(vvs_ctx* ctx, const void* const* d_tensors, int32_t n, vvs_stream s);
+
+/* Neighbour table for the relaxed rule: int32 [vocab, relax_k] on the device, for every id its
+ * nearest other ids in latent space in ascending distance.  Kept by reference. */
+vvs_status vvs_set_neighbors(vvs_ctx* ctx, const int32_t* d_nbr);
+
+/* Host-only check of a draft topology, with the same rules as vvs_verify (either array may be NULL;
+ * both NULL = chain).  Outputs (host, may be NULL): h_depth int32 [T], h_parent_out int32 [N]. */
+vvs_status vvs_check_tree(int32_t n_nodes, const int32_t* h_parent, const uint8_t* h_tree_mask, int32_t* h_depth,
+                          int32_t* h_parent_out);
+
+/* Prefill (Algorithm 2 of the supplementary material, first line): runs the P prefix tokens and then
+ * n_forced teacher-forced image tokens of every row through the model under a causal mask, caches
+ * their K/V, and samples the next image token of each prompt from the CFG-mixed distribution at
+ * the last position by inverse CDF with d_uniform[b].  Resets the context state.
+ *   d_prefix_cond  : class kind: int32 [B, P] class ids;      dense kind: dtype [B, P, d]
+ *   d_prefix_uncond: class kind: int32 [B, P] or NULL (null class); dense kind: dtype [P, d], shared
+ *   d_forced_tokens: int32 [B, n_forced] or NULL when n_forced == 0; n_forced <= G - 1
+ *   d_uniform      : float [B] in [0, 1)
+ *   d_first_token  : int32 [B] out (full-vocabulary id); it becomes the pending token. */
+vvs_status vvs_prefill(vvs_ctx* ctx, const void* d_prefix_cond, const void* d_prefix_uncond,
+                       int32_t n_forced, const int32_t* d_forced_tokens, const float* d_uniform,
+                       int32_t* d_first_token, vvs_stream s);
+
+/* One verification pass (Section 2; Algorithm 2: "logits <- M_T(C_t); a <- Verify(logits, C_t)").
+ *   n_nodes      : N >= 0 (0 = plain AR sampling of one token)
+ *   h_parent     : host int32 [N], h_parent[j-1] in [0, j-1] = parent of node j; NULL = chain
+ *   h_tree_mask  : host uint8 [T, T], entry (i, j) != 0 iff j is i or an ancestor of i; may be NULL.
+ *                  When both are given they must describe the same tree; when only the mask is
+ *                  given the parents are derived from it.
+ *   d_draft_tokens: int32 [B, N], full-vocabulary ids inside [logit_lo, logit_hi); siblings distinct
+ *   d_draft_probs : float [B, T, V_eff]; row j = the distribution the children of node j were drawn
+ *                   from (rows of leaves are not read)
+ *   d_uniforms    : float [B, T, 2] in [0, 1): [b, c, 0] decides node c, [b, j, 1] draws the final
+ *                   token when the walk ends at node j
+ *   mode          : VVS_STRICT or VVS_RELAXED
+ *   d_accept_len  : int32 [B] out, number of accepted draft tokens a_b
+ *   d_path        : int32 [B, VVS_MAX_T] out, node ids of the accepted path: path[0] = 0, then a_b ids
+ *   d_next_token  : int32 [B] out, resampled / bonus token (full-vocabulary id); -1 for a prompt whose
+ *                   image is already complete (then a_b = 0)
+ * Children of a node are tried in ascending node id; after a rejection the target becomes the
+ * normalised positive part of (target - draft) and the rejected id leaves the draft distribution.
+ * At most G - n_emitted_b - 1 draft tokens are accepted, so the final token still lies in the image.
+ * The outcome is also kept in the workspace for vvs_kv_commit. */
+vvs_status vvs_verify(vvs_ctx* ctx, int32_t n_nodes, const int32_t* h_parent, const uint8_t* h_tree_mask,
+                      const int32_t* d_draft_tokens, const float* d_draft_probs, const float* d_uniforms,
+                      int32_t mode, int32_t* d_accept_len, int32_t* d_path, int32_t* d_next_token,
+                      vvs_stream s);
+
+/* The acceptance stage alone (CFG mix, softmax, accept / resample, path walk) on logits supplied by
+ * the caller: d_raw_logits float [R, T, V_eff] (row-major, row r = 2b + {0: conditional,
+ * 1: unconditional}).  Same outputs as vvs_verify; does not touch the KV cache, and the outcome is
+ * not available to vvs_kv_commit. */
+vvs_status vvs_accept_from_logits(vvs_ctx* ctx, int32_t n_nodes, const int32_t* h_parent,
+                                  const uint8_t* h_tree_mask, const float* d_raw_logits,
+                                  const int32_t* d_draft_tokens, const float* d_draft_probs,
+                                  const float* d_uniforms, int32_t mode, int32_t* d_accept_len,
+                                  int32_t* d_path, int32_t* d_next_token, vvs_stream s);
+
+/* Section 4.1: moves the K/V of the pending token and of the accepted path of the last vvs_verify
+ * into consecutive cache slots S_b .. S_b + a_b, advances S_b and n_emitted_b by a_b + 1 and makes
+ * next_token the pending token.  Exactly one commit per verify. */
+vvs_status vvs_kv_commit(vvs_ctx* ctx, vvs_stream s);
+
+/* Per-prompt state: int32 [3, B] out = cached length S_b, emitted image tokens, pending token. */
+vvs_status vvs_read_state(vvs_ctx* ctx, int32_t* d_state, vvs_stream s);
+
+/* Inspection of the last verify (or prefill, with T = 1): any pointer may be NULL.
+ *   d_raw_logits float [R, T, V_eff]; d_mixed_logits float [B, T, V_eff]; d_probs float [B, T, V_eff]. */
+vvs_status vvs_debug_logits(vvs_ctx* ctx, float* d_raw_logits, float* d_mixed_logits, float* d_probs,
+                            vvs_stream s);
+
+/* Cached K and V of one (layer, row) as float [n_slots, d_model] (head-major inside a row), slots
+ * 0 .. n_slots - 1. */
+vvs_status vvs_debug_kv(vvs_ctx* ctx, int32_t layer, int32_t row, int32_t n_slots, float* d_k, float* d_v,
+                        vvs_stream s);
+
+/* C[M, N] = A[M, K] * W[K, N] through the same repacking and GEMM kernels the forward uses (bf16
+ * contexts: the MFMA path; n and k multiples of 64), for unit tests.  d_a dtype [M, K]; d_w dtype
+ * [K, N] (canonical [in, out] layout); d_scratch of vvs_debug_gemm_scratch_bytes bytes, 256-byte
+ * aligned; d_c float [M, N]. */
+size_t vvs_debug_gemm_scratch_bytes(const vvs_ctx* ctx, int32_t m, int32_t n, int32_t k);
+vvs_status vvs_debug_gemm(vvs_ctx* ctx, int32_t m, int32_t n, int32_t k, const void* d_a, const void* d_w,
+                          void* d_scratch, float* d_c, vvs_stream s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VVS_H */

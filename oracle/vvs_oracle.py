@@ -292,6 +292,7 @@ class Oracle:
         assert n_forced <= self.G - 1
         first = np.zeros(self.B, dtype=np.int64)
         self.prefill_logits = np.zeros((self.R, self.hi - self.lo))
+        self.prefill_probs = np.zeros((self.B, self.hi - self.lo))
         for b in range(self.B):
             pc, pu = self.prefix_embeddings(prefix_cond, prefix_uncond, b)
             rows_logits = []
@@ -309,6 +310,7 @@ class Oracle:
                 rows_logits.append(logits[T - 1])
                 self.prefill_logits[row] = logits[T - 1]
             _, p = self.mix(rows_logits[0], rows_logits[1])
+            self.prefill_probs[b] = p
             first[b] = self.lo + inverse_cdf(p, float(uniforms[b]))
             self.pending[b] = first[b]
             self.n_emitted[b] = n_forced + 1
@@ -337,6 +339,7 @@ class Oracle:
         accept_len = np.zeros(self.B, dtype=np.int64)
         next_token = -np.ones(self.B, dtype=np.int64)
         paths, node_kv = [], []
+        self.traces = [None] * self.B
         self.mixed_logits = np.zeros((self.B, T, self.hi - self.lo))
         self.raw_logits = np.zeros((self.R, T, self.hi - self.lo))
         self.probs = np.zeros_like(self.mixed_logits)
@@ -356,9 +359,11 @@ class Oracle:
                 paths.append([0])
                 continue
             cap = self.G - self.n_emitted[b] - 1
+            tr = {}
             a, path, nxt = decide(p, np.asarray(draft_probs[b], dtype=F64), draft_tokens[b] - self.lo, parent,
                                   np.asarray(uniforms[b], dtype=F64), cap, mode,
-                                  self.nbr, self.relax_k, self.relax_delta, self.lo)
+                                  self.nbr, self.relax_k, self.relax_delta, self.lo, trace=tr)
+            self.traces[b] = tr
             accept_len[b], next_token[b] = a, self.lo + nxt
             paths.append(path)
         self.last = dict(paths=paths, node_kv=node_kv, tokens=draft_tokens, accept_len=accept_len,
@@ -402,7 +407,7 @@ def inverse_cdf(p, u):
     return int(np.nonzero(p > 0)[0][-1])
 
 
-def relaxed_target(P, x, nbr_row, k, delta):
+def relaxed_target(P, x, nbr_row, k, delta, trace=None):
     """Relaxed rule: walk the neighbour list of x in ascending distance, absorbing target mass while
     the absorbed total stays <= delta (stop at the first neighbour that would exceed it).  Returns
     (numerator, modified target: absorbed mass moved onto x)."""
@@ -412,6 +417,8 @@ def relaxed_target(P, x, nbr_row, k, delta):
         n = int(n)
         if n < 0 or n >= P.shape[0]:       # neighbour outside the allowed slice: no target mass
             continue
+        if trace is not None:
+            trace["relax_margin"] = min(trace["relax_margin"], abs(absorbed + P[n] - delta))
         if absorbed + P[n] > delta:
             break
         absorbed += P[n]
@@ -420,7 +427,7 @@ def relaxed_target(P, x, nbr_row, k, delta):
     return Pt[x], Pt
 
 
-def decide(p_rows, q_rows, tok_local, parent, u, cap, mode=0, nbr=None, relax_k=0, relax_delta=0.0, lo=0):
+def decide(p_rows, q_rows, tok_local, parent, u, cap, mode=0, nbr=None, relax_k=0, relax_delta=0.0, lo=0, trace=None):
     """Acceptance walk for one prompt.
 
     p_rows [T, V] target distributions at the root (0) and at every draft node; q_rows [T, V]:
@@ -433,7 +440,12 @@ def decide(p_rows, q_rows, tok_local, parent, u, cap, mode=0, nbr=None, relax_k=
     positive part of target - draft, the rejected token leaves the draft distribution, which is
     renormalised).  A chain is the one-child case and is exactly the procedure of Section 2.
     Uniform u[c, 0] decides node c; u[j, 1] draws the final token when the walk ends at node j.
-    Returns (accept_len, path node ids starting with 0, next token id inside the slice)."""
+    Returns (accept_len, path node ids starting with 0, next token id inside the slice).
+    `trace` (a dict, optional) only records how close each decision was to flipping - the distance of
+    every consulted uniform to its threshold, of every budget test to delta, and the CDF of the final
+    draw - for tests that compare against lower-precision arithmetic; it changes nothing."""
+    if trace is not None:
+        trace.update(accept_margin=np.inf, relax_margin=np.inf)
     T = p_rows.shape[0]
     children = [[] for _ in range(T)]
     for j in range(1, T):
@@ -447,9 +459,12 @@ def decide(p_rows, q_rows, tok_local, parent, u, cap, mode=0, nbr=None, relax_k=
             for c in children[cur]:
                 x = int(tok_local[c - 1])
                 if mode == 1 and relax_k > 0:
-                    num, Pt = relaxed_target(P, x, nbr[lo + x] - lo, relax_k, relax_delta)
+                    num, Pt = relaxed_target(P, x, nbr[lo + x] - lo, relax_k, relax_delta, trace)
                 else:
                     num, Pt = P[x], P
+                if trace is not None:
+                    thr = min(1.0, num / Q[x]) if Q[x] > 0 else (1.0 if num > 0 else 0.0)
+                    trace["accept_margin"] = min(trace["accept_margin"], abs(u[c, 0] - thr))
                 if u[c, 0] * Q[x] < num:            # u < min(1, num / Q[x]); 0/0 rejects
                     accepted = c
                     break
@@ -466,4 +481,6 @@ def decide(p_rows, q_rows, tok_local, parent, u, cap, mode=0, nbr=None, relax_k=
             a += 1
             path.append(cur)
             continue
+        if trace is not None:
+            trace.update(term_node=cur, term_u=float(u[cur, 1]), term_cdf=np.cumsum(P) / np.sum(P))
         return a, path, inverse_cdf(P, u[cur, 1])

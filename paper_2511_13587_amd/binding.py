@@ -1,0 +1,235 @@
+"""ctypes binding of libvvs.so: the same entry points as include/vvs.h, taking torch CUDA tensors.
+
+Argument marshalling only - every step of the verify pass runs inside the HIP library.  PyTorch is
+used for device memory and the current stream.  There is no fallback: importing this module on a
+machine where the library has not been built raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libvvs.so")
+
+VVS_OK, VVS_EINVAL, VVS_ESTATE, VVS_ESIZE, VVS_EHIP = 0, -1, -2, -3, -4
+VVS_FP32, VVS_BF16 = 0, 1
+VVS_STRICT, VVS_RELAXED = 0, 1
+VVS_MAX_T = 64
+
+
+class VvsConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_heads", "d_ff", "vocab", "logit_lo", "logit_hi",
+                                         "grid_h", "grid_w", "prefix_len", "prefix_kind", "n_classes", "n_prompts",
+                                         "max_nodes", "dtype")] + \
+               [("cfg_scale", C.c_float), ("rms_eps", C.c_float), ("rope_base", C.c_float),
+                ("relax_k", C.c_int32), ("relax_delta", C.c_float)]
+
+
+class VvsError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"vvs status {status}: {msg}")
+        self.status = status
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it first (python -m paper_2511_13587_amd.build); "
+                          "there is no CPU or PyTorch fallback for the verify pass")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
+    sigs = {
+        "vvs_query_sizes": (i32, [C.POINTER(VvsConfig), C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]),
+        "vvs_create": (i32, [C.POINTER(VvsConfig), vp, vp, vp, C.POINTER(vp)]),
+        "vvs_destroy": (None, [vp]),
+        "vvs_last_error": (C.c_char_p, [vp]),
+        "vvs_num_weight_tensors": (i32, [C.POINTER(VvsConfig)]),
+        "vvs_load_weights": (i32, [vp, C.POINTER(vp), i32, vp]),
+        "vvs_set_neighbors": (i32, [vp, vp]),
+        "vvs_check_tree": (i32, [i32, vp, vp, vp, vp]),
+        "vvs_prefill": (i32, [vp, vp, vp, i32, vp, vp, vp, vp]),
+        "vvs_verify": (i32, [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]),
+        "vvs_accept_from_logits": (i32, [vp, i32, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]),
+        "vvs_kv_commit": (i32, [vp, vp]),
+        "vvs_read_state": (i32, [vp, vp, vp]),
+        "vvs_debug_logits": (i32, [vp, vp, vp, vp, vp]),
+        "vvs_debug_kv": (i32, [vp, i32, i32, i32, vp, vp, vp]),
+        "vvs_debug_gemm_scratch_bytes": (sz, [vp, i32, i32, i32]),
+        "vvs_debug_gemm": (i32, [vp, i32, i32, i32, vp, vp, vp, vp, vp]),
+    }
+    for name, (res, args) in sigs.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    return lib, list(sigs)
+
+
+lib, EXPORTS = _load()
+
+
+def make_config(shape, max_nodes: Optional[int] = None) -> VvsConfig:
+    """vvs_config from a synth.Shape-like object."""
+    return VvsConfig(shape.n_layers, shape.d_model, shape.n_heads, shape.d_ff, shape.vocab, shape.logit_lo,
+                     shape.logit_hi, shape.grid_h, shape.grid_w, shape.prefix_len, shape.prefix_kind,
+                     shape.n_classes, shape.n_prompts, shape.n_nodes if max_nodes is None else max_nodes,
+                     shape.dtype, shape.cfg_scale, shape.rms_eps, shape.rope_base, shape.relax_k, shape.relax_delta)
+
+
+def vvs_query_sizes(cfg: VvsConfig):
+    kv, ws, pw = C.c_size_t(), C.c_size_t(), C.c_size_t()
+    st = lib.vvs_query_sizes(C.byref(cfg), C.byref(kv), C.byref(ws), C.byref(pw))
+    if st != VVS_OK:
+        raise VvsError(st, (lib.vvs_last_error(None) or b"").decode())
+    return kv.value, ws.value, pw.value
+
+
+def vvs_check_tree(n_nodes: int, parent: Optional[np.ndarray], mask: Optional[np.ndarray]):
+    """Host-only topology check; returns (status, depth[T], parent[N])."""
+    depth = np.zeros(max(n_nodes, 0) + 1, dtype=np.int32)
+    pout = np.zeros(max(n_nodes, 1), dtype=np.int32)
+    p = None if parent is None else np.ascontiguousarray(parent, dtype=np.int32)
+    m = None if mask is None else np.ascontiguousarray(mask, dtype=np.uint8)
+    st = lib.vvs_check_tree(n_nodes, None if p is None else p.ctypes.data, None if m is None else m.ctypes.data,
+                            depth.ctypes.data, pout.ctypes.data)
+    return st, depth, pout[:max(n_nodes, 0)]
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device tensors must be contiguous CUDA tensors"
+    return t.data_ptr()
+
+
+def _stream():
+    return torch.cuda.current_stream().cuda_stream
+
+
+def to_device(a: np.ndarray, dtype: int) -> torch.Tensor:
+    """Model-dtype host array (float32 values) -> device tensor (bf16 bits as int16, or float32)."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if dtype == VVS_BF16:
+        u = a.view(np.uint32)
+        bits = ((u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)).astype(np.uint16)
+        return torch.from_numpy(bits.view(np.int16)).cuda()
+    return torch.from_numpy(a).cuda()
+
+
+class Context:
+    """Owns the three device buffers and the vvs_ctx; methods mirror the C entry points."""
+
+    def __init__(self, cfg: VvsConfig, device: str = "cuda:0"):
+        if not torch.cuda.is_available():
+            raise RuntimeError("libvvs needs a HIP device; there is no CPU path")
+        self.cfg = cfg
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.kv_bytes, self.ws_bytes, self.pw_bytes = vvs_query_sizes(cfg)
+        self.kv = torch.empty(self.kv_bytes, dtype=torch.uint8, device=self.device)
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.device)
+        self.pw = torch.empty(self.pw_bytes, dtype=torch.uint8, device=self.device)
+        torch.cuda.synchronize()
+        h = C.c_void_p()
+        st = lib.vvs_create(C.byref(cfg), self.kv.data_ptr(), self.ws.data_ptr(), self.pw.data_ptr(), C.byref(h))
+        if st != VVS_OK:
+            raise VvsError(st, (lib.vvs_last_error(None) or b"").decode())
+        self.h = h
+        self.B = cfg.n_prompts
+        self.R = 2 * cfg.n_prompts
+        self.veff = cfg.logit_hi - cfg.logit_lo
+        self._nbr = None
+        self.last_T = 0
+
+    def close(self):
+        if getattr(self, "h", None):
+            torch.cuda.synchronize()
+            lib.vvs_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st: int):
+        if st != VVS_OK:
+            raise VvsError(st, (lib.vvs_last_error(self.h) or b"").decode())
+
+    # -- weights -------------------------------------------------------------------------------
+    def vvs_load_weights(self, tensors: Sequence[Optional[torch.Tensor]]):
+        arr = (C.c_void_p * len(tensors))(*[_ptr(t) for t in tensors])
+        self._check(lib.vvs_load_weights(self.h, arr, len(tensors), _stream()))
+
+    def load_weights_from_host(self, weights: Dict[str, np.ndarray], names: Sequence[str]):
+        """Uploads float32 host arrays in canonical order (converted to the model dtype) and packs."""
+        dev = [to_device(weights[n], self.cfg.dtype) for n in names]
+        self.vvs_load_weights(dev)
+        torch.cuda.synchronize()
+        del dev
+
+    def vvs_set_neighbors(self, nbr: torch.Tensor):
+        assert nbr.dtype == torch.int32
+        self._nbr = nbr
+        self._check(lib.vvs_set_neighbors(self.h, _ptr(nbr)))
+
+    # -- the three calls of the hot path ---------------------------------------------------------
+    def vvs_prefill(self, prefix_cond: torch.Tensor, prefix_uncond: Optional[torch.Tensor], forced: Optional[torch.Tensor],
+                    uniform: torch.Tensor, first_token: torch.Tensor):
+        n_forced = 0 if forced is None else int(forced.shape[1])
+        self._check(lib.vvs_prefill(self.h, _ptr(prefix_cond), _ptr(prefix_uncond), n_forced, _ptr(forced),
+                                    _ptr(uniform), _ptr(first_token), _stream()))
+        self.last_T = 1
+
+    def vvs_verify(self, n_nodes: int, parent: Optional[np.ndarray], tree_mask: Optional[np.ndarray],
+                   draft_tokens: Optional[torch.Tensor], draft_probs: Optional[torch.Tensor], uniforms: torch.Tensor,
+                   mode: int, accept_len: torch.Tensor, path: torch.Tensor, next_token: torch.Tensor):
+        p = None if parent is None else np.ascontiguousarray(parent, dtype=np.int32)
+        m = None if tree_mask is None else np.ascontiguousarray(tree_mask, dtype=np.uint8)
+        self._check(lib.vvs_verify(self.h, n_nodes, None if p is None else p.ctypes.data,
+                                   None if m is None else m.ctypes.data, _ptr(draft_tokens), _ptr(draft_probs),
+                                   _ptr(uniforms), mode, _ptr(accept_len), _ptr(path), _ptr(next_token), _stream()))
+        self.last_T = n_nodes + 1
+
+    def vvs_accept_from_logits(self, n_nodes: int, parent, tree_mask, raw_logits: torch.Tensor, draft_tokens, draft_probs,
+                               uniforms, mode, accept_len, path, next_token):
+        p = None if parent is None else np.ascontiguousarray(parent, dtype=np.int32)
+        m = None if tree_mask is None else np.ascontiguousarray(tree_mask, dtype=np.uint8)
+        self._check(lib.vvs_accept_from_logits(self.h, n_nodes, None if p is None else p.ctypes.data,
+                                               None if m is None else m.ctypes.data, _ptr(raw_logits), _ptr(draft_tokens),
+                                               _ptr(draft_probs), _ptr(uniforms), mode, _ptr(accept_len), _ptr(path),
+                                               _ptr(next_token), _stream()))
+
+    def vvs_kv_commit(self):
+        self._check(lib.vvs_kv_commit(self.h, _stream()))
+
+    # -- inspection ----------------------------------------------------------------------------
+    def vvs_read_state(self) -> np.ndarray:
+        out = torch.empty((3, self.B), dtype=torch.int32, device=self.device)
+        self._check(lib.vvs_read_state(self.h, _ptr(out), _stream()))
+        return out.cpu().numpy()
+
+    def vvs_debug_logits(self):
+        T = self.last_T
+        raw = torch.empty((self.R, T, self.veff), dtype=torch.float32, device=self.device)
+        mixed = torch.empty((self.B, T, self.veff), dtype=torch.float32, device=self.device)
+        probs = torch.empty((self.B, T, self.veff), dtype=torch.float32, device=self.device)
+        self._check(lib.vvs_debug_logits(self.h, _ptr(raw), _ptr(mixed), _ptr(probs), _stream()))
+        return raw, mixed, probs
+
+    def vvs_debug_kv(self, layer: int, row: int, n_slots: int):
+        d = self.cfg.d_model
+        k = torch.empty((n_slots, d), dtype=torch.float32, device=self.device)
+        v = torch.empty((n_slots, d), dtype=torch.float32, device=self.device)
+        self._check(lib.vvs_debug_kv(self.h, layer, row, n_slots, _ptr(k), _ptr(v), _stream()))
+        return k, v
+
+    def vvs_debug_gemm(self, a: torch.Tensor, w: torch.Tensor, m: int, n: int, k: int) -> torch.Tensor:
+        nbytes = lib.vvs_debug_gemm_scratch_bytes(self.h, m, n, k)
+        scratch = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        out = torch.empty((m, n), dtype=torch.float32, device=self.device)
+        self._check(lib.vvs_debug_gemm(self.h, m, n, k, _ptr(a), _ptr(w), _ptr(scratch), _ptr(out), _stream()))
+        torch.cuda.synchronize()
+        return out

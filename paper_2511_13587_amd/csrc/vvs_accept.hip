@@ -1,0 +1,244 @@
+// Acceptance stage: CFG logit mix, softmax, strict / relaxed accept test with residual resampling,
+// path walk (Section 2, "Speculative Decoding"; tree verification as in Section 3).
+//
+// Every node of the draft tree is evaluated speculatively and in parallel - one workgroup per
+// (prompt, node) computes "which child of this node is accepted, or which token is drawn if none
+// is" - and a one-thread-per-prompt walk then follows the accepted children from the root.  The
+// uniforms are indexed by node, so this equals the sequential procedure.
+#include "vvs_device.h"
+
+#include <limits.h>
+
+namespace vvs {
+
+struct AcceptArgs {
+  const float* logits;        // [R][T][veff]
+  const int32_t* draft;       // [B][N]
+  const float* q;             // [B][T][veff]
+  const float* u;             // uniforms; element (b, j, which) at b*usb + j*usj + {uoa | uot}
+  int usb, usj, uoa, uot;
+  const int32_t* nbr;         // [vocab][relax_k] or nullptr
+  const int32_t* n_emitted;   // [B] or nullptr (no cap, never finished)
+  float* probs;               // [B][T][veff] out: target distributions
+  float* work;                // [B][T][2][veff] scratch: running target P and draft Q
+  int32_t* node_result;       // [B][VVS_MAX_T][2] out: (accepted child or 0, drawn token or -1)
+  int T, veff, lo, mode, relax_k, G;
+  float scale, delta;
+};
+
+// Inverse CDF in ascending id: first id whose running sum exceeds u * total; if rounding runs past
+// the end, the last id with mass.  Each thread owns a contiguous chunk.
+__device__ int inverse_cdf(const float* __restrict__ P, int n, float u, float* red, int* ired, float* scan) {
+  const int nt = blockDim.x, tid = threadIdx.x;
+  const int per = (n + nt - 1) / nt;
+  const int beg = min(tid * per, n), end = min(beg + per, n);
+  float local = 0.f;
+  for (int v = beg; v < end; ++v) local += P[v];
+  // exclusive scan of the per-thread sums: inclusive inside a wave, then wave offsets in order
+  float inc = local;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    float t = __shfl_up(inc, o, 64);
+    if ((tid & 63) >= o) inc += t;
+  }
+  const int w = tid >> 6, nw = nt >> 6;
+  __syncthreads();
+  if ((tid & 63) == 63) scan[w] = inc;
+  __syncthreads();
+  float woff = 0.f, total = 0.f;
+  for (int i = 0; i < nw; ++i) {
+    if (i < w) woff += scan[i];
+    total += scan[i];
+  }
+  const float target = u * total;
+  float run = woff + inc - local;
+  int cand = INT_MAX, last_pos = -1;
+  for (int v = beg; v < end; ++v) {
+    const float pv = P[v];
+    run += pv;
+    if (pv > 0.f) last_pos = v;
+    if (cand == INT_MAX && run > target) cand = v;
+  }
+  int win = block_min_int(cand, ired);
+  if (win == INT_MAX) win = block_max_int(last_pos, ired);
+  (void)red;
+  return win;
+}
+
+__global__ __launch_bounds__(1024) void k_accept_node(AcceptArgs a, TreeDesc tree) {
+  __shared__ float red[16];
+  __shared__ int ired[16];
+  __shared__ float scan[16];
+  __shared__ float nb_mass[64];
+  __shared__ int nb_id[64];
+  __shared__ float sh_num;
+  __shared__ int sh_m;
+  const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, nt = blockDim.x;
+  const int T = a.T, V = a.veff;
+  const float* lc = a.logits + ((size_t)(2 * b) * T + j) * V;
+  const float* lu = a.logits + ((size_t)(2 * b + 1) * T + j) * V;
+  float* P = a.work + ((size_t)(b * T + j) * 2) * V;
+  float* Q = P + V;
+  float* prow = a.probs + (size_t)(b * T + j) * V;
+
+  // CFG mix + softmax (temperature 1) over the allowed slice
+  float mx = -INFINITY;
+  for (int v = tid; v < V; v += nt) {
+    const float m = lu[v] + a.scale * (lc[v] - lu[v]);
+    P[v] = m;
+    mx = fmaxf(mx, m);
+  }
+  mx = block_max(mx, red);
+  float sum = 0.f;
+  for (int v = tid; v < V; v += nt) {
+    const float e = expf(P[v] - mx);
+    P[v] = e;
+    sum += e;
+  }
+  sum = block_sum(sum, red);
+  for (int v = tid; v < V; v += nt) {
+    const float p = P[v] / sum;
+    P[v] = p;
+    prow[v] = p;
+  }
+  __syncthreads();
+
+  int32_t* res = a.node_result + ((size_t)b * VVS_MAX_T + j) * 2;
+  int cap = INT_MAX;
+  if (a.n_emitted) {
+    const int ne = a.n_emitted[b];
+    if (ne >= a.G) {                       // image complete: nothing to accept, nothing to draw
+      if (tid == 0) { res[0] = 0; res[1] = -1; }
+      return;
+    }
+    cap = a.G - ne - 1;
+  }
+
+  int accepted = 0;
+  if (tree.first_child[j] >= 0 && tree.depth[j] < cap) {
+    const float* qrow = a.q + (size_t)(b * T + j) * V;
+    for (int v = tid; v < V; v += nt) Q[v] = qrow[v];
+    __syncthreads();
+    const int N = T - 1;
+    for (int c = tree.first_child[j]; c >= 0; c = tree.next_sibling[c]) {
+      const int x = min(max(a.draft[b * N + c - 1] - a.lo, 0), V - 1);
+      if (a.mode == VVS_RELAXED && a.relax_k > 0) {
+        // absorb neighbour mass in ascending distance while the absorbed total stays <= delta
+        if (tid < 64) {
+          float pm = 0.f;
+          int id = -1;
+          if (tid < a.relax_k) {
+            id = a.nbr[(size_t)(a.lo + x) * a.relax_k + tid] - a.lo;
+            if (id >= 0 && id < V) pm = P[id]; else id = -1;
+          }
+          nb_mass[tid] = pm;
+          nb_id[tid] = id;
+        }
+        __syncthreads();
+        if (tid == 0) {
+          float absorbed = 0.f;
+          int m = 0;
+          for (; m < a.relax_k; ++m) {
+            if (nb_id[m] < 0) continue;
+            if (absorbed + nb_mass[m] > a.delta) break;
+            absorbed += nb_mass[m];
+          }
+          sh_m = m;
+          sh_num = P[x] + absorbed;
+        }
+        __syncthreads();
+        if (tid < sh_m && nb_id[tid] >= 0) P[nb_id[tid]] = 0.f;
+        __syncthreads();
+        if (tid == 0) P[x] = sh_num;
+        __syncthreads();
+      }
+      const float num = P[x], qx = Q[x];
+      const float ua = a.u[(size_t)b * a.usb + (size_t)c * a.usj + a.uoa];
+      if (ua * qx < num) { accepted = c; break; }
+      // rejected: target <- normalised positive part of (target - draft); drop x from the draft
+      float z = 0.f;
+      for (int v = tid; v < V; v += nt) z += fmaxf(0.f, P[v] - Q[v]);
+      z = block_sum(z, red);
+      if (z > 0.f)
+        for (int v = tid; v < V; v += nt) P[v] = fmaxf(0.f, P[v] - Q[v]) / z;
+      __syncthreads();
+      if (tid == 0) Q[x] = 0.f;
+      __syncthreads();
+      float zq = 0.f;
+      for (int v = tid; v < V; v += nt) zq += Q[v];
+      zq = block_sum(zq, red);
+      if (!(zq > 0.f)) break;
+      for (int v = tid; v < V; v += nt) Q[v] = Q[v] / zq;
+      __syncthreads();
+    }
+  }
+  if (accepted) {
+    if (tid == 0) { res[0] = accepted; res[1] = -1; }
+    return;
+  }
+  const float ut = a.u[(size_t)b * a.usb + (size_t)j * a.usj + a.uot];
+  const int tok = inverse_cdf(P, V, ut, red, ired, scan);
+  if (tid == 0) { res[0] = 0; res[1] = a.lo + tok; }
+}
+
+// Follows accepted children from the root.
+__global__ void k_walk(const int32_t* __restrict__ node_result, int B, int32_t* __restrict__ accept_len,
+                       int32_t* __restrict__ path, int32_t* __restrict__ next_token, int32_t* __restrict__ keep) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  int cur = 0, a = 0;
+  int p[VVS_MAX_T];
+  p[0] = 0;
+  while (a < VVS_MAX_T - 1) {
+    const int nxt = node_result[((size_t)b * VVS_MAX_T + cur) * 2];
+    if (nxt <= cur) break;               // 0 = nothing accepted (children always have larger ids)
+    cur = nxt;
+    p[++a] = cur;
+  }
+  const int tok = node_result[((size_t)b * VVS_MAX_T + cur) * 2 + 1];
+  if (accept_len) accept_len[b] = a;
+  if (next_token) next_token[b] = tok;
+  if (keep) { keep[b] = a; keep[B + b] = tok; }
+  for (int i = 0; i < VVS_MAX_T; ++i) {
+    const int v = i <= a ? p[i] : -1;
+    if (path) path[b * VVS_MAX_T + i] = v;
+    if (keep) keep[2 * B + b * VVS_MAX_T + i] = v;
+  }
+}
+
+void launch_accept(Ctx* c, const TreeDesc& tree, int T, const float* d_logits, const int32_t* d_draft_tokens, const float* d_q,
+                   const float* d_u, int usb, int usj, int uoa, int uot, int mode, bool use_state, int32_t* d_accept_len,
+                   int32_t* d_path, int32_t* d_next, bool keep_outcome, hipStream_t s) {
+  AcceptArgs a;
+  a.logits = d_logits; a.draft = d_draft_tokens; a.q = d_q; a.u = d_u;
+  a.usb = usb; a.usj = usj; a.uoa = uoa; a.uot = uot;
+  a.nbr = c->nbr;
+  a.n_emitted = use_state ? (const int32_t*)(c->ws + c->w.state) + c->B : nullptr;
+  a.probs = (float*)(c->ws + c->w.probs);
+  a.work = (float*)(c->ws + c->w.pq_work);
+  a.node_result = (int32_t*)(c->ws + c->w.node_result);
+  a.T = T; a.veff = c->veff; a.lo = c->lo; a.mode = mode; a.relax_k = c->cfg.relax_k; a.G = c->G;
+  a.scale = c->cfg.cfg_scale; a.delta = c->cfg.relax_delta;
+  hipLaunchKernelGGL(k_accept_node, dim3(T, c->B), dim3(1024), 0, s, a, tree);
+  int32_t* keep = keep_outcome ? (int32_t*)(c->ws + c->w.outcome) : nullptr;
+  hipLaunchKernelGGL(k_walk, dim3((c->B + 63) / 64), dim3(64), 0, s, (const int32_t*)a.node_result, c->B, d_accept_len, d_path,
+                     d_next, keep);
+}
+
+__global__ void k_prefill_finish(const int32_t* __restrict__ node_result, int32_t* __restrict__ state, int32_t* __restrict__ first,
+                                 int B, int kv_len, int n_emitted) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  const int tok = node_result[((size_t)b * VVS_MAX_T) * 2 + 1];
+  first[b] = tok;
+  state[b] = kv_len;
+  state[B + b] = n_emitted;
+  state[2 * B + b] = tok;
+}
+
+void launch_prefill_finish(Ctx* c, int n_forced, int32_t* d_first, hipStream_t s) {
+  hipLaunchKernelGGL(k_prefill_finish, dim3((c->B + 63) / 64), dim3(64), 0, s, (const int32_t*)(c->ws + c->w.node_result),
+                     (int32_t*)(c->ws + c->w.state), d_first, c->B, c->P + n_forced, n_forced + 1);
+}
+
+}  // namespace vvs

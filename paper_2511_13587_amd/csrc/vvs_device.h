@@ -1,0 +1,98 @@
+// Device-side helpers shared by the kernel files.
+#pragma once
+#include "vvs_internal.h"
+
+namespace vvs {
+
+__device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+// round to nearest, ties to even (inputs here are finite)
+__device__ __forceinline__ bf16_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ float ld(const float* p) { return *p; }
+__device__ __forceinline__ float ld(const bf16_t* p) { return bf2f(*p); }
+__device__ __forceinline__ void st(float* p, float v) { *p = v; }
+__device__ __forceinline__ void st(bf16_t* p, float v) { *p = f2bf(v); }
+
+// V cache: per (layer,row,head) blocks of 32 slots, inside a block [dim][slot % 32] so that the 32
+// keys of one dim are contiguous (the contraction index of P*V).
+__device__ __forceinline__ size_t v_index(int slot, int dim, int dh) {
+  return ((size_t)(slot >> 5) * dh + dim) * 32 + (slot & 31);
+}
+
+// wave64 reductions, fixed order
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// Block reductions over blockDim.x threads (multiple of 64, <= 1024); red = 16 floats of LDS.
+// Every thread gets the result; deterministic (fixed tree).
+__device__ __forceinline__ float block_sum(float v, float* red) {
+  v = wave_sum(v);
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  float t = 0.f;
+  for (int i = 0; i < nw; ++i) t += red[i];
+  return t;
+}
+__device__ __forceinline__ float block_max(float v, float* red) {
+  v = wave_max(v);
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  float t = red[0];
+  for (int i = 1; i < nw; ++i) t = fmaxf(t, red[i]);
+  return t;
+}
+__device__ __forceinline__ int block_min_int(int v, int* red) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, 64));
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  int t = red[0];
+  for (int i = 1; i < nw; ++i) t = min(t, red[i]);
+  return t;
+}
+__device__ __forceinline__ int block_max_int(int v, int* red) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o, 64));
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  int t = red[0];
+  for (int i = 1; i < nw; ++i) t = max(t, red[i]);
+  return t;
+}
+
+// Position of block token t of row r: cache slot and image-token index (< 0: prefix token).
+__device__ __forceinline__ void token_pos(const PosDesc& pos, const TreeDesc& tree, int r, int t, int* slot, int* img) {
+  if (pos.kv_len) {
+    int b = r >> 1;
+    *slot = pos.kv_len[b] + t;
+    *img = pos.n_emitted[b] - 1 + tree.depth[t];
+  } else {
+    *slot = pos.kv_base + t;
+    *img = *slot - pos.prefix_len;
+  }
+}
+
+// MFMA attention / GEMM launchers (vvs_mfma.hip)
+void mfma_gemm(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, GemmPlan p, hipStream_t s);
+void mfma_attention(Ctx* c, int layer, const TreeDesc& tree, const PosDesc& pos, int T, hipStream_t s);
+
+}  // namespace vvs

@@ -1,0 +1,452 @@
+// Host side of libvvs: argument validation, buffer planning, tree tables and the C ABI entry
+// points.  Everything here runs before any launch, so bad input never reaches a kernel.
+#include "vvs_internal.h"
+
+#include <math.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+#include <algorithm>
+#include <vector>
+
+namespace vvs {
+
+static std::string g_last_error;   // for failures that have no context (query / create)
+
+static vvs_status fail(std::string* err, vvs_status st, const std::string& msg) {
+  if (err) *err = msg;
+  g_last_error = msg;
+  return st;
+}
+
+GemmPlan plan_gemm(const Ctx* c, int M, int N, int K) {
+  GemmPlan p{64, 64, 1};
+  if (c->cfg.dtype != VVS_BF16) return p;           // fp32 path: one wave per output column, no split
+  auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * (N / bn); };
+  const int want = 256;                             // one workgroup per CU at least
+  if (N % 128 == 0 && tiles(128, 128) >= want) return GemmPlan{128, 128, 1};
+  if (N % 128 == 0 && tiles(64, 128) >= want) return GemmPlan{64, 128, 1};
+  p.bm = 64; p.bn = 64;
+  int t = tiles(64, 64);
+  int kt = K / 64;
+  int splits = 1;
+  if (t < want) {
+    splits = std::min({(want + t - 1) / t, 8, std::max(1, kt / 4)});
+    int per = (kt + splits - 1) / splits;
+    splits = (kt + per - 1) / per;
+  }
+  p.splits = splits;
+  return p;
+}
+
+vvs_status plan_sizes(const vvs_config* cfg, Ctx* c, std::string* err) {
+  if (!cfg) return fail(err, VVS_EINVAL, "config is NULL");
+  const vvs_config& g = *cfg;
+  if (g.n_layers < 1 || g.d_model < 4 || g.n_heads < 1 || g.d_ff < 1 || g.vocab < 1 || g.n_prompts < 1 ||
+      g.grid_h < 1 || g.grid_w < 1 || g.prefix_len < 1 || g.max_nodes < 0)
+    return fail(err, VVS_EINVAL, "config: a dimension is not positive");
+  if (g.d_model % g.n_heads) return fail(err, VVS_EINVAL, "config: d_model is not a multiple of n_heads");
+  if (g.logit_lo < 0 || g.logit_hi > g.vocab || g.logit_lo >= g.logit_hi)
+    return fail(err, VVS_EINVAL, "config: logit slice must satisfy 0 <= lo < hi <= vocab");
+  if (g.dtype != VVS_FP32 && g.dtype != VVS_BF16) return fail(err, VVS_EINVAL, "config: unknown dtype");
+  if (g.prefix_kind != VVS_PREFIX_CLASS && g.prefix_kind != VVS_PREFIX_DENSE)
+    return fail(err, VVS_EINVAL, "config: unknown prefix_kind");
+  if (g.prefix_kind == VVS_PREFIX_CLASS && g.n_classes < 1) return fail(err, VVS_EINVAL, "config: n_classes < 1");
+  if (g.max_nodes > VVS_MAX_T - 1) return fail(err, VVS_ESIZE, "config: max_nodes exceeds VVS_MAX_T - 1");
+  if (g.relax_k < 0 || g.relax_k > 64) return fail(err, VVS_ESIZE, "config: relax_k must be in [0, 64]");
+  if (!(g.relax_delta >= 0.f)) return fail(err, VVS_EINVAL, "config: relax_delta < 0");
+  if (!(g.rms_eps > 0.f) || !(g.rope_base > 1.f)) return fail(err, VVS_EINVAL, "config: rms_eps / rope_base");
+  int dh = g.d_model / g.n_heads;
+  if (dh % 4) return fail(err, VVS_ESIZE, "config: head size must be a multiple of 4 (2D rotary pairs)");
+  if (dh > 256) return fail(err, VVS_ESIZE, "config: head size above 256 is not supported");
+  int veff = g.logit_hi - g.logit_lo;
+  if (g.dtype == VVS_BF16) {
+    if (g.d_model % 64 || g.d_ff % 64 || veff % 64)
+      return fail(err, VVS_ESIZE, "config: bf16 needs d_model, d_ff and the logit slice width to be multiples of 64");
+    if (dh != 64 && dh != 128) return fail(err, VVS_ESIZE, "config: bf16 needs head size 64 or 128");
+    if (dh == 128 && g.max_nodes > 31) return fail(err, VVS_ESIZE, "config: bf16 with head size 128 supports max_nodes <= 31");
+  }
+  c->cfg = g;
+  c->B = g.n_prompts; c->R = 2 * g.n_prompts; c->d = g.d_model; c->H = g.n_heads; c->dh = dh; c->F = g.d_ff;
+  c->L = g.n_layers; c->V = g.vocab; c->lo = g.logit_lo; c->veff = veff; c->P = g.prefix_len;
+  c->G = g.grid_h * g.grid_w; c->Tmax = g.max_nodes + 1;
+  c->chunk = (dh > 64) ? 32 : 64;
+  c->Mmax = c->R * std::max(c->Tmax, c->chunk);
+  c->Mlog = c->R * c->Tmax;
+  c->S_cap = (int)align_up((size_t)c->P + c->G + VVS_MAX_T, 32);
+  c->rope_pos = std::max(g.grid_h + VVS_MAX_T / g.grid_w + 2, g.grid_w);
+  c->esz = g.dtype == VVS_BF16 ? 2 : 4;
+  // KV cache: K [L][R][H][S_cap][dh], then V [L][R][H][S_cap/32][dh][32]
+  c->kv_head_stride = (size_t)c->S_cap * dh;
+  c->kv_row_stride = c->kv_head_stride * c->H;
+  c->kv_layer_stride = c->kv_row_stride * c->R;
+  c->kv_v_off = c->kv_layer_stride * c->L;
+  // GEMM partial-sum buffer: worst case over every M this context can be asked for
+  size_t go = 0;
+  int d = c->d, F = c->F;
+  const int shapes[4][2] = {{3 * d, d}, {d, d}, {2 * F, d}, {d, F}};
+  for (int M = 1; M <= c->Mmax; ++M)
+    for (auto& sh : shapes) {
+      GemmPlan p = plan_gemm(c, M, sh[0], sh[1]);
+      go = std::max(go, (size_t)p.splits * M * sh[0]);
+    }
+  c->gemm_out_elems = go;
+  // workspace carve-up
+  Workspace& w = c->w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  w.state = take(sizeof(int32_t) * 3 * c->B);
+  w.outcome = take(sizeof(int32_t) * c->B * (2 + VVS_MAX_T));
+  w.node_result = take(sizeof(int32_t) * c->B * VVS_MAX_T * 2);
+  w.tokens = take(sizeof(int32_t) * c->B * VVS_MAX_T);
+  w.rope_tab = take(sizeof(float) * 2 * c->rope_pos * (dh / 4));
+  w.x = take(sizeof(float) * (size_t)c->Mmax * d);
+  w.h = take(c->esz * (size_t)c->Mmax * d);
+  w.gemm_out = take(sizeof(float) * go);
+  w.q = take(c->esz * (size_t)c->Mmax * d);
+  w.attn = take(c->esz * (size_t)c->Mmax * d);
+  w.act = take(c->esz * (size_t)c->Mmax * F);
+  w.hf = take(c->esz * (size_t)c->Mlog * d);
+  w.logits = take(sizeof(float) * (size_t)c->Mlog * veff);
+  w.probs = take(sizeof(float) * (size_t)c->B * c->Tmax * veff);
+  w.pq_work = take(sizeof(float) * (size_t)c->B * c->Tmax * 2 * veff);
+  w.total = off;
+  // packed weights
+  PackedLayout& p = c->p;
+  off = 0;
+  size_t e = c->esz;
+  p.embed = take(e * (size_t)c->V * d);
+  p.prefix_embed = take(e * (size_t)(g.n_classes + 1) * d);
+  p.gf = take(sizeof(float) * d);
+  p.wout = take(e * (size_t)veff * d);
+  p.layer0 = off;
+  size_t base = off;
+  p.g1 = take(sizeof(float) * d) - base;
+  p.wqkv = take(e * (size_t)3 * d * d) - base;
+  p.wo = take(e * (size_t)d * d) - base;
+  p.g2 = take(sizeof(float) * d) - base;
+  p.wgu = take(e * (size_t)2 * F * d) - base;
+  p.wd = take(e * (size_t)d * F) - base;
+  p.layer_stride = off - base;
+  p.total = p.layer0 + p.layer_stride * c->L;
+  return VVS_OK;
+}
+
+// Validates the topology and fills the kernel-side tables.
+vvs_status build_tree(int n_nodes, const int32_t* h_parent, const uint8_t* h_mask, TreeDesc* t, std::string* err) {
+  if (n_nodes < 0 || n_nodes > VVS_MAX_T - 1) return fail(err, VVS_ESIZE, "tree: n_nodes out of range");
+  const int T = n_nodes + 1;
+  std::vector<int> par(T, -1);
+  if (h_parent) {
+    for (int j = 1; j < T; ++j) {
+      int p = h_parent[j - 1];
+      if (p < 0 || p > j - 1) return fail(err, VVS_EINVAL, "tree: parent of node j must lie in [0, j-1]");
+      par[j] = p;
+    }
+  } else if (h_mask) {
+    // the parent is the closest proper ancestor = the largest index among them
+    for (int j = 1; j < T; ++j) {
+      int p = -1;
+      for (int i = 0; i < j; ++i) if (h_mask[(size_t)j * T + i]) p = i;
+      if (p < 0) return fail(err, VVS_EINVAL, "tree mask: a node does not see the root");
+      par[j] = p;
+    }
+  } else {
+    for (int j = 1; j < T; ++j) par[j] = j - 1;
+  }
+  memset(t, 0, sizeof(*t));
+  t->T = T;
+  bool chain = true;
+  for (int j = 0; j < VVS_MAX_T; ++j) { t->parent[j] = -1; t->first_child[j] = -1; t->next_sibling[j] = -1; }
+  std::vector<int> last_child(T, -1);
+  for (int j = 0; j < T; ++j) {
+    uint64_t m = 1ull << j;
+    if (j) {
+      t->parent[j] = (int8_t)par[j];
+      t->depth[j] = (int8_t)(t->depth[par[j]] + 1);
+      m |= t->anc[par[j]];
+      if (par[j] != j - 1) chain = false;
+      if (last_child[par[j]] < 0) t->first_child[par[j]] = (int8_t)j;
+      else t->next_sibling[last_child[par[j]]] = (int8_t)j;
+      last_child[par[j]] = j;
+    }
+    t->anc[j] = m;
+  }
+  t->causal = chain ? 1 : 0;
+  if (h_mask) {
+    for (int i = 0; i < T; ++i)
+      for (int j = 0; j < T; ++j) {
+        bool want = (t->anc[i] >> j) & 1ull;
+        if ((h_mask[(size_t)i * T + j] != 0) != want)
+          return fail(err, VVS_EINVAL, "tree mask is not the ancestor-or-self closure of the parent array");
+      }
+  }
+  return VVS_OK;
+}
+
+static void causal_tree(int T, TreeDesc* t) {
+  memset(t, 0, sizeof(*t));
+  t->T = T;
+  t->causal = 1;
+  for (int j = 0; j < VVS_MAX_T; ++j) { t->parent[j] = (int8_t)(j - 1); t->first_child[j] = -1; t->next_sibling[j] = -1; }
+  for (int j = 0; j < T && j < VVS_MAX_T; ++j) {
+    t->depth[j] = (int8_t)j;
+    t->anc[j] = (j == 63) ? ~0ull : ((1ull << (j + 1)) - 1);
+  }
+}
+
+static vvs_status hip_fail(Ctx* c, hipError_t e, const char* what) {
+  return fail(&c->err, VVS_EHIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+static vvs_status check_launch(Ctx* c, const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(c, e, what);
+  return VVS_OK;
+}
+
+}  // namespace vvs
+
+using namespace vvs;
+
+extern "C" {
+
+vvs_status vvs_query_sizes(const vvs_config* cfg, size_t* kv_bytes, size_t* workspace_bytes, size_t* packed_weight_bytes) {
+  Ctx c{};
+  vvs_status st = plan_sizes(cfg, &c, nullptr);
+  if (st != VVS_OK) return st;
+  if (kv_bytes) *kv_bytes = 2 * c.kv_v_off * c.esz;
+  if (workspace_bytes) *workspace_bytes = c.w.total;
+  if (packed_weight_bytes) *packed_weight_bytes = c.p.total;
+  return VVS_OK;
+}
+
+int32_t vvs_num_weight_tensors(const vvs_config* cfg) { return cfg ? 4 + 9 * cfg->n_layers : 0; }
+
+vvs_status vvs_check_tree(int32_t n_nodes, const int32_t* h_parent, const uint8_t* h_tree_mask, int32_t* h_depth,
+                          int32_t* h_parent_out) {
+  TreeDesc t;
+  vvs_status st = build_tree(n_nodes, h_parent, h_tree_mask, &t, nullptr);
+  if (st != VVS_OK) return st;
+  for (int j = 0; j <= n_nodes; ++j) {
+    if (h_depth) h_depth[j] = t.depth[j];
+    if (h_parent_out && j) h_parent_out[j - 1] = t.parent[j];
+  }
+  return VVS_OK;
+}
+
+vvs_status vvs_create(const vvs_config* cfg, void* d_kv, void* d_workspace, void* d_packed_weights, vvs_ctx** out) {
+  if (!out) return fail(nullptr, VVS_EINVAL, "create: out is NULL");
+  *out = nullptr;
+  if (!d_kv || !d_workspace || !d_packed_weights) return fail(nullptr, VVS_EINVAL, "create: NULL device buffer");
+  if (((uintptr_t)d_kv | (uintptr_t)d_workspace | (uintptr_t)d_packed_weights) & 255)
+    return fail(nullptr, VVS_EINVAL, "create: device buffers must be 256-byte aligned");
+  Ctx* c = new Ctx{};
+  vvs_status st = plan_sizes(cfg, c, nullptr);
+  if (st != VVS_OK) { delete c; return st; }
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) {
+    delete c;
+    return fail(nullptr, VVS_EHIP, "create: no HIP device (this library has no CPU path)");
+  }
+  c->kv = (char*)d_kv; c->ws = (char*)d_workspace; c->pw = (char*)d_packed_weights;
+  c->nbr = nullptr;
+  // zero the KV cache (padded slots are read, multiplied by zero weights) and the state block
+  launch_fill_zero(c->kv, 2 * c->kv_v_off * c->esz, nullptr);
+  launch_fill_zero(c->ws, c->w.x, nullptr);
+  // rotary table in double -> float: [pos][pair] (cos, sin); theta_i = base^(-2i / (dh/2))
+  int np = c->dh / 4;
+  std::vector<float> tab((size_t)2 * c->rope_pos * np);
+  for (int pos = 0; pos < c->rope_pos; ++pos)
+    for (int i = 0; i < np; ++i) {
+      double th = pow((double)c->cfg.rope_base, -2.0 * i / (c->dh / 2));
+      tab[((size_t)pos * np + i) * 2 + 0] = (float)cos(pos * th);
+      tab[((size_t)pos * np + i) * 2 + 1] = (float)sin(pos * th);
+    }
+  hipError_t e = hipMemcpy(c->ws + c->w.rope_tab, tab.data(), tab.size() * sizeof(float), hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) { std::string m = std::string("create: ") + hipGetErrorString(e); delete c; return fail(nullptr, VVS_EHIP, m); }
+  *out = reinterpret_cast<vvs_ctx*>(c);
+  return VVS_OK;
+}
+
+void vvs_destroy(vvs_ctx* ctx) { delete reinterpret_cast<Ctx*>(ctx); }
+
+const char* vvs_last_error(const vvs_ctx* ctx) {
+  if (!ctx) return g_last_error.c_str();
+  return reinterpret_cast<const Ctx*>(ctx)->err.c_str();
+}
+
+vvs_status vvs_load_weights(vvs_ctx* ctx, const void* const* d_tensors, int32_t n, vvs_stream s) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return VVS_EINVAL;
+  if (!d_tensors) return fail(&c->err, VVS_EINVAL, "load_weights: tensor list is NULL");
+  if (n != vvs_num_weight_tensors(&c->cfg)) return fail(&c->err, VVS_EINVAL, "load_weights: wrong number of tensors");
+  for (int i = 0; i < n; ++i)
+    if (!d_tensors[i] && !(i == 1 && c->cfg.prefix_kind == VVS_PREFIX_DENSE))
+      return fail(&c->err, VVS_EINVAL, "load_weights: a tensor pointer is NULL");
+  launch_pack_weights(c, d_tensors, (hipStream_t)s);
+  vvs_status st = check_launch(c, "load_weights");
+  if (st == VVS_OK) c->weights_loaded = true;
+  return st;
+}
+
+vvs_status vvs_set_neighbors(vvs_ctx* ctx, const int32_t* d_nbr) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return VVS_EINVAL;
+  if (!d_nbr) return fail(&c->err, VVS_EINVAL, "set_neighbors: table is NULL");
+  if (c->cfg.relax_k < 1) return fail(&c->err, VVS_EINVAL, "set_neighbors: context was created with relax_k = 0");
+  c->nbr = d_nbr;
+  return VVS_OK;
+}
+
+vvs_status vvs_prefill(vvs_ctx* ctx, const void* d_prefix_cond, const void* d_prefix_uncond, int32_t n_forced,
+                       const int32_t* d_forced_tokens, const float* d_uniform, int32_t* d_first_token, vvs_stream s) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return VVS_EINVAL;
+  if (!c->weights_loaded) return fail(&c->err, VVS_ESTATE, "prefill: weights not loaded");
+  if (!d_prefix_cond || !d_uniform || !d_first_token) return fail(&c->err, VVS_EINVAL, "prefill: NULL argument");
+  if (c->cfg.prefix_kind == VVS_PREFIX_DENSE && !d_prefix_uncond)
+    return fail(&c->err, VVS_EINVAL, "prefill: dense prefixes need the shared null prefix");
+  if (n_forced < 0 || n_forced > c->G - 1) return fail(&c->err, VVS_EINVAL, "prefill: n_forced must be in [0, G-1]");
+  if (n_forced > 0 && !d_forced_tokens) return fail(&c->err, VVS_EINVAL, "prefill: forced tokens are NULL");
+  hipStream_t st = (hipStream_t)s;
+  const int total = c->P + n_forced;
+  PosDesc pos{nullptr, nullptr, 0, c->P, c->cfg.grid_w};
+  for (int c0 = 0; c0 < total; c0 += c->chunk) {
+    int T = std::min(c->chunk, total - c0);
+    TreeDesc tree;
+    causal_tree(T, &tree);
+    pos.kv_base = c0;
+    bool last = c0 + T >= total;
+    launch_forward(c, tree, pos, T, nullptr, d_prefix_cond, d_prefix_uncond, c0, d_forced_tokens, n_forced, last ? 2 : 0, st);
+    if (last) {
+      TreeDesc one;
+      causal_tree(1, &one);
+      launch_accept(c, one, 1, (const float*)(c->ws + c->w.logits), nullptr, nullptr, d_uniform, 1, 0, 0, 0, VVS_STRICT,
+                    false, nullptr, nullptr, nullptr, false, st);
+      launch_prefill_finish(c, n_forced, d_first_token, st);
+    }
+  }
+  vvs_status rc = check_launch(c, "prefill");
+  if (rc != VVS_OK) return rc;
+  c->prefilled = true;
+  c->verify_pending = false;
+  c->last_T = 1;
+  return VVS_OK;
+}
+
+static vvs_status check_verify_args(Ctx* c, const char* who, int32_t n_nodes, const int32_t* d_draft_tokens,
+                                    const float* d_draft_probs, const float* d_uniforms, int32_t mode,
+                                    int32_t* d_accept_len, int32_t* d_path, int32_t* d_next_token) {
+  std::string w(who);
+  if (n_nodes < 0) return fail(&c->err, VVS_EINVAL, w + ": n_nodes < 0");
+  if (n_nodes > c->cfg.max_nodes) return fail(&c->err, VVS_ESIZE, w + ": n_nodes exceeds max_nodes of the context");
+  if (n_nodes > 0 && (!d_draft_tokens || !d_draft_probs)) return fail(&c->err, VVS_EINVAL, w + ": draft tokens / probs are NULL");
+  if (!d_uniforms || !d_accept_len || !d_path || !d_next_token) return fail(&c->err, VVS_EINVAL, w + ": NULL argument");
+  if (mode != VVS_STRICT && mode != VVS_RELAXED) return fail(&c->err, VVS_EINVAL, w + ": unknown mode");
+  if (mode == VVS_RELAXED && c->cfg.relax_k > 0 && !c->nbr)
+    return fail(&c->err, VVS_ESTATE, w + ": relaxed mode needs vvs_set_neighbors first");
+  return VVS_OK;
+}
+
+vvs_status vvs_verify(vvs_ctx* ctx, int32_t n_nodes, const int32_t* h_parent, const uint8_t* h_tree_mask,
+                      const int32_t* d_draft_tokens, const float* d_draft_probs, const float* d_uniforms, int32_t mode,
+                      int32_t* d_accept_len, int32_t* d_path, int32_t* d_next_token, vvs_stream s) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return VVS_EINVAL;
+  if (!c->prefilled) return fail(&c->err, VVS_ESTATE, "verify: call vvs_prefill first");
+  if (c->verify_pending) return fail(&c->err, VVS_ESTATE, "verify: the previous verify was not committed");
+  vvs_status rc = check_verify_args(c, "verify", n_nodes, d_draft_tokens, d_draft_probs, d_uniforms, mode, d_accept_len,
+                                    d_path, d_next_token);
+  if (rc != VVS_OK) return rc;
+  TreeDesc tree;
+  rc = build_tree(n_nodes, h_parent, h_tree_mask, &tree, &c->err);
+  if (rc != VVS_OK) return rc;
+  hipStream_t st = (hipStream_t)s;
+  const int T = n_nodes + 1;
+  const int32_t* state = (const int32_t*)(c->ws + c->w.state);
+  PosDesc pos{state, state + c->B, 0, c->P, c->cfg.grid_w};
+  launch_build_tokens(c, T, d_draft_tokens, st);
+  launch_forward(c, tree, pos, T, (const int32_t*)(c->ws + c->w.tokens), nullptr, nullptr, 0, nullptr, 0, 1, st);
+  launch_accept(c, tree, T, (const float*)(c->ws + c->w.logits), d_draft_tokens, d_draft_probs, d_uniforms, 2 * T, 2, 0, 1,
+                mode, true, d_accept_len, d_path, d_next_token, true, st);
+  rc = check_launch(c, "verify");
+  if (rc != VVS_OK) return rc;
+  c->verify_pending = true;
+  c->last_T = T;
+  return VVS_OK;
+}
+
+vvs_status vvs_accept_from_logits(vvs_ctx* ctx, int32_t n_nodes, const int32_t* h_parent, const uint8_t* h_tree_mask,
+                                  const float* d_raw_logits, const int32_t* d_draft_tokens, const float* d_draft_probs,
+                                  const float* d_uniforms, int32_t mode, int32_t* d_accept_len, int32_t* d_path,
+                                  int32_t* d_next_token, vvs_stream s) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return VVS_EINVAL;
+  if (!d_raw_logits) return fail(&c->err, VVS_EINVAL, "accept_from_logits: logits are NULL");
+  vvs_status rc = check_verify_args(c, "accept_from_logits", n_nodes, d_draft_tokens, d_draft_probs, d_uniforms, mode,
+                                    d_accept_len, d_path, d_next_token);
+  if (rc != VVS_OK) return rc;
+  TreeDesc tree;
+  rc = build_tree(n_nodes, h_parent, h_tree_mask, &tree, &c->err);
+  if (rc != VVS_OK) return rc;
+  launch_accept(c, tree, n_nodes + 1, d_raw_logits, d_draft_tokens, d_draft_probs, d_uniforms, 2 * (n_nodes + 1), 2, 0, 1,
+                mode, false, d_accept_len, d_path, d_next_token, false, (hipStream_t)s);
+  return check_launch(c, "accept_from_logits");
+}
+
+vvs_status vvs_kv_commit(vvs_ctx* ctx, vvs_stream s) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return VVS_EINVAL;
+  if (!c->verify_pending) return fail(&c->err, VVS_ESTATE, "kv_commit: no verify to commit");
+  launch_commit(c, (hipStream_t)s);
+  vvs_status rc = check_launch(c, "kv_commit");
+  if (rc != VVS_OK) return rc;
+  c->verify_pending = false;
+  return VVS_OK;
+}
+
+vvs_status vvs_read_state(vvs_ctx* ctx, int32_t* d_state, vvs_stream s) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return VVS_EINVAL;
+  if (!d_state) return fail(&c->err, VVS_EINVAL, "read_state: NULL");
+  launch_read_state(c, d_state, (hipStream_t)s);
+  return check_launch(c, "read_state");
+}
+
+vvs_status vvs_debug_logits(vvs_ctx* ctx, float* d_raw, float* d_mixed, float* d_probs, vvs_stream s) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return VVS_EINVAL;
+  if (c->last_T < 1) return fail(&c->err, VVS_ESTATE, "debug_logits: nothing has run yet");
+  launch_debug_logits(c, d_raw, d_mixed, d_probs, (hipStream_t)s);
+  return check_launch(c, "debug_logits");
+}
+
+vvs_status vvs_debug_kv(vvs_ctx* ctx, int32_t layer, int32_t row, int32_t n_slots, float* d_k, float* d_v, vvs_stream s) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return VVS_EINVAL;
+  if (layer < 0 || layer >= c->L || row < 0 || row >= c->R || n_slots < 0 || n_slots > c->S_cap || !d_k || !d_v)
+    return fail(&c->err, VVS_EINVAL, "debug_kv: argument out of range");
+  launch_debug_kv(c, layer, row, n_slots, d_k, d_v, (hipStream_t)s);
+  return check_launch(c, "debug_kv");
+}
+
+size_t vvs_debug_gemm_scratch_bytes(const vvs_ctx* ctx, int32_t m, int32_t n, int32_t k) {
+  const Ctx* c = reinterpret_cast<const Ctx*>(ctx);
+  if (!c || m < 1 || n < 1 || k < 1) return 0;
+  GemmPlan p = plan_gemm(c, m, n, k);
+  return align_up((size_t)n * k * c->esz, 256) + align_up((size_t)p.splits * m * n * sizeof(float), 256);
+}
+
+vvs_status vvs_debug_gemm(vvs_ctx* ctx, int32_t m, int32_t n, int32_t k, const void* d_a, const void* d_w, void* d_scratch,
+                          float* d_c, vvs_stream s) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return VVS_EINVAL;
+  if (m < 1 || n < 1 || k < 1 || !d_a || !d_w || !d_scratch || !d_c) return fail(&c->err, VVS_EINVAL, "debug_gemm: bad argument");
+  if (c->cfg.dtype == VVS_BF16 && (n % 64 || k % 64)) return fail(&c->err, VVS_ESIZE, "debug_gemm: bf16 needs n, k multiples of 64");
+  launch_debug_gemm(c, m, n, k, d_a, d_w, d_scratch, d_c, (hipStream_t)s);
+  return check_launch(c, "debug_gemm");
+}
+
+}  // extern "C"

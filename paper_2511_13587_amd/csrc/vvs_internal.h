@@ -1,0 +1,89 @@
+// Internal declarations shared by the host planner and the HIP kernels of libvvs.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <string>
+#include "vvs.h"
+
+namespace vvs {
+
+typedef uint16_t bf16_t;   // raw bf16 bits
+
+// Tree topology of one verify call, handed to kernels by value (no device allocation, no copy).
+struct TreeDesc {
+  int32_t T;                       // query tokens per row (root + N)
+  int32_t causal;                  // 1: chain / prefill chunk (token i sees tokens 0..i of the block)
+  int8_t parent[VVS_MAX_T];        // parent[0] = -1
+  int8_t depth[VVS_MAX_T];
+  int8_t first_child[VVS_MAX_T];   // -1 = leaf
+  int8_t next_sibling[VVS_MAX_T];  // -1 = last child
+  uint64_t anc[VVS_MAX_T];         // bit j set iff block token j is visible to token i
+};
+
+// How the positions of the T block tokens of row r are found.
+struct PosDesc {
+  const int32_t* kv_len;      // device [B] (verify) or nullptr (prefill: kv_base for every row)
+  const int32_t* n_emitted;   // device [B] (verify) or nullptr
+  int32_t kv_base;            // prefill: first slot of this chunk
+  int32_t prefix_len;
+  int32_t grid_w;
+};
+
+struct GemmPlan { int bm, bn, splits; };
+
+// Byte offsets into the caller's workspace.
+struct Workspace {
+  size_t state, outcome, node_result, tokens, rope_tab, x, h, gemm_out, q, attn, act, hf, logits, probs,
+      pq_work, total;
+};
+
+struct PackedLayout {
+  size_t embed, prefix_embed, gf, wout;
+  size_t layer0, layer_stride;           // per layer block
+  size_t g1, wqkv, wo, g2, wgu, wd;      // offsets inside a layer block
+  size_t total;
+};
+
+struct Ctx {
+  vvs_config cfg;
+  int B, R, d, H, dh, F, L, V, lo, veff, P, G, Tmax, chunk, Mmax, Mlog, S_cap, rope_pos;
+  size_t esz;                            // bytes per model element
+  char* kv; char* ws; char* pw;
+  size_t kv_layer_stride, kv_row_stride, kv_head_stride, kv_v_off;  // in elements; V half starts at kv_v_off
+  Workspace w;
+  PackedLayout p;
+  size_t gemm_out_elems;
+  const int32_t* nbr;
+  bool weights_loaded, prefilled, verify_pending;
+  int last_T;                            // T of the last verify / prefill (for debug export)
+  std::string err;
+};
+
+// ---- host planner (vvs_host.cpp)
+vvs_status plan_sizes(const vvs_config* cfg, Ctx* c, std::string* err);
+GemmPlan plan_gemm(const Ctx* c, int M, int N, int K);
+vvs_status build_tree(int n_nodes, const int32_t* h_parent, const uint8_t* h_mask, TreeDesc* out, std::string* err);
+
+// ---- launchers (kernels_*.hip); all asynchronous on the stream
+void launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+void launch_pack_weights(Ctx* c, const void* const* tensors, hipStream_t s);
+void launch_forward(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int T, const int32_t* d_tokens_bt,
+                    const void* d_prefix_cond, const void* d_prefix_uncond, int chunk_start,
+                    const int32_t* d_forced, int n_forced, int logits_mode /*0 none, 1 every token, 2 last token of each row*/,
+                    hipStream_t s);
+void launch_build_tokens(Ctx* c, int T, const int32_t* d_draft, hipStream_t s);
+void launch_accept(Ctx* c, const TreeDesc& tree, int T, const float* d_logits, const int32_t* d_draft_tokens,
+                   const float* d_q, const float* d_u, int u_stride_b, int u_stride_j, int u_off_acc, int u_off_term,
+                   int mode, bool use_state, int32_t* d_accept_len, int32_t* d_path, int32_t* d_next,
+                   bool keep_outcome, hipStream_t s);
+void launch_prefill_finish(Ctx* c, int n_forced, int32_t* d_first, hipStream_t s);
+void launch_commit(Ctx* c, hipStream_t s);
+void launch_read_state(Ctx* c, int32_t* d_state, hipStream_t s);
+void launch_debug_logits(Ctx* c, float* raw, float* mixed, float* probs, hipStream_t s);
+void launch_debug_kv(Ctx* c, int layer, int row, int n_slots, float* dk, float* dv, hipStream_t s);
+void launch_debug_gemm(Ctx* c, int m, int n, int k, const void* a, const void* w, void* scratch, float* out, hipStream_t s);
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace vvs

@@ -1,0 +1,501 @@
+// Element-wise / reduction kernels of the verify pass, the fp32 (reference-shape) GEMM and attention
+// kernels, weight repacking, KV commit, and the launch sequence of one transformer forward.
+// The bf16 GEMM and attention kernels (MFMA) live in vvs_mfma.hip; the acceptance stage in
+// vvs_accept.hip.
+#include "vvs_device.h"
+
+#include <stdlib.h>
+#include <algorithm>
+
+namespace vvs {
+
+// ------------------------------------------------------------------------------------------------ utilities
+__global__ void k_fill_zero(uint4* p, size_t n16) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  const uint4 z = make_uint4(0, 0, 0, 0);
+  for (; i < n16; i += stride) p[i] = z;
+}
+
+void launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
+  size_t n16 = bytes / 16;
+  if (!n16) return;
+  int blocks = (int)std::min<size_t>((n16 + 255) / 256, 256 * 32);
+  hipLaunchKernelGGL(k_fill_zero, dim3(blocks), dim3(256), 0, s, (uint4*)p, n16);
+}
+
+// out[n][k] = in[k][col0 + n]   (in: [K][ld])
+template <typename T>
+__global__ void k_transpose(const T* __restrict__ in, T* __restrict__ out, int K, int N, int ld, int col0) {
+  __shared__ T tile[32][33];
+  const int n0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
+  for (int i = threadIdx.y; i < 32; i += 8) {
+    int k = k0 + i, n = n0 + threadIdx.x;
+    if (k < K && n < N) tile[i][threadIdx.x] = in[(size_t)k * ld + col0 + n];
+  }
+  __syncthreads();
+  for (int i = threadIdx.y; i < 32; i += 8) {
+    int n = n0 + i, k = k0 + threadIdx.x;
+    if (k < K && n < N) out[(size_t)n * K + k] = tile[threadIdx.x][i];
+  }
+}
+
+template <typename T>
+static void transpose_into(const void* in, void* out, int K, int N, int ld, int col0, hipStream_t s) {
+  dim3 grid((N + 31) / 32, (K + 31) / 32);
+  hipLaunchKernelGGL(k_transpose<T>, grid, dim3(32, 8), 0, s, (const T*)in, (T*)out, K, N, ld, col0);
+}
+
+template <typename T>
+__global__ void k_copy(const T* __restrict__ in, T* __restrict__ out, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (; i < n; i += (size_t)gridDim.x * blockDim.x) out[i] = in[i];
+}
+template <typename T>
+__global__ void k_to_float(const T* __restrict__ in, float* __restrict__ out, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (; i < n; i += (size_t)gridDim.x * blockDim.x) out[i] = ld(in + i);
+}
+
+template <typename T>
+static void pack_weights_t(Ctx* c, const void* const* t, hipStream_t s) {
+  const int d = c->d, F = c->F;
+  auto copy = [&](const void* in, size_t off, size_t n) {
+    int blocks = (int)std::min<size_t>((n + 255) / 256, 8192);
+    hipLaunchKernelGGL(k_copy<T>, dim3(blocks), dim3(256), 0, s, (const T*)in, (T*)(c->pw + off), n);
+  };
+  auto gain = [&](const void* in, size_t off) {
+    hipLaunchKernelGGL(k_to_float<T>, dim3((d + 255) / 256), dim3(256), 0, s, (const T*)in, (float*)(c->pw + off), (size_t)d);
+  };
+  copy(t[0], c->p.embed, (size_t)c->V * d);
+  if (t[1]) copy(t[1], c->p.prefix_embed, (size_t)(c->cfg.n_classes + 1) * d);
+  for (int l = 0; l < c->L; ++l) {
+    const void* const* w = t + 2 + 9 * l;
+    size_t base = c->p.layer0 + c->p.layer_stride * l;
+    gain(w[0], base + c->p.g1);
+    char* qkv = c->pw + base + c->p.wqkv;
+    for (int i = 0; i < 3; ++i) transpose_into<T>(w[1 + i], qkv + (size_t)i * d * d * sizeof(T), d, d, d, 0, s);
+    transpose_into<T>(w[4], c->pw + base + c->p.wo, d, d, d, 0, s);
+    gain(w[5], base + c->p.g2);
+    char* gu = c->pw + base + c->p.wgu;
+    transpose_into<T>(w[6], gu, d, F, F, 0, s);
+    transpose_into<T>(w[7], gu + (size_t)F * d * sizeof(T), d, F, F, 0, s);
+    transpose_into<T>(w[8], c->pw + base + c->p.wd, F, d, d, 0, s);
+  }
+  const void* const* tail = t + 2 + 9 * c->L;
+  gain(tail[0], c->p.gf);
+  transpose_into<T>(tail[1], c->pw + c->p.wout, d, c->veff, c->V, c->lo, s);
+}
+
+void launch_pack_weights(Ctx* c, const void* const* tensors, hipStream_t s) {
+  if (c->cfg.dtype == VVS_BF16) pack_weights_t<bf16_t>(c, tensors, s);
+  else pack_weights_t<float>(c, tensors, s);
+}
+
+// ------------------------------------------------------------------------------------------------ embedding
+struct EmbedArgs {
+  int T, d, V, mode;                 // mode 0: verify (token table), 1: prefill chunk
+  const int32_t* tokens_bt;          // [B][T]
+  const void* pc; const void* pu;    // prefix inputs
+  int prefix_kind, n_classes, P, chunk_start, n_forced;
+  const int32_t* forced;
+};
+
+template <typename T>
+__global__ void k_embed(float* __restrict__ x, const T* __restrict__ embed, const T* __restrict__ prefix_tab, EmbedArgs a) {
+  const int m = blockIdx.x, r = m / a.T, t = m % a.T, b = r >> 1;
+  const T* src;
+  if (a.mode == 0) {
+    int tok = min(max(a.tokens_bt[b * a.T + t], 0), a.V - 1);
+    src = embed + (size_t)tok * a.d;
+  } else {
+    int slot = a.chunk_start + t;
+    if (slot < a.P) {
+      if (a.prefix_kind == VVS_PREFIX_CLASS) {
+        int id;
+        if (r & 1) id = a.pu ? ((const int32_t*)a.pu)[b * a.P + slot] : a.n_classes;
+        else id = ((const int32_t*)a.pc)[b * a.P + slot];
+        id = min(max(id, 0), a.n_classes);
+        src = prefix_tab + (size_t)id * a.d;
+      } else {
+        src = (r & 1) ? (const T*)a.pu + (size_t)slot * a.d : (const T*)a.pc + ((size_t)b * a.P + slot) * a.d;
+      }
+    } else {
+      int tok = min(max(a.forced[b * a.n_forced + slot - a.P], 0), a.V - 1);
+      src = embed + (size_t)tok * a.d;
+    }
+  }
+  for (int i = threadIdx.x; i < a.d; i += blockDim.x) x[(size_t)m * a.d + i] = ld(src + i);
+}
+
+__global__ void k_build_tokens(int32_t* __restrict__ tokens, const int32_t* __restrict__ pending, const int32_t* __restrict__ draft,
+                               int B, int T) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B * T) return;
+  int b = i / T, j = i % T;
+  tokens[i] = j == 0 ? pending[b] : draft[b * (T - 1) + j - 1];
+}
+
+void launch_build_tokens(Ctx* c, int T, const int32_t* d_draft, hipStream_t s) {
+  int n = c->B * T;
+  const int32_t* pending = (const int32_t*)(c->ws + c->w.state) + 2 * c->B;
+  hipLaunchKernelGGL(k_build_tokens, dim3((n + 255) / 256), dim3(256), 0, s, (int32_t*)(c->ws + c->w.tokens), pending, d_draft,
+                     c->B, T);
+}
+
+// ------------------------------------------------------------------------------------------------ residual add + RMSNorm
+// Output row i reads x row (i * in_stride + in_off): x_row += sum of GEMM partials (if any), then
+// h_row = x_row / sqrt(mean(x_row^2) + eps) * g, rounded to the operand type.
+template <typename T>
+__global__ void k_add_rmsnorm(float* __restrict__ x, const float* __restrict__ partial, int splits, size_t split_stride, int d,
+                              const float* __restrict__ g, float eps, T* __restrict__ h, int in_stride, int in_off) {
+  __shared__ float red[16];
+  const size_t row = (size_t)blockIdx.x * in_stride + in_off;
+  float* xr = x + row * d;
+  float ss = 0.f;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) {
+    float v = xr[k];
+    if (splits) {
+      for (int s = 0; s < splits; ++s) v += partial[s * split_stride + row * d + k];
+      xr[k] = v;
+    }
+    ss += v * v;
+  }
+  ss = block_sum(ss, red);
+  const float scale = 1.0f / sqrtf(ss / (float)d + eps);
+  T* hr = h + (size_t)blockIdx.x * d;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) st(hr + k, xr[k] * scale * g[k]);
+}
+
+// ------------------------------------------------------------------------------------------------ RoPE + KV write
+template <typename T>
+__global__ void k_rope_kv(const float* __restrict__ qkv, int splits, size_t split_stride, T* __restrict__ q, T* __restrict__ kc,
+                          T* __restrict__ vc, const float* __restrict__ rope_tab, TreeDesc tree, PosDesc pos, int T_, int d,
+                          int dh, size_t row_stride, size_t head_stride, int S_cap, int rope_pos) {
+  const int m = blockIdx.x, r = m / T_, t = m % T_;
+  int slot, img;
+  token_pos(pos, tree, r, t, &slot, &img);
+  const int half = dh >> 1, np = dh >> 2;
+  int gr = 0, gc = 0;
+  if (img >= 0) { gr = min(img / pos.grid_w, rope_pos - 1); gc = img % pos.grid_w; }
+  const bool in_cache = slot >= 0 && slot < S_cap;
+  const size_t n3 = (size_t)3 * d;
+  for (int i = threadIdx.x; i < (d >> 1); i += blockDim.x) {
+    const int e0 = 2 * i, hd = e0 / dh, e = e0 % dh;
+    const int seg = e / half, ip = (e % half) >> 1;
+    float cs = 1.f, sn = 0.f;
+    if (img >= 0) {
+      const int pv = seg ? gc : gr;
+      cs = rope_tab[((size_t)pv * np + ip) * 2];
+      sn = rope_tab[((size_t)pv * np + ip) * 2 + 1];
+    }
+    float v[6] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < splits; ++s) {
+      const float* row = qkv + s * split_stride + (size_t)m * n3;
+      v[0] += row[e0]; v[1] += row[e0 + 1];
+      v[2] += row[d + e0]; v[3] += row[d + e0 + 1];
+      v[4] += row[2 * d + e0]; v[5] += row[2 * d + e0 + 1];
+    }
+    st(q + (size_t)m * d + e0, v[0] * cs - v[1] * sn);
+    st(q + (size_t)m * d + e0 + 1, v[0] * sn + v[1] * cs);
+    if (in_cache) {
+      const size_t hb = (size_t)r * row_stride + (size_t)hd * head_stride;
+      st(kc + hb + (size_t)slot * dh + e, v[2] * cs - v[3] * sn);
+      st(kc + hb + (size_t)slot * dh + e + 1, v[2] * sn + v[3] * cs);
+      st(vc + hb + v_index(slot, e, dh), v[4]);
+      st(vc + hb + v_index(slot, e + 1, dh), v[5]);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ attention, one query per workgroup
+template <typename T>
+__global__ void k_attn_simple(const T* __restrict__ q, const T* __restrict__ kc, const T* __restrict__ vc, T* __restrict__ out,
+                              TreeDesc tree, PosDesc pos, int T_, int d, int dh, size_t row_stride, size_t head_stride, int S_cap) {
+  extern __shared__ float sc[];          // [S_cap] scores, then 16 floats for reductions
+  float* red = sc + S_cap;
+  const int t = blockIdx.x, hd = blockIdx.y, r = blockIdx.z, m = r * T_ + t;
+  const int S = pos.kv_len ? pos.kv_len[r >> 1] : pos.kv_base;
+  const int n = min(S + T_, S_cap);
+  const uint64_t mask = tree.anc[t];
+  const T* qv = q + (size_t)m * d + (size_t)hd * dh;
+  const T* kb = kc + (size_t)r * row_stride + (size_t)hd * head_stride;
+  const T* vb = vc + (size_t)r * row_stride + (size_t)hd * head_stride;
+  const float scale = 1.0f / sqrtf((float)dh);
+  float mx = -INFINITY;
+  for (int k = threadIdx.x; k < n; k += blockDim.x) {
+    bool vis = k < S || ((mask >> (k - S)) & 1ull);
+    float sv = -INFINITY;
+    if (vis) {
+      float dot = 0.f;
+      for (int e = 0; e < dh; ++e) dot += ld(qv + e) * ld(kb + (size_t)k * dh + e);
+      sv = dot * scale;
+    }
+    sc[k] = sv;
+    mx = fmaxf(mx, sv);
+  }
+  mx = block_max(mx, red);
+  float sum = 0.f;
+  for (int k = threadIdx.x; k < n; k += blockDim.x) {
+    float e = sc[k] == -INFINITY ? 0.f : expf(sc[k] - mx);
+    sc[k] = e;
+    sum += e;
+  }
+  sum = block_sum(sum, red);
+  for (int e = threadIdx.x; e < dh; e += blockDim.x) {
+    float o = 0.f;
+    for (int k = 0; k < n; ++k) o += sc[k] * ld(vb + v_index(k, e, dh));
+    st(out + (size_t)m * d + (size_t)hd * dh + e, o / sum);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------ SwiGLU
+template <typename T>
+__global__ void k_swiglu(const float* __restrict__ gu, int splits, size_t split_stride, T* __restrict__ act, int M, int F) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)M * F) return;
+  const size_t m = i / F, f = i % F;
+  float g = 0.f, u = 0.f;
+  for (int s = 0; s < splits; ++s) {
+    const float* row = gu + s * split_stride + m * 2 * F;
+    g += row[f];
+    u += row[F + f];
+  }
+  st(act + i, g / (1.0f + expf(-g)) * u);
+}
+
+// ------------------------------------------------------------------------------------------------ GEMM, one wave per output column
+// C[m][n] = sum_k A[m][k] * W[n][k]; lanes stride over k (coalesced), 8 rows of A per pass.
+template <typename T>
+__global__ void k_gemm_simple(const T* __restrict__ A, const T* __restrict__ W, float* __restrict__ C, int M, int N, int K) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = blockIdx.x * 4 + wave, m0 = blockIdx.y * 8;
+  if (n >= N) return;
+  float acc[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+  for (int k = lane; k < K; k += 64) {
+    const float w = ld(W + (size_t)n * K + k);
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      if (m0 + i < M) acc[i] += ld(A + (size_t)(m0 + i) * K + k) * w;
+  }
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    float v = wave_sum(acc[i]);
+    if (lane == 0 && m0 + i < M) C[(size_t)(m0 + i) * N + n] = v;
+  }
+}
+
+static bool force_simple() {
+  static int v = -1;
+  if (v < 0) { const char* e = getenv("VVS_FORCE_SIMPLE"); v = (e && e[0] == '1') ? 1 : 0; }
+  return v == 1;
+}
+
+// C[splits][M][N] (fp32 partial sums) = A[M][K] * W[N][K]^T
+static int run_gemm(Ctx* c, const void* A, const void* W, float* C, int M, int N, int K, bool allow_split, hipStream_t s) {
+  GemmPlan p = plan_gemm(c, M, N, K);
+  if (!allow_split) p.splits = 1;
+  if (c->cfg.dtype == VVS_BF16 && !force_simple()) {
+    mfma_gemm((const bf16_t*)A, (const bf16_t*)W, C, M, N, K, p, s);
+    return p.splits;
+  }
+  dim3 grid((N + 3) / 4, (M + 7) / 8);
+  if (c->cfg.dtype == VVS_BF16)
+    hipLaunchKernelGGL(k_gemm_simple<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)A, (const bf16_t*)W, C, M, N, K);
+  else
+    hipLaunchKernelGGL(k_gemm_simple<float>, grid, dim3(256), 0, s, (const float*)A, (const float*)W, C, M, N, K);
+  return 1;
+}
+
+// ------------------------------------------------------------------------------------------------ one forward over T tokens per row
+template <typename T>
+static void forward_t(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, const int32_t* d_tokens_bt, const void* pc,
+                      const void* pu, int chunk_start, const int32_t* forced, int n_forced, int logits_mode, hipStream_t s) {
+  const int d = c->d, F = c->F, M = c->R * Tq;
+  float* x = (float*)(c->ws + c->w.x);
+  T* h = (T*)(c->ws + c->w.h);
+  float* go = (float*)(c->ws + c->w.gemm_out);
+  T* q = (T*)(c->ws + c->w.q);
+  T* attn = (T*)(c->ws + c->w.attn);
+  T* act = (T*)(c->ws + c->w.act);
+  const float* rope = (const float*)(c->ws + c->w.rope_tab);
+  EmbedArgs ea{Tq, d, c->V, d_tokens_bt ? 0 : 1, d_tokens_bt, pc, pu, c->cfg.prefix_kind, c->cfg.n_classes, c->P, chunk_start,
+               n_forced, forced};
+  hipLaunchKernelGGL(k_embed<T>, dim3(M), dim3(256), 0, s, x, (const T*)(c->pw + c->p.embed),
+                     (const T*)(c->pw + c->p.prefix_embed), ea);
+  int splits = 0;   // partial sums waiting to be added to x
+  size_t sstride = 0;
+  for (int l = 0; l < c->L; ++l) {
+    const char* lw = c->pw + c->p.layer0 + c->p.layer_stride * l;
+    T* kc = (T*)c->kv + c->kv_layer_stride * l;
+    T* vc = (T*)c->kv + c->kv_v_off + c->kv_layer_stride * l;
+    hipLaunchKernelGGL(k_add_rmsnorm<T>, dim3(M), dim3(256), 0, s, x, go, splits, sstride, d, (const float*)(lw + c->p.g1),
+                       c->cfg.rms_eps, h, 1, 0);
+    int sp = run_gemm(c, h, lw + c->p.wqkv, go, M, 3 * d, d, true, s);
+    hipLaunchKernelGGL(k_rope_kv<T>, dim3(M), dim3(256), 0, s, go, sp, (size_t)M * 3 * d, q, kc, vc, rope, tree, pos, Tq, d, c->dh,
+                       c->kv_row_stride, c->kv_head_stride, c->S_cap, c->rope_pos);
+    if (c->cfg.dtype == VVS_BF16 && !force_simple()) {
+      mfma_attention(c, l, tree, pos, Tq, s);
+    } else {
+      size_t lds = sizeof(float) * (c->S_cap + 16);
+      hipLaunchKernelGGL(k_attn_simple<T>, dim3(Tq, c->H, c->R), dim3(256), lds, s, q, kc, vc, attn, tree, pos, Tq, d, c->dh,
+                         c->kv_row_stride, c->kv_head_stride, c->S_cap);
+    }
+    sp = run_gemm(c, attn, lw + c->p.wo, go, M, d, d, true, s);
+    hipLaunchKernelGGL(k_add_rmsnorm<T>, dim3(M), dim3(256), 0, s, x, go, sp, (size_t)M * d, d, (const float*)(lw + c->p.g2),
+                       c->cfg.rms_eps, h, 1, 0);
+    sp = run_gemm(c, h, lw + c->p.wgu, go, M, 2 * F, d, true, s);
+    {
+      size_t n = (size_t)M * F;
+      hipLaunchKernelGGL(k_swiglu<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, go, sp, (size_t)M * 2 * F, act, M, F);
+    }
+    splits = run_gemm(c, act, lw + c->p.wd, go, M, d, F, true, s);
+    sstride = (size_t)M * d;
+  }
+  if (logits_mode == 0) return;
+  T* hf = (T*)(c->ws + c->w.hf);
+  float* logits = (float*)(c->ws + c->w.logits);
+  const float* gf = (const float*)(c->pw + c->p.gf);
+  int Ml;
+  if (logits_mode == 1) {     // every token
+    Ml = M;
+    hipLaunchKernelGGL(k_add_rmsnorm<T>, dim3(Ml), dim3(256), 0, s, x, go, splits, sstride, d, gf, c->cfg.rms_eps, hf, 1, 0);
+  } else {                    // last token of every row
+    Ml = c->R;
+    hipLaunchKernelGGL(k_add_rmsnorm<T>, dim3(Ml), dim3(256), 0, s, x, go, splits, sstride, d, gf, c->cfg.rms_eps, hf, Tq, Tq - 1);
+  }
+  run_gemm(c, hf, c->pw + c->p.wout, logits, Ml, c->veff, d, false, s);
+}
+
+void launch_forward(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int T, const int32_t* d_tokens_bt, const void* pc,
+                    const void* pu, int chunk_start, const int32_t* forced, int n_forced, int logits_mode, hipStream_t s) {
+  if (c->cfg.dtype == VVS_BF16) forward_t<bf16_t>(c, tree, pos, T, d_tokens_bt, pc, pu, chunk_start, forced, n_forced, logits_mode, s);
+  else forward_t<float>(c, tree, pos, T, d_tokens_bt, pc, pu, chunk_start, forced, n_forced, logits_mode, s);
+}
+
+// ------------------------------------------------------------------------------------------------ KV commit
+// One thread owns one (head, dim) column and walks the accepted path in order: slot S + path[i]
+// moves to slot S + i.  path is strictly increasing with path[i] >= i, so a destination is never a
+// source that is still needed.
+template <typename T>
+__global__ void k_commit_kv(T* __restrict__ kcache, T* __restrict__ vcache, const int32_t* __restrict__ kv_len,
+                            const int32_t* __restrict__ accept_len, const int32_t* __restrict__ next_token,
+                            const int32_t* __restrict__ path, int H, int dh, size_t layer_stride, size_t row_stride,
+                            size_t head_stride, int S_cap) {
+  const int r = blockIdx.x, l = blockIdx.y, b = r >> 1;
+  if (next_token[b] < 0) return;
+  const int S = kv_len[b], a = accept_len[b];
+  T* kb = kcache + l * layer_stride + r * row_stride;
+  T* vb = vcache + l * layer_stride + r * row_stride;
+  for (int col = threadIdx.x; col < H * dh; col += blockDim.x) {
+    const int hd = col / dh, e = col % dh;
+    T* kh = kb + hd * head_stride;
+    T* vh = vb + hd * head_stride;
+    for (int i = 1; i <= a; ++i) {
+      const int src = S + path[b * VVS_MAX_T + i], dst = S + i;
+      if (src == dst || src >= S_cap) continue;
+      kh[(size_t)dst * dh + e] = kh[(size_t)src * dh + e];
+      vh[v_index(dst, e, dh)] = vh[v_index(src, e, dh)];
+    }
+  }
+}
+
+__global__ void k_commit_state(int32_t* __restrict__ state, const int32_t* __restrict__ accept_len,
+                               const int32_t* __restrict__ next_token, int B) {
+  int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B || next_token[b] < 0) return;
+  state[b] += accept_len[b] + 1;           // cached length
+  state[B + b] += accept_len[b] + 1;       // emitted image tokens
+  state[2 * B + b] = next_token[b];        // pending token
+}
+
+void launch_commit(Ctx* c, hipStream_t s) {
+  int32_t* state = (int32_t*)(c->ws + c->w.state);
+  const int32_t* oc = (const int32_t*)(c->ws + c->w.outcome);
+  const int32_t* accept_len = oc;
+  const int32_t* next_token = oc + c->B;
+  const int32_t* path = oc + 2 * c->B;
+  dim3 grid(c->R, c->L);
+  if (c->cfg.dtype == VVS_BF16)
+    hipLaunchKernelGGL(k_commit_kv<bf16_t>, grid, dim3(256), 0, s, (bf16_t*)c->kv, (bf16_t*)c->kv + c->kv_v_off, state, accept_len,
+                       next_token, path, c->H, c->dh, c->kv_layer_stride, c->kv_row_stride, c->kv_head_stride, c->S_cap);
+  else
+    hipLaunchKernelGGL(k_commit_kv<float>, grid, dim3(256), 0, s, (float*)c->kv, (float*)c->kv + c->kv_v_off, state, accept_len,
+                       next_token, path, c->H, c->dh, c->kv_layer_stride, c->kv_row_stride, c->kv_head_stride, c->S_cap);
+  hipLaunchKernelGGL(k_commit_state, dim3((c->B + 63) / 64), dim3(64), 0, s, state, accept_len, next_token, c->B);
+}
+
+__global__ void k_read_state(const int32_t* __restrict__ state, int32_t* __restrict__ out, int n) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = state[i];
+}
+
+void launch_read_state(Ctx* c, int32_t* d_state, hipStream_t s) {
+  int n = 3 * c->B;
+  hipLaunchKernelGGL(k_read_state, dim3((n + 255) / 256), dim3(256), 0, s, (const int32_t*)(c->ws + c->w.state), d_state, n);
+}
+
+// ------------------------------------------------------------------------------------------------ inspection
+__global__ void k_debug_logits(const float* __restrict__ logits, const float* __restrict__ probs_ws, float* __restrict__ raw,
+                               float* __restrict__ mixed, float* __restrict__ probs, int B, int T, int veff, float scale) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t per = (size_t)T * veff, n = (size_t)B * per;
+  if (i >= n) return;
+  const size_t b = i / per, rem = i % per;
+  const float lc = logits[(2 * b) * per + rem], lu = logits[(2 * b + 1) * per + rem];
+  if (raw) { raw[(2 * b) * per + rem] = lc; raw[(2 * b + 1) * per + rem] = lu; }
+  if (mixed) mixed[i] = lu + scale * (lc - lu);
+  if (probs) probs[i] = probs_ws[i];
+}
+
+void launch_debug_logits(Ctx* c, float* raw, float* mixed, float* probs, hipStream_t s) {
+  size_t n = (size_t)c->B * c->last_T * c->veff;
+  hipLaunchKernelGGL(k_debug_logits, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const float*)(c->ws + c->w.logits),
+                     (const float*)(c->ws + c->w.probs), raw, mixed, probs, c->B, c->last_T, c->veff, c->cfg.cfg_scale);
+}
+
+template <typename T>
+__global__ void k_debug_kv(const T* __restrict__ kh, const T* __restrict__ vh, float* __restrict__ dk, float* __restrict__ dv, int n_slots,
+                           int H, int dh, size_t head_stride) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t d = (size_t)H * dh;
+  if (i >= (size_t)n_slots * d) return;
+  const int slot = (int)(i / d), col = (int)(i % d), hd = col / dh, e = col % dh;
+  dk[i] = ld(kh + hd * head_stride + (size_t)slot * dh + e);
+  dv[i] = ld(vh + hd * head_stride + v_index(slot, e, dh));
+}
+
+void launch_debug_kv(Ctx* c, int layer, int row, int n_slots, float* dk, float* dv, hipStream_t s) {
+  size_t n = (size_t)n_slots * c->d;
+  if (!n) return;
+  size_t off = c->kv_layer_stride * layer + c->kv_row_stride * row;
+  unsigned blocks = (unsigned)((n + 255) / 256);
+  if (c->cfg.dtype == VVS_BF16)
+    hipLaunchKernelGGL(k_debug_kv<bf16_t>, dim3(blocks), dim3(256), 0, s, (const bf16_t*)c->kv + off,
+                       (const bf16_t*)c->kv + c->kv_v_off + off, dk, dv, n_slots, c->H, c->dh, c->kv_head_stride);
+  else
+    hipLaunchKernelGGL(k_debug_kv<float>, dim3(blocks), dim3(256), 0, s, (const float*)c->kv + off,
+                       (const float*)c->kv + c->kv_v_off + off, dk, dv, n_slots, c->H, c->dh, c->kv_head_stride);
+}
+
+__global__ void k_sum_splits(const float* __restrict__ part, int splits, size_t n, float* __restrict__ out) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float v = 0.f;
+  for (int s = 0; s < splits; ++s) v += part[s * n + i];
+  out[i] = v;
+}
+
+void launch_debug_gemm(Ctx* c, int m, int n, int k, const void* a, const void* w, void* scratch, float* out, hipStream_t s) {
+  char* wt = (char*)scratch;
+  float* part = (float*)(wt + align_up((size_t)n * k * c->esz, 256));
+  if (c->cfg.dtype == VVS_BF16) transpose_into<bf16_t>(w, wt, k, n, n, 0, s);
+  else transpose_into<float>(w, wt, k, n, n, 0, s);
+  int sp = run_gemm(c, a, wt, part, m, n, k, true, s);
+  size_t cnt = (size_t)m * n;
+  hipLaunchKernelGGL(k_sum_splits, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, s, part, sp, cnt, out);
+}
+
+}  // namespace vvs

@@ -1,0 +1,271 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU checker on the same seeded inputs.
+Every test here needs an MI355X."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_13587_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gc():
+    import gpu_common
+    return gpu_common
+
+
+def bf16_round(a):
+    return synth.bf16_bits_to_f32(synth.f32_to_bf16_bits(np.asarray(a, dtype=np.float32)))
+
+
+# ------------------------------------------------------------------------------------------------ GEMM unit parity
+@pytest.mark.parametrize("m,n,k", [(48, 2304, 768), (432, 1280, 3456), (100, 128, 64), (1, 64, 64), (27, 3840, 1280),
+                                   (300, 6912, 1280), (1024, 3840, 1280)])
+def test_gemm_bf16_mfma(gc, m, n, k):
+    """Spans every tile shape and split-K plan, ragged M, one row."""
+    pair = gc.Pair(synth.B_SHAPE.replace(n_layers=1, n_prompts=1, vocab=1024, logit_hi=1024), with_oracle=False)
+    rng = np.random.default_rng(m * 7 + n)
+    a = bf16_round(rng.standard_normal((m, k)))
+    w = bf16_round(rng.standard_normal((k, n)) * 0.05)
+    got = pair.ctx.vvs_debug_gemm(gc.vb.to_device(a, 1), gc.vb.to_device(w, 1), m, n, k).cpu().numpy()
+    want = a.astype(np.float64) @ w.astype(np.float64)
+    scale = np.sqrt(k) * 0.05
+    assert np.abs(got - want).max() < 2e-5 * scale * 10, np.abs(got - want).max()
+    pair.close()
+
+
+@pytest.mark.parametrize("m,n,k", [(10, 384, 128), (7, 1024, 344), (3, 5, 9)])
+def test_gemm_fp32(gc, m, n, k):
+    pair = gc.Pair(synth.TINY, with_oracle=False)
+    rng = np.random.default_rng(m + n + k)
+    a = rng.standard_normal((m, k)).astype(np.float32)
+    w = (rng.standard_normal((k, n)) * 0.05).astype(np.float32)
+    got = pair.ctx.vvs_debug_gemm(gc.vb.to_device(a, 0), gc.vb.to_device(w, 0), m, n, k).cpu().numpy()
+    want = a.astype(np.float64) @ w.astype(np.float64)
+    assert np.abs(got - want).max() < 1e-5
+    pair.close()
+
+
+# ------------------------------------------------------------------------------------------------ whole image, fp32 reference shape
+def test_tiny_whole_image_fp32(gc):
+    """Config 1: the whole 64-token image through repeated verify + commit calls, chain K = 4,
+    strict acceptance; logits 1e-4, probabilities 1e-3, decisions identical outside the guard band;
+    cache contents and per-prompt state agree after every commit."""
+    shape = synth.TINY
+    pair = gc.Pair(shape, gain_jitter=0.1)
+    first, ofirst, u0 = pair.prefill()
+    raw, mixed, probs = pair.gpu_logits()
+    assert np.abs(raw[:, 0] - pair.oracle.prefill_logits).max() < 1e-4
+    assert np.abs(probs[:, 0] - pair.oracle.prefill_probs).max() < 1e-3
+    assert (first == ofirst).all()
+    parent = synth.tree_parents(None, shape.n_nodes)
+    calls = exact = guarded = 0
+    while pair.oracle.n_emitted[0] < shape.grid:
+        q, toks = synth.make_draft(shape, parent, calls)
+        u = synth.make_uniforms(shape, shape.n_nodes, calls)
+        out, oout = pair.verify(parent, toks, q, u)
+        gc.check_logits(pair, f"call {calls}")
+        e, g = gc.decisions_match(out, oout, pair.oracle.traces, shape.logit_lo)
+        exact += e
+        guarded += g
+        if not ((out[0] == oout[0]).all() and (out[2] == oout[2]).all()):
+            break                                    # a guarded draw went the other way: stop the lockstep
+        pair.commit()
+        st = pair.ctx.vvs_read_state()
+        assert st[0, 0] == pair.oracle.kv_len(0) and st[1, 0] == pair.oracle.n_emitted[0] and st[2, 0] == pair.oracle.pending[0]
+        calls += 1
+    assert calls >= 20 and exact >= calls - 3
+    # cache contents after the last commit
+    S = pair.oracle.kv_len(0)
+    for layer in range(shape.n_layers):
+        for row in range(shape.n_rows):
+            k, v = pair.ctx.vvs_debug_kv(layer, row, S)
+            assert np.abs(k.cpu().numpy() - pair.oracle.kc[row][layer].reshape(S, -1)).max() < 1e-4
+            assert np.abs(v.cpu().numpy() - pair.oracle.vc[row][layer].reshape(S, -1)).max() < 1e-4
+    pair.close()
+
+
+def test_tiny_plain_ar_and_finish(gc):
+    """N = 0 is plain AR decoding: exactly one token per pass; a finished prompt emits nothing."""
+    shape = synth.TINY.replace(grid_h=2, grid_w=3)
+    pair = gc.Pair(shape)
+    pair.prefill()
+    for it in range(shape.grid - 1):
+        u = synth.make_uniforms(shape, 0, it)
+        out, oout = pair.verify(None, None, None, u)
+        gc.check_logits(pair)
+        gc.decisions_match(out, oout, pair.oracle.traces, shape.logit_lo)
+        assert out[0][0] == 0 and out[2][0] >= 0
+        assert out[2][0] == oout[2][0]
+        pair.commit()
+    st = pair.ctx.vvs_read_state()
+    assert st[1, 0] == shape.grid
+    out, oout = pair.verify(None, None, None, synth.make_uniforms(shape, 0, 99))
+    assert out[0][0] == 0 and out[2][0] == -1 and oout[2][0] == -1
+    pair.commit()
+    assert (pair.ctx.vvs_read_state() == st).all()
+    pair.close()
+
+
+# ------------------------------------------------------------------------------------------------ bf16 shapes
+def run_bf16_case(gc, shape, n_forced, calls=2, mode=0, nbr=None, correlated=True):
+    pair = gc.Pair(shape)
+    if nbr is not None:
+        pair.set_neighbors(nbr)
+    first, ofirst, _ = pair.prefill(n_forced=n_forced, robust_u=True)
+    raw, mixed, probs = pair.gpu_logits()
+    assert np.abs(raw[:, 0] - pair.oracle.prefill_logits).max() <= gc.logit_tol(shape)
+    assert (first == ofirst).all()
+    parent = synth.tree_parents(shape.tree_widths, shape.n_nodes)
+    mask = synth.ancestor_mask(parent)
+    stats = []
+    for it in range(calls):
+        base = None
+        if correlated and it > 0:
+            base = pair.oracle.mixed_logits.astype(np.float32)   # draft that resembles the target: longer accepts
+        q, toks = synth.make_draft(shape, parent, it, base_logits=base)
+        u = synth.make_uniforms(shape, shape.n_nodes, it)
+        out, oout = pair.verify(parent, toks, q, u, mode=mode, mask=mask)
+        stats.append(gc.check_logits(pair, f"{shape.name} call {it}"))
+        # cache contents of the draft block (before commit): slots S .. S + T - 1
+        S = pair.oracle.kv_len(0)
+        k, v = pair.ctx.vvs_debug_kv(shape.n_layers - 1, 1, S)
+        ok = pair.oracle.kc[1][shape.n_layers - 1].reshape(S, -1)
+        assert np.abs(k.cpu().numpy() - ok).max() < 0.06 * max(1.0, np.abs(ok).max())
+        # the two sides may legitimately take different decisions here (bf16 logit noise moves the
+        # thresholds); continue from the checker's outcome on both sides is impossible, so stop the
+        # lockstep at the first divergence
+        if not ((out[0] == oout[0]).all() and (out[2] == oout[2]).all()):
+            break
+        pair.commit()
+        st = pair.ctx.vvs_read_state()
+        for b in range(shape.n_prompts):
+            assert st[0, b] == pair.oracle.kv_len(b) and st[1, b] == pair.oracle.n_emitted[b]
+    pair.close()
+    return stats
+
+
+def test_b_shape_full_depth(gc):
+    """Config 2 at full size (12 layers, 8 rows, chain K = 5) at a mid-image cache length."""
+    stats = run_bf16_case(gc, synth.B_SHAPE, n_forced=70, calls=2)
+    print("llamagen_b: max-abs raw/mixed/prob errors per call:", stats)
+
+
+def test_xl_tree_reduced_depth(gc):
+    """Config 3's shape (d = 1280, 20 heads, 26-node tree, dense 120-token prefix, 16 rows) with 2 layers."""
+    stats = run_bf16_case(gc, synth.XL_TREE.replace(n_layers=2), n_forced=45, calls=2)
+    print("xl_tree L=2:", stats)
+
+
+def test_7b_slice_reduced(gc):
+    """Config 4's structure (head size 128, 65536-id vocabulary with an 8192-id slice, chain K = 6)
+    at reduced width and depth."""
+    shape = synth.SEVEN_B.replace(n_layers=2, d_model=1024, n_heads=8, d_ff=2816)
+    for n_forced in (0, 40):
+        stats = run_bf16_case(gc, shape, n_forced=n_forced, calls=2)
+        print("7b-like:", n_forced, stats)
+
+
+def test_xl_stress_reduced_depth_relaxed(gc):
+    """Config 5's shape (60-node tree, relaxed acceptance with 50 neighbours, delta 0.2), 2 layers,
+    4 prompts."""
+    shape = synth.XL_STRESS.replace(n_layers=2, n_prompts=4)
+    nbr = synth.make_codebook_neighbours(shape.vocab, shape.relax_k)
+    for mode in (0, 1):
+        stats = run_bf16_case(gc, shape, n_forced=20, calls=2, mode=mode, nbr=nbr)
+        print("xl_stress L=2 mode", mode, stats)
+
+
+# ------------------------------------------------------------------------------------------------ acceptance stage on given logits
+@pytest.mark.parametrize("name,mode", [("tiny", 0), ("llamagen_xl_tree26", 0), ("llamagen_xl_tree60", 0),
+                                       ("llamagen_xl_tree60", 1), ("7b_slice", 0)])
+def test_accept_stage_on_checker_logits(gc, name, mode):
+    """CFG mix + softmax + accept / resample + path walk, fed with the same fp32 logits on both sides:
+    decisions must be identical outside the guard band.  Several draft styles: independent, close to
+    the target (long accepts), identical to the target (accept everything)."""
+    from oracle import vvs_oracle as vo
+    shape = synth.SHAPES[name].replace(n_layers=1, d_model=64, n_heads=1, d_ff=64, n_prompts=3, prefix_len=1)
+    if shape.dtype == synth.DTYPE_FP32:
+        shape = shape.replace(n_heads=2)
+    pair = gc.Pair(shape, with_oracle=False)
+    nbr = None
+    if mode == 1:
+        nbr = synth.make_codebook_neighbours(shape.vocab, shape.relax_k)
+        pair.set_neighbors(nbr)
+    parent = synth.tree_parents(shape.tree_widths, shape.n_nodes)
+    T, V, B = shape.n_nodes + 1, shape.v_eff, shape.n_prompts
+    rng = np.random.default_rng(11)
+    exact = guarded = 0
+    for style in ("independent", "close", "identical", "peaked"):
+        lc = rng.standard_normal((B, T, V)).astype(np.float32) * (4.0 if style == "peaked" else 1.0)
+        lu = rng.standard_normal((B, T, V)).astype(np.float32)
+        raw = np.stack([lc, lu], axis=1).reshape(2 * B, T, V)
+        mixed = lu.astype(np.float64) + shape.cfg_scale * (lc.astype(np.float64) - lu)
+        p = vo.softmax(mixed)
+        if style == "independent":
+            q, toks = synth.make_draft(shape, parent, 3)
+        elif style == "identical":
+            q, toks = synth.make_draft(shape.replace(draft_noise_std=0.0), parent, 4, base_logits=mixed.astype(np.float32))
+        else:
+            q, toks = synth.make_draft(shape.replace(draft_noise_std=0.5), parent, 5, base_logits=mixed.astype(np.float32))
+        u = synth.make_uniforms(shape, shape.n_nodes, 7)
+        dev = pair.dev
+        pair.ctx.vvs_accept_from_logits(shape.n_nodes, parent, None, torch.from_numpy(raw).to(dev),
+                                        torch.from_numpy(toks).to(dev), torch.from_numpy(q).to(dev),
+                                        torch.from_numpy(u).to(dev), mode, pair.accept_len, pair.path, pair.next_token)
+        torch.cuda.synchronize()
+        out = (pair.accept_len.cpu().numpy(), pair.path.cpu().numpy(), pair.next_token.cpu().numpy())
+        a_o, paths_o, next_o, traces = [], [], [], []
+        for b in range(B):
+            tr = {}
+            a, path, nxt = vo.decide(p[b], q[b].astype(np.float64), toks[b] - shape.logit_lo, parent, u[b].astype(np.float64),
+                                     10 ** 9, mode, nbr, shape.relax_k, shape.relax_delta, shape.logit_lo, trace=tr)
+            a_o.append(a); paths_o.append(path); next_o.append(shape.logit_lo + nxt); traces.append(tr)
+        e, g = gc.decisions_match(out, (np.array(a_o), paths_o, np.array(next_o)), traces, shape.logit_lo)
+        exact += e
+        guarded += g
+        if style == "identical" and mode == 0:
+            depth = synth.node_depths(parent)
+            assert (out[0] >= 1).all()               # first child always accepted when q == p
+    assert exact >= 8, (exact, guarded)
+    pair.close()
+
+
+# ------------------------------------------------------------------------------------------------ call-order and argument errors
+def test_call_order_and_argument_errors(gc):
+    vb = gc.vb
+    shape = synth.TINY
+    pair = gc.Pair(shape, with_oracle=False)
+    dev = pair.dev
+    parent = synth.tree_parents(None, shape.n_nodes)
+    q, toks = synth.make_draft(shape, parent, 0)
+    args = lambda n: (n, None, None, torch.from_numpy(toks).to(dev), torch.from_numpy(q).to(dev),
+                      torch.from_numpy(synth.make_uniforms(shape, shape.n_nodes, 0)).to(dev), 0, pair.accept_len, pair.path,
+                      pair.next_token)
+    with pytest.raises(vb.VvsError) as e:
+        pair.ctx.vvs_verify(*args(4))
+    assert e.value.status == vb.VVS_ESTATE                       # verify before prefill
+    with pytest.raises(vb.VvsError) as e:
+        pair.ctx.vvs_kv_commit()
+    assert e.value.status == vb.VVS_ESTATE                       # commit without verify
+    pair.prefill(run_oracle=False)
+    with pytest.raises(vb.VvsError) as e:
+        pair.ctx.vvs_verify(*args(5))
+    assert e.value.status == vb.VVS_ESIZE                        # more nodes than the context was sized for
+    with pytest.raises(vb.VvsError) as e:
+        pair.ctx.vvs_verify(4, np.array([0, 3, 1, 2]), *args(4)[2:])
+    assert e.value.status == vb.VVS_EINVAL                       # malformed tree
+    with pytest.raises(vb.VvsError) as e:
+        pair.ctx.vvs_verify(4, None, None, None, None, *args(4)[5:])
+    assert e.value.status == vb.VVS_EINVAL                       # NULL drafts
+    pair.ctx.vvs_verify(*args(4))
+    with pytest.raises(vb.VvsError) as e:
+        pair.ctx.vvs_verify(*args(4))
+    assert e.value.status == vb.VVS_ESTATE                       # two verifies without a commit
+    pair.ctx.vvs_kv_commit()
+    with pytest.raises(vb.VvsError) as e:
+        pair.ctx.vvs_kv_commit()
+    assert e.value.status == vb.VVS_ESTATE                       # double commit
+    torch.cuda.synchronize()
+    pair.close()
