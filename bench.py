@@ -1,0 +1,267 @@
+#!/usr/bin/env python3
+"""Benchmark of the verify pass on one MI355X.
+
+A step = one pass of the whole hot path over one batch: vvs_verify (embedding, L transformer layers
+over the T = N + 1 query tokens of every row against the KV cache, lm_head, CFG mix, softmax,
+accept / resample, path walk) followed by vvs_kv_commit.  Every step starts from the same saved
+per-prompt state (vvs_set_state, one tiny kernel, inside the timed region), so all steps do the same
+work at the same cache length.  Inputs are synthetic, seeded, and resident in HBM before timing starts.
+
+Default workload: the LlamaGen-XL shape with a 26-node depth-6 draft tree, 8 prompts x 2 CFG rows,
+at mid-image cache length.  Prints one JSON line."""
+import argparse
+import dataclasses
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 MFMA rate
+FP32_VALU_PEAK_TFLOPS = 157.3
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_correlated_draft(ctx, vb, synth, shape, parent, torch, noise_std, bufs):
+    """Synthetic drafter of tunable quality.  Level by level: run a verify pass, read the target's
+    mixed logits at the nodes of depth k, let the draft distribution of those nodes be the normalised
+    exponential of (target logits + Gaussian noise), and draw their children from it without
+    replacement.  After depth passes every internal node has a draft distribution that resembles the
+    target's, as a trained drafter's would.  Not timed."""
+    dev = ctx.device
+    B, N, V = shape.n_prompts, shape.n_nodes, shape.v_eff
+    T = N + 1
+    depth = synth.node_depths(parent)
+    rng = np.random.default_rng(shape.seed + 99)
+    q = np.full((B, T, V), 1.0 / V, dtype=np.float32)
+    toks = rng.integers(shape.logit_lo, shape.logit_hi, size=(B, N)).astype(np.int32)
+    u = synth.make_uniforms(shape, N, 0)
+    state = bufs["state"]
+    children = {}
+    for j in range(1, T):
+        children.setdefault(int(parent[j - 1]), []).append(j)
+    for level in range(int(depth.max())):
+        ctx.vvs_set_state(state)
+        ctx.vvs_verify(N, parent, None, torch.from_numpy(toks).to(dev), torch.from_numpy(q).to(dev),
+                       torch.from_numpy(u).to(dev), vb.VVS_STRICT, bufs["a"], bufs["path"], bufs["next"])
+        _, mixed, _ = ctx.vvs_debug_logits()
+        mixed = mixed.cpu().numpy()
+        for j in [j for j in range(T) if depth[j] == level and j in children]:
+            lg = mixed[:, j, :].astype(np.float64) + noise_std * rng.standard_normal((B, V))
+            lg -= lg.max(axis=1, keepdims=True)
+            e = np.exp(lg)
+            qj = e / e.sum(axis=1, keepdims=True)
+            q[:, j, :] = qj.astype(np.float32)
+            for b in range(B):
+                w = q[b, j].astype(np.float64)
+                w /= w.sum()
+                nz = int((w > 0).sum())
+                kids = children[j]
+                picks = rng.choice(V, size=len(kids), replace=False, p=w) if nz >= len(kids) else rng.choice(V, size=len(kids), replace=False)
+                for c, x in zip(kids, picks):
+                    toks[b, c - 1] = shape.logit_lo + int(x)
+    ctx.vvs_set_state(state)
+    return q, toks, u
+
+
+def algorithmic_counts(shape, S_mean):
+    """Bytes and flops one verify call must move / do (weights once, KV cache once, draft probs once)."""
+    L, d, F, V = shape.n_layers, shape.d_model, shape.d_ff, shape.v_eff
+    R, T, B = shape.n_rows, shape.n_nodes + 1, shape.n_prompts
+    M = R * T
+    w_bytes = 2 * (L * (4 * d * d + 3 * d * F) + d * V)
+    kv_read = R * L * 2 * S_mean * d * 2
+    kv_write = R * L * 2 * T * d * 2
+    q_read = B * T * V * 4
+    gemm_flops = 2 * M * (L * (4 * d * d + 3 * d * F) + d * V)
+    attn_flops = 4 * T * (S_mean + T) * d * L * R
+    return dict(w_bytes=w_bytes, kv_read=kv_read, kv_write=kv_write, q_read=q_read, gemm_flops=gemm_flops,
+                attn_flops=attn_flops, M=M)
+
+
+def cpu_baseline(shape, weights, synth, n_forced, log_fn):
+    """The CPU checker as it stands, timed on a bounded sample: ONE prompt (2 CFG rows) of the same
+    workload, same draft tree, short cache (prefix + n_forced image tokens).  Only verify + commit are
+    timed; the value is emitted tokens per second of that call."""
+    from oracle import vvs_oracle as vo
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [os.cpu_count()])
+    except Exception:
+        threads = os.cpu_count()
+    s1 = shape.replace(n_prompts=1)
+    o = vo.Oracle(dataclasses.asdict(s1), weights)
+    pc, pu = synth.make_prefix(s1)
+    t0 = time.perf_counter()
+    o.prefill(pc, pu, synth.make_forced_tokens(s1, n_forced), np.array([0.5]))
+    log_fn(f"cpu baseline: prefill of the sample took {time.perf_counter() - t0:.1f} s (not counted)")
+    parent = synth.tree_parents(s1.tree_widths, s1.n_nodes)
+    q, toks = synth.make_draft(s1, parent, 0)
+    u = synth.make_uniforms(s1, s1.n_nodes, 0)
+    t0 = time.perf_counter()
+    a, _, _ = o.verify(parent, toks, q, u)
+    o.kv_commit()
+    dt = time.perf_counter() - t0
+    emitted = float(a.sum() + len(a))
+    return {"value": emitted / dt, "unit": "verified tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"1 of {shape.n_prompts} prompts (2 CFG rows), same {s1.n_nodes}-node tree, cache length "
+                      f"{s1.prefix_len}+{n_forced}; verify+commit took {dt:.2f} s for {emitted:.0f} emitted / "
+                      f"{s1.n_nodes} scored draft tokens"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llamagen_xl_tree26")
+    ap.add_argument("--image-tokens", type=int, default=-1, help="image tokens already emitted (default: half the grid)")
+    ap.add_argument("--draft-noise", type=float, default=1.0, help="std of the noise between draft and target logits")
+    ap.add_argument("--mode", choices=["strict", "relaxed"], default="strict")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", type=int, default=0, help="override depth (debugging only; the result is then not the named workload)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; prompts shard across GPUs without any collective, which is not "
+              "exercised here.  Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2511_13587_amd import binding as vb
+    from paper_2511_13587_amd import synth
+
+    shape = synth.SHAPES[args.workload]
+    if args.layers:
+        shape = shape.replace(n_layers=args.layers)
+    n_emitted = shape.grid // 2 if args.image_tokens < 0 else args.image_tokens
+    n_forced = n_emitted - 1
+    mode = vb.VVS_RELAXED if args.mode == "relaxed" else vb.VVS_STRICT
+
+    t0 = time.perf_counter()
+    weights = synth.make_weights(shape)
+    log(f"weights generated in {time.perf_counter() - t0:.1f} s")
+    ctx = vb.Context(vb.make_config(shape))
+    ctx.load_weights_from_host(weights, synth.weight_names(shape))
+    dev = ctx.device
+    if shape.relax_k:
+        nbr = torch.from_numpy(synth.make_codebook_neighbours(shape.vocab, shape.relax_k)).to(dev)
+        ctx.vvs_set_neighbors(nbr)
+    log(f"context: kv {ctx.kv_bytes / 2**30:.2f} GiB, workspace {ctx.ws_bytes / 2**30:.2f} GiB, weights {ctx.pw_bytes / 2**30:.2f} GiB")
+
+    B = shape.n_prompts
+    pc, pu = synth.make_prefix(shape)
+    if shape.prefix_kind == synth.PREFIX_CLASS:
+        dpc, dpu = torch.from_numpy(pc).to(dev), None
+    else:
+        dpc, dpu = vb.to_device(pc, shape.dtype), vb.to_device(pu, shape.dtype)
+    forced = torch.from_numpy(synth.make_forced_tokens(shape, n_forced)).to(dev) if n_forced > 0 else None
+    first = torch.zeros(B, dtype=torch.int32, device=dev)
+    u0 = torch.from_numpy(np.random.default_rng(1).random(B, dtype=np.float32)).to(dev)
+    t0 = time.perf_counter()
+    ctx.vvs_prefill(dpc, dpu, forced, u0, first)
+    torch.cuda.synchronize()
+    log(f"prefill to cache length {shape.prefix_len}+{n_forced}: {time.perf_counter() - t0:.3f} s")
+    state0 = ctx.vvs_read_state()
+    state = torch.from_numpy(state0).to(dev)
+    bufs = dict(state=state, a=torch.zeros(B, dtype=torch.int32, device=dev),
+                path=torch.zeros((B, vb.VVS_MAX_T), dtype=torch.int32, device=dev),
+                next=torch.zeros(B, dtype=torch.int32, device=dev))
+    parent = synth.tree_parents(shape.tree_widths, shape.n_nodes)
+    mask = synth.ancestor_mask(parent)
+    q, toks, u = build_correlated_draft(ctx, vb, synth, shape, parent, torch, args.draft_noise, bufs)
+    dq, dtoks, du = torch.from_numpy(q).to(dev), torch.from_numpy(toks).to(dev), torch.from_numpy(u).to(dev)
+    N = shape.n_nodes
+
+    def step():
+        ctx.vvs_set_state(state)
+        ctx.vvs_verify(N, parent, mask, dtoks, dq, du, mode, bufs["a"], bufs["path"], bufs["next"])
+        ctx.vvs_kv_commit()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    accept = bufs["a"].cpu().numpy()
+    emitted = float(accept.sum() + B)
+    value = emitted / (ms_per_step * 1e-3)
+
+    # per-kernel-class durations from HIP events recorded by the library on this stream
+    ctx.vvs_timing_enable(True)
+    tsteps = min(args.steps, 10)
+    for _ in range(tsteps):
+        step()
+    torch.cuda.synchronize()
+    names = ["gemm", "attention", "accept", "elementwise", "commit"]
+    classes = {}
+    for k, nm in enumerate(names):
+        n, ms = ctx.vvs_timing_read(k)
+        classes[nm] = {"launches_per_step": n / tsteps, "ms_per_step": ms / tsteps}
+    ctx.vvs_timing_enable(False)
+    S_mean = float(state0[0].mean())
+    cnt = algorithmic_counts(shape, S_mean)
+    dom = max(("gemm", "attention"), key=lambda k: classes[k]["ms_per_step"])
+    if dom == "gemm":
+        n_launch = classes["gemm"]["launches_per_step"]
+        t_launch = classes["gemm"]["ms_per_step"] * 1e-3 / n_launch
+        bytes_launch, flops_launch = cnt["w_bytes"] / n_launch, cnt["gemm_flops"] / n_launch
+        kernel = "k_gemm_mfma (all bf16 projection GEMMs of one verify call)"
+    else:
+        n_launch = classes["attention"]["launches_per_step"]
+        t_launch = classes["attention"]["ms_per_step"] * 1e-3 / n_launch
+        bytes_launch = (cnt["kv_read"] + cnt["kv_write"]) / n_launch
+        flops_launch = cnt["attn_flops"] / n_launch
+        kernel = "k_attn_mfma"
+    ideal_hbm, ideal_mfma = bytes_launch / (HBM_PEAK_GBS * 1e9), flops_launch / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    if ideal_mfma > ideal_hbm:
+        ach = flops_launch / t_launch / 1e12
+        roof = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS}
+    else:
+        ach = bytes_launch / t_launch / 1e9
+        roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS}
+    roof.update(traffic=None, kernel=kernel, launches_per_step=n_launch, avg_launch_us=t_launch * 1e6,
+                algorithmic_bytes_per_launch=bytes_launch, algorithmic_flops_per_launch=flops_launch)
+    total_bytes = cnt["w_bytes"] + cnt["kv_read"] + cnt["kv_write"] + cnt["q_read"]
+
+    out = {
+        "metric": "verified tokens/s + verify latency at XL shape; % HBM/MFMA roofline",
+        "value": value, "unit": "verified tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if shape.dtype == synth.DTYPE_BF16 else "f32", "data": "synthetic",
+        "config": {"workload": shape.name, "layers": shape.n_layers, "d_model": shape.d_model, "prompts": B,
+                   "rows": shape.n_rows, "draft_nodes": N, "tree_depth": int(synth.node_depths(parent).max()),
+                   "cache_len_mean": S_mean, "mode": args.mode, "draft_noise_std": args.draft_noise},
+        "verify_latency_ms": ms_per_step, "mean_accept_len": float(accept.mean()),
+        "emitted_tokens_per_step": emitted, "scored_draft_tokens_per_s": B * N / (ms_per_step * 1e-3),
+        "whole_pass": {"algorithmic_GB": total_bytes / 1e9, "algorithmic_TFLOP": (cnt["gemm_flops"] + cnt["attn_flops"]) / 1e12,
+                       "hbm_frac": total_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9),
+                       "mfma_frac": (cnt["gemm_flops"] + cnt["attn_flops"]) / (ms_per_step * 1e-3) / (MFMA_BF16_PEAK_TFLOPS * 1e12)},
+        "kernel_classes": classes,
+        "roofline": roof,
+    }
+    ctx.close()
+    del ctx
+    if not args.no_cpu_baseline:
+        try:
+            out["cpu_baseline"] = cpu_baseline(shape, weights, synth, 32, log)
+        except MemoryError as e:           # pragma: no cover
+            out["cpu_baseline"] = {"value": None, "unit": "verified tokens/s", "cores": os.cpu_count(), "kind": "oracle",
+                                   "sample": f"failed: {e}"}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -161,6 +161,20 @@ vvs_status vvs_kv_commit(vvs_ctx* ctx, vvs_stream s);
 /* Per-prompt state: int32 [3, B] out = cached length S_b, emitted image tokens, pending token. */
 vvs_status vvs_read_state(vvs_ctx* ctx, int32_t* d_state, vvs_stream s);
 
+/* Overwrites the per-prompt state with int32 [3, B] (same layout as vvs_read_state): rolls the context
+ * back (or forward) to a cached length whose K/V are still in the cache, e.g. to replay one verify
+ * call.  Cached slots below the given length must hold valid K/V; that is the caller's business.
+ * Clears a pending (uncommitted) verify. */
+vvs_status vvs_set_state(vvs_ctx* ctx, const int32_t* d_state, vvs_stream s);
+
+/* Kernel-class timing for benchmarks.  While enabled, every kernel launch of prefill / verify /
+ * commit is bracketed by HIP events recorded on the caller's stream (host objects; no device
+ * memory).  vvs_timing_read waits for the recorded events and returns the number of launches and
+ * their summed duration for one class since timing was enabled. */
+enum { VVS_K_GEMM = 0, VVS_K_ATTENTION = 1, VVS_K_ACCEPT = 2, VVS_K_ELEMENTWISE = 3, VVS_K_COMMIT = 4, VVS_K_CLASSES = 5 };
+vvs_status vvs_timing_enable(vvs_ctx* ctx, int32_t on);
+vvs_status vvs_timing_read(vvs_ctx* ctx, int32_t kernel_class, int32_t* n_launches, float* total_ms);
+
 /* Inspection of the last verify (or prefill, with T = 1): any pointer may be NULL.
  *   d_raw_logits float [R, T, V_eff]; d_mixed_logits float [B, T, V_eff]; d_probs float [B, T, V_eff]. */
 vvs_status vvs_debug_logits(vvs_ctx* ctx, float* d_raw_logits, float* d_mixed_logits, float* d_probs,

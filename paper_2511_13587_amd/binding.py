@@ -19,6 +19,7 @@ VVS_OK, VVS_EINVAL, VVS_ESTATE, VVS_ESIZE, VVS_EHIP = 0, -1, -2, -3, -4
 VVS_FP32, VVS_BF16 = 0, 1
 VVS_STRICT, VVS_RELAXED = 0, 1
 VVS_MAX_T = 64
+VVS_K_GEMM, VVS_K_ATTENTION, VVS_K_ACCEPT, VVS_K_ELEMENTWISE, VVS_K_COMMIT = range(5)
 
 
 class VvsConfig(C.Structure):
@@ -55,6 +56,9 @@ def _load():
         "vvs_accept_from_logits": (i32, [vp, i32, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]),
         "vvs_kv_commit": (i32, [vp, vp]),
         "vvs_read_state": (i32, [vp, vp, vp]),
+        "vvs_set_state": (i32, [vp, vp, vp]),
+        "vvs_timing_enable": (i32, [vp, i32]),
+        "vvs_timing_read": (i32, [vp, i32, C.POINTER(i32), C.POINTER(C.c_float)]),
         "vvs_debug_logits": (i32, [vp, vp, vp, vp, vp]),
         "vvs_debug_kv": (i32, [vp, i32, i32, i32, vp, vp, vp]),
         "vvs_debug_gemm_scratch_bytes": (sz, [vp, i32, i32, i32]),
@@ -210,6 +214,18 @@ class Context:
         out = torch.empty((3, self.B), dtype=torch.int32, device=self.device)
         self._check(lib.vvs_read_state(self.h, _ptr(out), _stream()))
         return out.cpu().numpy()
+
+    def vvs_set_state(self, state: torch.Tensor):
+        assert state.dtype == torch.int32 and state.numel() == 3 * self.B
+        self._check(lib.vvs_set_state(self.h, _ptr(state), _stream()))
+
+    def vvs_timing_enable(self, on: bool):
+        self._check(lib.vvs_timing_enable(self.h, 1 if on else 0))
+
+    def vvs_timing_read(self, kernel_class: int):
+        n, ms = C.c_int32(), C.c_float()
+        self._check(lib.vvs_timing_read(self.h, kernel_class, C.byref(n), C.byref(ms)))
+        return n.value, ms.value
 
     def vvs_debug_logits(self):
         T = self.last_T

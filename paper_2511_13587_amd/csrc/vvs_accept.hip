@@ -209,6 +209,7 @@ __global__ void k_walk(const int32_t* __restrict__ node_result, int B, int32_t* 
 void launch_accept(Ctx* c, const TreeDesc& tree, int T, const float* d_logits, const int32_t* d_draft_tokens, const float* d_q,
                    const float* d_u, int usb, int usj, int uoa, int uot, int mode, bool use_state, int32_t* d_accept_len,
                    int32_t* d_path, int32_t* d_next, bool keep_outcome, hipStream_t s) {
+  Timed timed(c, VVS_K_ACCEPT, s);
   AcceptArgs a;
   a.logits = d_logits; a.draft = d_draft_tokens; a.q = d_q; a.u = d_u;
   a.usb = usb; a.usj = usj; a.uoa = uoa; a.uot = uot;

@@ -270,7 +270,53 @@ vvs_status vvs_create(const vvs_config* cfg, void* d_kv, void* d_workspace, void
   return VVS_OK;
 }
 
-void vvs_destroy(vvs_ctx* ctx) { delete reinterpret_cast<Ctx*>(ctx); }
+void vvs_destroy(vvs_ctx* ctx) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return;
+  for (auto& t : c->timed) { (void)hipEventDestroy(t.t0); (void)hipEventDestroy(t.t1); }
+  delete c;
+}
+
+vvs_status vvs_timing_enable(vvs_ctx* ctx, int32_t on) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return VVS_EINVAL;
+  c->timing = on != 0;
+  if (on) c->n_timed = 0;
+  return VVS_OK;
+}
+
+vvs_status vvs_timing_read(vvs_ctx* ctx, int32_t kernel_class, int32_t* n_launches, float* total_ms) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return VVS_EINVAL;
+  if (kernel_class < 0 || kernel_class >= VVS_K_CLASSES || !n_launches || !total_ms)
+    return fail(&c->err, VVS_EINVAL, "timing_read: bad argument");
+  int n = 0;
+  float ms = 0.f;
+  for (size_t i = 0; i < c->n_timed; ++i) {
+    TimedLaunch& t = c->timed[i];
+    if (t.cls != kernel_class) continue;
+    hipError_t e = hipEventSynchronize(t.t1);
+    float one = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&one, t.t0, t.t1);
+    if (e != hipSuccess) return hip_fail(c, e, "timing_read");
+    ms += one;
+    ++n;
+  }
+  *n_launches = n;
+  *total_ms = ms;
+  return VVS_OK;
+}
+
+vvs_status vvs_set_state(vvs_ctx* ctx, const int32_t* d_state, vvs_stream s) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return VVS_EINVAL;
+  if (!d_state) return fail(&c->err, VVS_EINVAL, "set_state: NULL");
+  if (!c->prefilled) return fail(&c->err, VVS_ESTATE, "set_state: call vvs_prefill first");
+  launch_set_state(c, d_state, (hipStream_t)s);
+  vvs_status rc = check_launch(c, "set_state");
+  if (rc == VVS_OK) c->verify_pending = false;
+  return rc;
+}
 
 const char* vvs_last_error(const vvs_ctx* ctx) {
   if (!ctx) return g_last_error.c_str();

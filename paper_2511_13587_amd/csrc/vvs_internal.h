@@ -4,6 +4,7 @@
 #include <stdint.h>
 #include <stddef.h>
 #include <string>
+#include <vector>
 #include "vvs.h"
 
 namespace vvs {
@@ -45,6 +46,8 @@ struct PackedLayout {
   size_t total;
 };
 
+struct TimedLaunch { int cls; hipEvent_t t0, t1; };
+
 struct Ctx {
   vvs_config cfg;
   int B, R, d, H, dh, F, L, V, lo, veff, P, G, Tmax, chunk, Mmax, Mlog, S_cap, rope_pos;
@@ -58,6 +61,26 @@ struct Ctx {
   bool weights_loaded, prefilled, verify_pending;
   int last_T;                            // T of the last verify / prefill (for debug export)
   std::string err;
+  bool timing;                           // bracket launches with events
+  std::vector<TimedLaunch> timed;        // recorded launches (events are reused across enables)
+  size_t n_timed;
+};
+
+// Brackets the launches made during its lifetime with two events when timing is enabled.
+struct Timed {
+  Ctx* c; hipStream_t s; TimedLaunch* t;
+  Timed(Ctx* ctx, int cls, hipStream_t st) : c(ctx), s(st), t(nullptr) {
+    if (!c->timing) return;
+    if (c->n_timed == c->timed.size()) {
+      TimedLaunch n{cls, nullptr, nullptr};
+      if (hipEventCreate(&n.t0) != hipSuccess || hipEventCreate(&n.t1) != hipSuccess) return;
+      c->timed.push_back(n);
+    }
+    t = &c->timed[c->n_timed++];
+    t->cls = cls;
+    (void)hipEventRecord(t->t0, s);
+  }
+  ~Timed() { if (t) (void)hipEventRecord(t->t1, s); }
 };
 
 // ---- host planner (vvs_host.cpp)
@@ -80,6 +103,7 @@ void launch_accept(Ctx* c, const TreeDesc& tree, int T, const float* d_logits, c
 void launch_prefill_finish(Ctx* c, int n_forced, int32_t* d_first, hipStream_t s);
 void launch_commit(Ctx* c, hipStream_t s);
 void launch_read_state(Ctx* c, int32_t* d_state, hipStream_t s);
+void launch_set_state(Ctx* c, const int32_t* d_state, hipStream_t s);
 void launch_debug_logits(Ctx* c, float* raw, float* mixed, float* probs, hipStream_t s);
 void launch_debug_kv(Ctx* c, int layer, int row, int n_slots, float* dk, float* dv, hipStream_t s);
 void launch_debug_gemm(Ctx* c, int m, int n, int k, const void* a, const void* w, void* scratch, float* out, hipStream_t s);

@@ -137,6 +137,7 @@ __global__ void k_build_tokens(int32_t* __restrict__ tokens, const int32_t* __re
 }
 
 void launch_build_tokens(Ctx* c, int T, const int32_t* d_draft, hipStream_t s) {
+  Timed timed(c, VVS_K_ELEMENTWISE, s);
   int n = c->B * T;
   const int32_t* pending = (const int32_t*)(c->ws + c->w.state) + 2 * c->B;
   hipLaunchKernelGGL(k_build_tokens, dim3((n + 255) / 256), dim3(256), 0, s, (int32_t*)(c->ws + c->w.tokens), pending, d_draft,
@@ -297,6 +298,7 @@ static bool force_simple() {
 static int run_gemm(Ctx* c, const void* A, const void* W, float* C, int M, int N, int K, bool allow_split, hipStream_t s) {
   GemmPlan p = plan_gemm(c, M, N, K);
   if (!allow_split) p.splits = 1;
+  Timed timed(c, VVS_K_GEMM, s);
   if (c->cfg.dtype == VVS_BF16 && !force_simple()) {
     mfma_gemm((const bf16_t*)A, (const bf16_t*)W, C, M, N, K, p, s);
     return p.splits;
@@ -323,33 +325,45 @@ static void forward_t(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, 
   const float* rope = (const float*)(c->ws + c->w.rope_tab);
   EmbedArgs ea{Tq, d, c->V, d_tokens_bt ? 0 : 1, d_tokens_bt, pc, pu, c->cfg.prefix_kind, c->cfg.n_classes, c->P, chunk_start,
                n_forced, forced};
+  { Timed timed(c, VVS_K_ELEMENTWISE, s);
   hipLaunchKernelGGL(k_embed<T>, dim3(M), dim3(256), 0, s, x, (const T*)(c->pw + c->p.embed),
                      (const T*)(c->pw + c->p.prefix_embed), ea);
+  }
   int splits = 0;   // partial sums waiting to be added to x
   size_t sstride = 0;
   for (int l = 0; l < c->L; ++l) {
     const char* lw = c->pw + c->p.layer0 + c->p.layer_stride * l;
     T* kc = (T*)c->kv + c->kv_layer_stride * l;
     T* vc = (T*)c->kv + c->kv_v_off + c->kv_layer_stride * l;
+    { Timed timed(c, VVS_K_ELEMENTWISE, s);
     hipLaunchKernelGGL(k_add_rmsnorm<T>, dim3(M), dim3(256), 0, s, x, go, splits, sstride, d, (const float*)(lw + c->p.g1),
                        c->cfg.rms_eps, h, 1, 0);
+    }
     int sp = run_gemm(c, h, lw + c->p.wqkv, go, M, 3 * d, d, true, s);
+    { Timed timed(c, VVS_K_ELEMENTWISE, s);
     hipLaunchKernelGGL(k_rope_kv<T>, dim3(M), dim3(256), 0, s, go, sp, (size_t)M * 3 * d, q, kc, vc, rope, tree, pos, Tq, d, c->dh,
                        c->kv_row_stride, c->kv_head_stride, c->S_cap, c->rope_pos);
+    }
     if (c->cfg.dtype == VVS_BF16 && !force_simple()) {
+      Timed timed(c, VVS_K_ATTENTION, s);
       mfma_attention(c, l, tree, pos, Tq, s);
     } else {
+      Timed timed(c, VVS_K_ATTENTION, s);
       size_t lds = sizeof(float) * (c->S_cap + 16);
       hipLaunchKernelGGL(k_attn_simple<T>, dim3(Tq, c->H, c->R), dim3(256), lds, s, q, kc, vc, attn, tree, pos, Tq, d, c->dh,
                          c->kv_row_stride, c->kv_head_stride, c->S_cap);
     }
     sp = run_gemm(c, attn, lw + c->p.wo, go, M, d, d, true, s);
+    { Timed timed(c, VVS_K_ELEMENTWISE, s);
     hipLaunchKernelGGL(k_add_rmsnorm<T>, dim3(M), dim3(256), 0, s, x, go, sp, (size_t)M * d, d, (const float*)(lw + c->p.g2),
                        c->cfg.rms_eps, h, 1, 0);
+    }
     sp = run_gemm(c, h, lw + c->p.wgu, go, M, 2 * F, d, true, s);
     {
       size_t n = (size_t)M * F;
+      { Timed timed(c, VVS_K_ELEMENTWISE, s);
       hipLaunchKernelGGL(k_swiglu<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, go, sp, (size_t)M * 2 * F, act, M, F);
+      }
     }
     splits = run_gemm(c, act, lw + c->p.wd, go, M, d, F, true, s);
     sstride = (size_t)M * d;
@@ -361,10 +375,14 @@ static void forward_t(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, 
   int Ml;
   if (logits_mode == 1) {     // every token
     Ml = M;
+    { Timed timed(c, VVS_K_ELEMENTWISE, s);
     hipLaunchKernelGGL(k_add_rmsnorm<T>, dim3(Ml), dim3(256), 0, s, x, go, splits, sstride, d, gf, c->cfg.rms_eps, hf, 1, 0);
+    }
   } else {                    // last token of every row
     Ml = c->R;
+    { Timed timed(c, VVS_K_ELEMENTWISE, s);
     hipLaunchKernelGGL(k_add_rmsnorm<T>, dim3(Ml), dim3(256), 0, s, x, go, splits, sstride, d, gf, c->cfg.rms_eps, hf, Tq, Tq - 1);
+    }
   }
   run_gemm(c, hf, c->pw + c->p.wout, logits, Ml, c->veff, d, false, s);
 }
@@ -412,6 +430,7 @@ __global__ void k_commit_state(int32_t* __restrict__ state, const int32_t* __res
 }
 
 void launch_commit(Ctx* c, hipStream_t s) {
+  Timed timed(c, VVS_K_COMMIT, s);
   int32_t* state = (int32_t*)(c->ws + c->w.state);
   const int32_t* oc = (const int32_t*)(c->ws + c->w.outcome);
   const int32_t* accept_len = oc;
@@ -435,6 +454,11 @@ __global__ void k_read_state(const int32_t* __restrict__ state, int32_t* __restr
 void launch_read_state(Ctx* c, int32_t* d_state, hipStream_t s) {
   int n = 3 * c->B;
   hipLaunchKernelGGL(k_read_state, dim3((n + 255) / 256), dim3(256), 0, s, (const int32_t*)(c->ws + c->w.state), d_state, n);
+}
+
+void launch_set_state(Ctx* c, const int32_t* d_state, hipStream_t s) {
+  int n = 3 * c->B;
+  hipLaunchKernelGGL(k_read_state, dim3((n + 255) / 256), dim3(256), 0, s, d_state, (int32_t*)(c->ws + c->w.state), n);
 }
 
 // ------------------------------------------------------------------------------------------------ inspection

@@ -134,8 +134,9 @@ def check_logits(pair, label=""):
 
 def decisions_match(out, oout, traces, lo, guard=GUARD):
     """Compares (accept_len, path, next_token) per prompt.  Returns (n_exact, n_guarded): prompts
-    compared exactly / prompts where a consulted draw was inside the guard band (those only need a
-    valid outcome).  Raises AssertionError on a real mismatch."""
+    whose outcome had to be (and was) identical / prompts where a consulted draw was inside the guard
+    band, which only need a valid outcome (for the final draw: a token whose CDF interval lies within
+    the guard of the uniform).  Raises AssertionError on a real mismatch."""
     a_g, path_g, next_g = out
     a_o, paths_o, next_o = oout
     exact = guarded = 0
