@@ -22,6 +22,27 @@ __device__ __forceinline__ size_t v_index(int slot, int dim, int dh) {
   return ((size_t)(slot >> 5) * dh + dim) * 32 + (slot & 31);
 }
 
+// GEMM operands of the bf16 path are stored in MFMA fragment order: 1 KiB blocks of 32 rows x 16
+// contraction indices; inside a block lane = row%32 + 32*((k%16)/8) holds 8 consecutive k.
+__device__ __host__ __forceinline__ size_t pack_index(int row, int k, int K) {
+  return ((size_t)(row >> 5) * (K >> 4) + (k >> 4)) * 512 + (size_t)(((row & 31) + 32 * ((k >> 3) & 1)) * 8 + (k & 7));
+}
+// Stores 8 consecutive activation values (k0 % 8 == 0) of one row: row-major fp32, or one 16-byte
+// chunk of the packed bf16 layout.
+__device__ __forceinline__ void store8(float* base, int row, int k0, int K, const float* v) {
+  float4* p = (float4*)(base + (size_t)row * K + k0);
+  p[0] = make_float4(v[0], v[1], v[2], v[3]);
+  p[1] = make_float4(v[4], v[5], v[6], v[7]);
+}
+__device__ __forceinline__ void store8(bf16_t* base, int row, int k0, int K, const float* v) {
+  uint4 o;
+  o.x = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
+  o.y = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
+  o.z = (uint32_t)f2bf(v[4]) | ((uint32_t)f2bf(v[5]) << 16);
+  o.w = (uint32_t)f2bf(v[6]) | ((uint32_t)f2bf(v[7]) << 16);
+  *(uint4*)(base + pack_index(row, k0, K)) = o;
+}
+
 // wave64 reductions, fixed order
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -93,6 +114,9 @@ __device__ __forceinline__ void token_pos(const PosDesc& pos, const TreeDesc& tr
 
 // MFMA attention / GEMM launchers (vvs_mfma.hip)
 void mfma_gemm(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, GemmPlan p, hipStream_t s);
+void mfma_gemm_swiglu(const bf16_t* A, const bf16_t* Wgu, bf16_t* act, int M, int F, int K, GemmPlan p, hipStream_t s);
+void mfma_gemm_qkv(Ctx* c, int layer, const bf16_t* A, const bf16_t* Wqkv, const TreeDesc& tree, const PosDesc& pos, int T, GemmPlan p,
+                   hipStream_t s);
 void mfma_attention(Ctx* c, int layer, const TreeDesc& tree, const PosDesc& pos, int T, hipStream_t s);
 
 }  // namespace vvs

@@ -22,18 +22,17 @@ static vvs_status fail(std::string* err, vvs_status st, const std::string& msg) 
 GemmPlan plan_gemm(const Ctx* c, int M, int N, int K) {
   GemmPlan p{64, 64, 1};
   if (c->cfg.dtype != VVS_BF16) return p;           // fp32 path: one wave per output column, no split
-  auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * (N / bn); };
-  const int want = 256;                             // one workgroup per CU at least
-  if (N % 128 == 0 && tiles(128, 128) >= want) return GemmPlan{128, 128, 1};
-  if (N % 128 == 0 && tiles(64, 128) >= want) return GemmPlan{64, 128, 1};
-  p.bm = 64; p.bn = 64;
-  int t = tiles(64, 64);
-  int kt = K / 64;
+  // bf16: 64 x 64 output tiles (32 x 64 for up to 32 rows); every workgroup already splits its K range
+  // over its 4 waves.  Add grid-level K splits until there is about one workgroup per CU, keeping at
+  // least 8 k-steps of 16 per wave.
+  p.bm = M <= 32 ? 32 : 64;
+  const int tiles = ((M + p.bm - 1) / p.bm) * (N / 64);
+  const int kb = K / 16;
   int splits = 1;
-  if (t < want) {
-    splits = std::min({(want + t - 1) / t, 8, std::max(1, kt / 4)});
-    int per = (kt + splits - 1) / splits;
-    splits = (kt + per - 1) / per;
+  if (tiles < 256) {
+    splits = std::min({(256 + tiles - 1) / tiles, 8, std::max(1, kb / 32)});
+    const int per = (kb + splits - 1) / splits;
+    splits = (kb + per - 1) / per;
   }
   p.splits = splits;
   return p;
@@ -58,6 +57,7 @@ vvs_status plan_sizes(const vvs_config* cfg, Ctx* c, std::string* err) {
   if (!(g.rms_eps > 0.f) || !(g.rope_base > 1.f)) return fail(err, VVS_EINVAL, "config: rms_eps / rope_base");
   int dh = g.d_model / g.n_heads;
   if (dh % 4) return fail(err, VVS_ESIZE, "config: head size must be a multiple of 4 (2D rotary pairs)");
+  if (g.d_model % 8 || g.d_ff % 8) return fail(err, VVS_ESIZE, "config: d_model and d_ff must be multiples of 8");
   if (dh > 256) return fail(err, VVS_ESIZE, "config: head size above 256 is not supported");
   int veff = g.logit_hi - g.logit_lo;
   if (g.dtype == VVS_BF16) {
@@ -71,8 +71,8 @@ vvs_status plan_sizes(const vvs_config* cfg, Ctx* c, std::string* err) {
   c->L = g.n_layers; c->V = g.vocab; c->lo = g.logit_lo; c->veff = veff; c->P = g.prefix_len;
   c->G = g.grid_h * g.grid_w; c->Tmax = g.max_nodes + 1;
   c->chunk = (dh > 64) ? 32 : 64;
-  c->Mmax = c->R * std::max(c->Tmax, c->chunk);
-  c->Mlog = c->R * c->Tmax;
+  c->Mmax = (int)align_up((size_t)c->R * std::max(c->Tmax, c->chunk), 32);   // packed operands come in 32-row blocks
+  c->Mlog = (int)align_up((size_t)c->R * c->Tmax, 32);
   c->S_cap = (int)align_up((size_t)c->P + c->G + VVS_MAX_T, 32);
   c->rope_pos = std::max(g.grid_h + VVS_MAX_T / g.grid_w + 2, g.grid_w);
   c->esz = g.dtype == VVS_BF16 ? 2 : 4;
@@ -482,7 +482,8 @@ size_t vvs_debug_gemm_scratch_bytes(const vvs_ctx* ctx, int32_t m, int32_t n, in
   const Ctx* c = reinterpret_cast<const Ctx*>(ctx);
   if (!c || m < 1 || n < 1 || k < 1) return 0;
   GemmPlan p = plan_gemm(c, m, n, k);
-  return align_up((size_t)n * k * c->esz, 256) + align_up((size_t)p.splits * m * n * sizeof(float), 256);
+  return align_up((size_t)n * k * c->esz, 256) + align_up(align_up((size_t)m, 32) * k * c->esz, 256) +
+         align_up((size_t)p.splits * m * n * sizeof(float), 256);
 }
 
 vvs_status vvs_debug_gemm(vvs_ctx* ctx, int32_t m, int32_t n, int32_t k, const void* d_a, const void* d_w, void* d_scratch,

@@ -40,8 +40,50 @@ __global__ void k_transpose(const T* __restrict__ in, T* __restrict__ out, int K
   }
 }
 
+// bf16 weights: out = packed fragment order of W^T, i.e. rows = output features n, contraction = k;
+// in[k][col0 + n].  One thread per 16-byte chunk; the 32 lanes of a half-block read 32 consecutive n.
+// Row block nb of the source lands in row block nb * nb_stride + nb_off of the destination (gate and
+// up projections are interleaved block by block so that one GEMM tile holds both for the same units).
+__global__ void k_pack_w(const bf16_t* __restrict__ in, uint4* __restrict__ out, int K, int N, int ld, int col0, int nb_stride,
+                         int nb_off) {
+  const size_t chunk = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t total = (size_t)(N >> 5) * (K >> 4) * 64;
+  if (chunk >= total) return;
+  const int lane = (int)(chunk & 63);
+  const size_t blk = chunk >> 6;
+  const int kb = (int)(blk % (K >> 4)), nb = (int)(blk / (K >> 4));
+  const int n = nb * 32 + (lane & 31), k0 = kb * 16 + (lane >> 5) * 8;
+  uint32_t w[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint32_t lo = in[(size_t)(k0 + 2 * i) * ld + col0 + n], hi = in[(size_t)(k0 + 2 * i + 1) * ld + col0 + n];
+    w[i] = lo | (hi << 16);
+  }
+  out[(((size_t)nb * nb_stride + nb_off) * (K >> 4) + kb) * 64 + lane] = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// bf16 activations, row-major [M][K] -> packed fragment order (rows beyond M are zero)
+__global__ void k_pack_a(const bf16_t* __restrict__ in, uint4* __restrict__ out, int M, int K) {
+  const size_t chunk = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t total = (size_t)((M + 31) >> 5) * (K >> 4) * 64;
+  if (chunk >= total) return;
+  const int lane = (int)(chunk & 63);
+  const size_t blk = chunk >> 6;
+  const int kb = (int)(blk % (K >> 4)), mb = (int)(blk / (K >> 4));
+  const int m = mb * 32 + (lane & 31), k0 = kb * 16 + (lane >> 5) * 8;
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (m < M) v = *(const uint4*)(in + (size_t)m * K + k0);
+  out[chunk] = v;
+}
+
 template <typename T>
-static void transpose_into(const void* in, void* out, int K, int N, int ld, int col0, hipStream_t s) {
+static void transpose_into(const void* in, void* out, int K, int N, int ld, int col0, hipStream_t s, int nb_stride = 1, int nb_off = 0) {
+  if (sizeof(T) == 2) {
+    const size_t total = (size_t)(N >> 5) * (K >> 4) * 64;
+    hipLaunchKernelGGL(k_pack_w, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const bf16_t*)in, (uint4*)out, K, N, ld, col0,
+                       nb_stride, nb_off);
+    return;
+  }
   dim3 grid((N + 31) / 32, (K + 31) / 32);
   hipLaunchKernelGGL(k_transpose<T>, grid, dim3(32, 8), 0, s, (const T*)in, (T*)out, K, N, ld, col0);
 }
@@ -78,8 +120,13 @@ static void pack_weights_t(Ctx* c, const void* const* t, hipStream_t s) {
     transpose_into<T>(w[4], c->pw + base + c->p.wo, d, d, d, 0, s);
     gain(w[5], base + c->p.g2);
     char* gu = c->pw + base + c->p.wgu;
-    transpose_into<T>(w[6], gu, d, F, F, 0, s);
-    transpose_into<T>(w[7], gu + (size_t)F * d * sizeof(T), d, F, F, 0, s);
+    if (sizeof(T) == 2) {            // bf16: gate / up interleaved in blocks of 32 output features
+      transpose_into<T>(w[6], gu, d, F, F, 0, s, 2, 0);
+      transpose_into<T>(w[7], gu, d, F, F, 0, s, 2, 1);
+    } else {
+      transpose_into<T>(w[6], gu, d, F, F, 0, s);
+      transpose_into<T>(w[7], gu + (size_t)F * d * sizeof(T), d, F, F, 0, s);
+    }
     transpose_into<T>(w[8], c->pw + base + c->p.wd, F, d, d, 0, s);
   }
   const void* const* tail = t + 2 + 9 * c->L;
@@ -164,8 +211,12 @@ __global__ void k_add_rmsnorm(float* __restrict__ x, const float* __restrict__ p
   }
   ss = block_sum(ss, red);
   const float scale = 1.0f / sqrtf(ss / (float)d + eps);
-  T* hr = h + (size_t)blockIdx.x * d;
-  for (int k = threadIdx.x; k < d; k += blockDim.x) st(hr + k, xr[k] * scale * g[k]);
+  for (int k0 = threadIdx.x * 8; k0 < d; k0 += blockDim.x * 8) {
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = xr[k0 + i] * scale * g[k0 + i];
+    store8(h, (int)blockIdx.x, k0, d, v);
+  }
 }
 
 // ------------------------------------------------------------------------------------------------ RoPE + KV write
@@ -252,17 +303,25 @@ __global__ void k_attn_simple(const T* __restrict__ q, const T* __restrict__ kc,
 
 // ------------------------------------------------------------------------------------------------ SwiGLU
 template <typename T>
-__global__ void k_swiglu(const float* __restrict__ gu, int splits, size_t split_stride, T* __restrict__ act, int M, int F) {
-  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= (size_t)M * F) return;
-  const size_t m = i / F, f = i % F;
-  float g = 0.f, u = 0.f;
+__global__ void k_swiglu(const float* __restrict__ gu, int splits, size_t split_stride, T* __restrict__ act, int M, int F,
+                         int interleaved) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;      // one thread per 8 consecutive f
+  const int per_row = F >> 3;
+  if (i >= (size_t)M * per_row) return;
+  const int m = (int)(i / per_row), f0 = (int)(i % per_row) * 8;
+  float g[8], u[8], v[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) g[k] = u[k] = 0.f;
   for (int s = 0; s < splits; ++s) {
-    const float* row = gu + s * split_stride + m * 2 * F;
-    g += row[f];
-    u += row[F + f];
+    const float* row = gu + s * split_stride + (size_t)m * 2 * F;
+    // column of gate unit f: f (then up at F + f), or interleaved in blocks of 32: (f/32)*64 + f%32 (up 32 further)
+    const int gc = interleaved ? (f0 >> 5) * 64 + (f0 & 31) : f0, uc = interleaved ? gc + 32 : F + f0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) { g[k] += row[gc + k]; u[k] += row[uc + k]; }
   }
-  st(act + i, g / (1.0f + expf(-g)) * u);
+#pragma unroll
+  for (int k = 0; k < 8; ++k) v[k] = g[k] / (1.0f + expf(-g[k])) * u[k];
+  store8(act, m, f0, F, v);
 }
 
 // ------------------------------------------------------------------------------------------------ GEMM, one wave per output column
@@ -288,26 +347,17 @@ __global__ void k_gemm_simple(const T* __restrict__ A, const T* __restrict__ W, 
   }
 }
 
-static bool force_simple() {
-  static int v = -1;
-  if (v < 0) { const char* e = getenv("VVS_FORCE_SIMPLE"); v = (e && e[0] == '1') ? 1 : 0; }
-  return v == 1;
-}
-
-// C[splits][M][N] (fp32 partial sums) = A[M][K] * W[N][K]^T
+// C[splits][M][N] (fp32 partial sums) = A[M][K] * W[N][K]^T (bf16: both operands in packed fragment order)
 static int run_gemm(Ctx* c, const void* A, const void* W, float* C, int M, int N, int K, bool allow_split, hipStream_t s) {
   GemmPlan p = plan_gemm(c, M, N, K);
   if (!allow_split) p.splits = 1;
   Timed timed(c, VVS_K_GEMM, s);
-  if (c->cfg.dtype == VVS_BF16 && !force_simple()) {
+  if (c->cfg.dtype == VVS_BF16) {
     mfma_gemm((const bf16_t*)A, (const bf16_t*)W, C, M, N, K, p, s);
     return p.splits;
   }
   dim3 grid((N + 3) / 4, (M + 7) / 8);
-  if (c->cfg.dtype == VVS_BF16)
-    hipLaunchKernelGGL(k_gemm_simple<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)A, (const bf16_t*)W, C, M, N, K);
-  else
-    hipLaunchKernelGGL(k_gemm_simple<float>, grid, dim3(256), 0, s, (const float*)A, (const float*)W, C, M, N, K);
+  hipLaunchKernelGGL(k_gemm_simple<float>, grid, dim3(256), 0, s, (const float*)A, (const float*)W, C, M, N, K);
   return 1;
 }
 
@@ -339,12 +389,18 @@ static void forward_t(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, 
     hipLaunchKernelGGL(k_add_rmsnorm<T>, dim3(M), dim3(256), 0, s, x, go, splits, sstride, d, (const float*)(lw + c->p.g1),
                        c->cfg.rms_eps, h, 1, 0);
     }
-    int sp = run_gemm(c, h, lw + c->p.wqkv, go, M, 3 * d, d, true, s);
-    { Timed timed(c, VVS_K_ELEMENTWISE, s);
-    hipLaunchKernelGGL(k_rope_kv<T>, dim3(M), dim3(256), 0, s, go, sp, (size_t)M * 3 * d, q, kc, vc, rope, tree, pos, Tq, d, c->dh,
-                       c->kv_row_stride, c->kv_head_stride, c->S_cap, c->rope_pos);
+    int sp;
+    GemmPlan pq = plan_gemm(c, M, 3 * d, d);
+    if (c->cfg.dtype == VVS_BF16 && pq.splits == 1) {
+      Timed timed(c, VVS_K_GEMM, s);           // projection + rotary + cache write in one kernel
+      mfma_gemm_qkv(c, l, (const bf16_t*)h, (const bf16_t*)(lw + c->p.wqkv), tree, pos, Tq, pq, s);
+    } else {
+      sp = run_gemm(c, h, lw + c->p.wqkv, go, M, 3 * d, d, true, s);
+      Timed timed(c, VVS_K_ELEMENTWISE, s);
+      hipLaunchKernelGGL(k_rope_kv<T>, dim3(M), dim3(256), 0, s, go, sp, (size_t)M * 3 * d, q, kc, vc, rope, tree, pos, Tq, d, c->dh,
+                         c->kv_row_stride, c->kv_head_stride, c->S_cap, c->rope_pos);
     }
-    if (c->cfg.dtype == VVS_BF16 && !force_simple()) {
+    if (c->cfg.dtype == VVS_BF16) {
       Timed timed(c, VVS_K_ATTENTION, s);
       mfma_attention(c, l, tree, pos, Tq, s);
     } else {
@@ -358,12 +414,16 @@ static void forward_t(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, 
     hipLaunchKernelGGL(k_add_rmsnorm<T>, dim3(M), dim3(256), 0, s, x, go, sp, (size_t)M * d, d, (const float*)(lw + c->p.g2),
                        c->cfg.rms_eps, h, 1, 0);
     }
-    sp = run_gemm(c, h, lw + c->p.wgu, go, M, 2 * F, d, true, s);
-    {
-      size_t n = (size_t)M * F;
-      { Timed timed(c, VVS_K_ELEMENTWISE, s);
-      hipLaunchKernelGGL(k_swiglu<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, go, sp, (size_t)M * 2 * F, act, M, F);
-      }
+    GemmPlan pg = plan_gemm(c, M, 2 * F, d);
+    if (c->cfg.dtype == VVS_BF16 && pg.splits == 1) {
+      Timed timed(c, VVS_K_GEMM, s);           // projection + SwiGLU in one kernel
+      mfma_gemm_swiglu((const bf16_t*)h, (const bf16_t*)(lw + c->p.wgu), (bf16_t*)act, M, F, d, pg, s);
+    } else {
+      sp = run_gemm(c, h, lw + c->p.wgu, go, M, 2 * F, d, true, s);
+      size_t n = (size_t)M * (F / 8);
+      Timed timed(c, VVS_K_ELEMENTWISE, s);
+      hipLaunchKernelGGL(k_swiglu<T>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, go, sp, (size_t)M * 2 * F, act, M, F,
+                         c->cfg.dtype == VVS_BF16 ? 1 : 0);
     }
     splits = run_gemm(c, act, lw + c->p.wd, go, M, d, F, true, s);
     sstride = (size_t)M * d;
@@ -514,9 +574,16 @@ __global__ void k_sum_splits(const float* __restrict__ part, int splits, size_t 
 
 void launch_debug_gemm(Ctx* c, int m, int n, int k, const void* a, const void* w, void* scratch, float* out, hipStream_t s) {
   char* wt = (char*)scratch;
-  float* part = (float*)(wt + align_up((size_t)n * k * c->esz, 256));
-  if (c->cfg.dtype == VVS_BF16) transpose_into<bf16_t>(w, wt, k, n, n, 0, s);
-  else transpose_into<float>(w, wt, k, n, n, 0, s);
+  char* at = wt + align_up((size_t)n * k * c->esz, 256);
+  float* part = (float*)(at + align_up((size_t)align_up(m, 32) * k * c->esz, 256));
+  if (c->cfg.dtype == VVS_BF16) {
+    transpose_into<bf16_t>(w, wt, k, n, n, 0, s);
+    const size_t total = (size_t)((m + 31) >> 5) * (k >> 4) * 64;
+    hipLaunchKernelGGL(k_pack_a, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const bf16_t*)a, (uint4*)at, m, k);
+    a = at;
+  } else {
+    transpose_into<float>(w, wt, k, n, n, 0, s);
+  }
   int sp = run_gemm(c, a, wt, part, m, n, k, true, s);
   size_t cnt = (size_t)m * n;
   hipLaunchKernelGGL(k_sum_splits, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, s, part, sp, cnt, out);

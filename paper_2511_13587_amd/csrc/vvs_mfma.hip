@@ -18,23 +18,52 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // ------------------------------------------------------------------------------------------------ GEMM
-// C[split][M][N] (fp32) = A[M][K] (bf16, row-major) * W[N][K]^T (bf16, K contiguous), K range of the
-// split.  Workgroup tile BM x BN, 4 waves as 2 x 2, each wave (BM/2) x (BN/2) in 32x32x16 MFMA tiles;
-// BK = 64 staged through LDS (row stride 72 elements: conflict-free 16-byte fragment reads), the next
-// tile's global loads are in flight while the current one is multiplied.
-template <int BM, int BN>
-__global__ __launch_bounds__(256) void k_gemm_mfma(const bf16_t* __restrict__ A, const bf16_t* __restrict__ W, float* __restrict__ C,
-                                                   int M, int N, int K, int kt_per_split) {
-  constexpr int BK = 64, LS = BK + 8;
-  constexpr int TM = BM / 64, TN = BN / 64;
-  constexpr int AP = BM / 32, BP = BN / 32;
-  __shared__ __attribute__((aligned(16))) bf16_t sA[BM * LS];
-  __shared__ __attribute__((aligned(16))) bf16_t sB[BN * LS];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN, split = blockIdx.z;
-  const int kt_total = K / BK;
-  const int kt0 = split * kt_per_split, kt1 = min(kt_total, kt0 + kt_per_split);
+// C[split][M][N] (fp32) = A[M][K] * W[N][K]^T with both operands pre-packed in MFMA fragment order:
+//   block (rb, kb) of a matrix with rows r and contraction index k = 64 lanes x 8 bf16 (1 KiB,
+//   contiguous); lane l holds row rb*32 + l%32, k = kb*16 + 8*(l/32) .. +8.        (pack_index)
+// A workgroup owns a (TM*32) x (TN*32) output tile.  Its 4 waves split the K range between them and
+// each wave streams ITS OWN A and B fragments straight from global memory into MFMA operand
+// registers - 1 KiB fully coalesced per load instruction, D k-steps in flight per wave, no LDS and
+// no barrier in the main loop (at these sizes a projection is bound by memory latency, not by MFMA
+// rate: the whole weight matrix is only a few MB, so what matters is how many bytes every CU keeps
+// in flight).  The 4 partial tiles are summed through LDS at the end, in a fixed order.
+//
+// Epilogues (after the 4-way sum):
+//   EPI_PARTIAL: store the fp32 tile to C[split] (consumers add the splits);
+//   EPI_SWIGLU : the weight rows are interleaved so that tile columns 0..31 are gate and 32..63 up
+//                outputs of the same 32 hidden units: write silu(gate) * up as the packed bf16
+//                operand of the down projection (one K split only);
+//   EPI_QKV    : the tile lies inside the q, k or v third of the fused projection: apply the 2D
+//                rotary embedding to q and k, write q (bf16 row-major) and put k / v into the cache
+//                slots of their tokens (one K split only).
+enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_QKV = 2 };
+
+struct GemmEpi {
+  bf16_t* act; int F;                                      // EPI_SWIGLU
+  bf16_t* q; bf16_t* kc; bf16_t* vc; const float* rope;    // EPI_QKV
+  int T, d, dh, S_cap, rope_pos;
+  size_t row_stride, head_stride;
+  PosDesc pos;
+  TreeDesc tree;
+};
+
+template <int TM, int TN, int D, int EPI>
+__global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ Ap, const uint4* __restrict__ Wp, float* __restrict__ C,
+                                                     int M, int N, int K, int kb_per_split, const GemmEpi ep) {
+  constexpr int BM = TM * 32, BN = TN * 32, LDC = BN + 4;
+  extern __shared__ float red[];           // [4][BM][LDC]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int KB = K >> 4;
+  const int s0 = blockIdx.z * kb_per_split, s1 = min(KB, s0 + kb_per_split);
+  const int per_w = (max(s1 - s0, 0) + 3) >> 2;
+  const int w0 = s0 + wave * per_w, w1 = min(s1, w0 + per_w);
+  const int nk = max(w1 - w0, 0);
+  const uint4* ap[TM];
+  const uint4* bp[TN];
+#pragma unroll
+  for (int t = 0; t < TM; ++t) ap[t] = Ap + ((size_t)(blockIdx.y * TM + t) * KB) * 64 + lane;
+#pragma unroll
+  for (int t = 0; t < TN; ++t) bp[t] = Wp + ((size_t)(blockIdx.x * TN + t) * KB) * 64 + lane;
   floatx16 acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -42,85 +71,166 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const bf16_t* __restrict__ A,
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-  // staging: each thread moves one 16-byte chunk per 32 tile rows (named registers, not arrays, so
-  // that they stay in VGPRs)
-  const int lrow = tid >> 3, lchunk = tid & 7;
-  const bf16_t* pa = A + lchunk * 8;
-  const bf16_t* pb = W + (size_t)(n0 + lrow) * K + lchunk * 8;
-  const size_t ar0 = (size_t)min(m0 + lrow, M - 1) * K, ar1 = (size_t)min(m0 + 32 + lrow, M - 1) * K;
-  const size_t ar2 = (size_t)min(m0 + 64 + lrow, M - 1) * K, ar3 = (size_t)min(m0 + 96 + lrow, M - 1) * K;
-  const size_t br = (size_t)32 * K;
-  uint4 ra0, ra1, ra2, ra3, rb0, rb1, rb2, rb3;
-  ra2 = ra3 = rb2 = rb3 = make_uint4(0, 0, 0, 0);
-#define VVS_GLOAD(kt)                                              \
-  {                                                                \
-    const size_t ko = (size_t)(kt) * BK;                           \
-    ra0 = *(const uint4*)(pa + ar0 + ko);                          \
-    ra1 = *(const uint4*)(pa + ar1 + ko);                          \
-    if (AP > 2) {                                                  \
-      ra2 = *(const uint4*)(pa + ar2 + ko);                        \
-      ra3 = *(const uint4*)(pa + ar3 + ko);                        \
-    }                                                              \
-    rb0 = *(const uint4*)(pb + ko);                                \
-    rb1 = *(const uint4*)(pb + br + ko);                           \
-    if (BP > 2) {                                                  \
-      rb2 = *(const uint4*)(pb + 2 * br + ko);                     \
-      rb3 = *(const uint4*)(pb + 3 * br + ko);                     \
-    }                                                              \
+  uint4 fa[D][TM], fb[D][TN];
+#pragma unroll
+  for (int i = 0; i < D; ++i) {
+    const size_t kk = (size_t)min(w0 + i, KB - 1) * 64;      // clamped: loads past the range are unused
+#pragma unroll
+    for (int t = 0; t < TM; ++t) fa[i][t] = ap[t][kk];
+#pragma unroll
+    for (int t = 0; t < TN; ++t) fb[i][t] = bp[t][kk];
+    // keep the load groups in program order: the wait before a k-step's MFMAs is then "all but the
+    // (D-1) younger groups", never "everything"
+    __builtin_amdgcn_sched_barrier(0);
   }
-  VVS_GLOAD(min(kt0, kt_total - 1));
-  for (int kt = kt0; kt < kt1; ++kt) {
-    __syncthreads();
-    {
-      bf16_t* da = sA + lrow * LS + lchunk * 8;
-      bf16_t* db = sB + lrow * LS + lchunk * 8;
-      *(uint4*)(da) = ra0;
-      *(uint4*)(da + 32 * LS) = ra1;
-      if (AP > 2) { *(uint4*)(da + 64 * LS) = ra2; *(uint4*)(da + 96 * LS) = ra3; }
-      *(uint4*)(db) = rb0;
-      *(uint4*)(db + 32 * LS) = rb1;
-      if (BP > 2) { *(uint4*)(db + 64 * LS) = rb2; *(uint4*)(db + 96 * LS) = rb3; }
-    }
-    __syncthreads();
-    VVS_GLOAD(min(kt + 1, kt1 - 1));   // the last iteration re-reads its own tile (no branch around the loads)
+  for (int kb = 0; kb < nk; kb += D) {
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 af[TM], bfr[TN];
-      const int koff = ks * 16 + (lane >> 5) * 8;
+    for (int i = 0; i < D; ++i) {
+      if (kb + i < nk) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
-        af[i] = as_bf16x8(*(const uint4*)(sA + (wm * (BM / 2) + i * 32 + (lane & 31)) * LS + koff));
+        for (int ti = 0; ti < TM; ++ti)
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
-        bfr[j] = as_bf16x8(*(const uint4*)(sB + (wn * (BN / 2) + j * 32 + (lane & 31)) * LS + koff));
+          for (int tj = 0; tj < TN; ++tj)
+            acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(fa[i][ti]), as_bf16x8(fb[i][tj]), acc[ti][tj], 0, 0, 0);
+      }
+      const size_t kk = (size_t)min(w0 + kb + i + D, KB - 1) * 64;
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+      for (int t = 0; t < TM; ++t) fa[i][t] = ap[t][kk];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+      for (int t = 0; t < TN; ++t) fb[i][t] = bp[t][kk];
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
-#undef VVS_GLOAD
-  float* Cs = C + (size_t)split * M * N;
+  // publish the partial tile: acc[i][j][r] is row i*32 + 8*(r/4) + 4*(lane/32) + r%4, col j*32 + lane%32
+  float* mine = red + (size_t)wave * BM * LDC;
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int n = n0 + wn * (BN / 2) + j * 32 + (lane & 31);
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = m0 + wm * (BM / 2) + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-        if (m < M) Cs[(size_t)m * N + n] = acc[i][j][r];
+      for (int r = 0; r < 16; ++r)
+        mine[(i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * LDC + j * 32 + (lane & 31)] = acc[i][j][r];
+  __syncthreads();
+  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  constexpr int PS = BM * LDC;   // stride between the waves' partial tiles
+  if constexpr (EPI == EPI_PARTIAL) {
+    float* Cs = C + (size_t)blockIdx.z * M * N;
+    for (int e = threadIdx.x; e < BM * BN; e += 256) {
+      const int row = e / BN, col = e % BN;
+      const float* p = red + row * LDC + col;
+      const float v = ((p[0] + p[PS]) + p[2 * PS]) + p[3 * PS];
+      if (m0 + row < M) Cs[(size_t)(m0 + row) * N + n0 + col] = v;
+    }
+  } else if constexpr (EPI == EPI_SWIGLU) {
+    static_assert(TN == 2, "gate / up interleave assumes a 64-column tile");
+    for (int u = threadIdx.x; u < BM * 4; u += 256) {       // one unit = (row, 8 consecutive hidden units)
+      const int row = u >> 2, f8 = (u & 3) * 8;
+      if (m0 + row >= M) continue;
+      const float* pg = red + row * LDC + f8;
+      float v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float g = ((pg[i] + pg[i + PS]) + pg[i + 2 * PS]) + pg[i + 3 * PS];
+        const float up = ((pg[32 + i] + pg[32 + i + PS]) + pg[32 + i + 2 * PS]) + pg[32 + i + 3 * PS];
+        v[i] = g / (1.0f + expf(-g)) * up;
+      }
+      store8(ep.act, m0 + row, blockIdx.x * 32 + f8, ep.F, v);
+    }
+  } else {
+    const int half = ep.dh >> 1, np = ep.dh >> 2;
+    for (int u = threadIdx.x; u < BM * (BN / 16); u += 256) {   // one unit = (row, 16 consecutive columns)
+      const int row = u / (BN / 16), c0 = (u % (BN / 16)) * 16;
+      const int m = m0 + row;
+      if (m >= M) continue;
+      const float* p = red + row * LDC + c0;
+      float v[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) v[i] = ((p[i] + p[i + PS]) + p[i + 2 * PS]) + p[i + 3 * PS];
+      const int n = n0 + c0, sec = n / ep.d, eg = n % ep.d, hd = eg / ep.dh, e = eg % ep.dh;
+      const int r = m / ep.T, t = m % ep.T;
+      int slot, img;
+      token_pos(ep.pos, ep.tree, r, t, &slot, &img);
+      if (sec < 2 && img >= 0) {
+        const int gr = min(img / ep.pos.grid_w, ep.rope_pos - 1), gc = img % ep.pos.grid_w;
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+          const int ei = e + i, pv = (ei / half) ? gc : gr, ip = (ei % half) >> 1;
+          const float cs = ep.rope[((size_t)pv * np + ip) * 2], sn = ep.rope[((size_t)pv * np + ip) * 2 + 1];
+          const float a = v[i], b = v[i + 1];
+          v[i] = a * cs - b * sn;
+          v[i + 1] = a * sn + b * cs;
+        }
+      }
+      uint32_t w[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) w[i] = (uint32_t)f2bf(v[2 * i]) | ((uint32_t)f2bf(v[2 * i + 1]) << 16);
+      if (sec == 0) {
+        uint4* dst = (uint4*)(ep.q + (size_t)m * ep.d + eg);
+        dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+        dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+      } else if (slot >= 0 && slot < ep.S_cap) {
+        const size_t hb = (size_t)r * ep.row_stride + (size_t)hd * ep.head_stride;
+        if (sec == 1) {
+          uint4* dst = (uint4*)(ep.kc + hb + (size_t)slot * ep.dh + e);
+          dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+          dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+        } else {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) ep.vc[hb + v_index(slot, e + i, ep.dh)] = (bf16_t)(w[i >> 1] >> ((i & 1) * 16));
+        }
       }
     }
+  }
+}
+
+template <int TM, int TN, int D, int EPI>
+static void launch_gemm_direct(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, int splits, const GemmEpi& ep,
+                               hipStream_t s) {
+  constexpr size_t lds = (size_t)4 * TM * 32 * (TN * 32 + 4) * sizeof(float);
+  static bool configured = false;
+  if (!configured) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_direct<TM, TN, D, EPI>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)lds);
+    configured = true;
+  }
+  const int KB = K / 16;
+  const int per = (KB + splits - 1) / splits;
+  dim3 grid(N / (TN * 32), (M + TM * 32 - 1) / (TM * 32), splits);
+  hipLaunchKernelGGL((k_gemm_direct<TM, TN, D, EPI>), grid, dim3(256), lds, s, (const uint4*)A, (const uint4*)W, C, M, N, K, per, ep);
+}
+
+template <int EPI>
+static void gemm_dispatch(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, GemmPlan p, const GemmEpi& ep, hipStream_t s) {
+  if (p.bm == 32) launch_gemm_direct<1, 2, 8, EPI>(A, W, C, M, N, K, p.splits, ep, s);
+  else launch_gemm_direct<2, 2, 6, EPI>(A, W, C, M, N, K, p.splits, ep, s);
 }
 
 void mfma_gemm(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, GemmPlan p, hipStream_t s) {
-  const int kt = K / 64;
-  const int per = (kt + p.splits - 1) / p.splits;
-  dim3 grid(N / p.bn, (M + p.bm - 1) / p.bm, p.splits);
-  if (p.bm == 128 && p.bn == 128) hipLaunchKernelGGL((k_gemm_mfma<128, 128>), grid, dim3(256), 0, s, A, W, C, M, N, K, per);
-  else if (p.bm == 64 && p.bn == 128) hipLaunchKernelGGL((k_gemm_mfma<64, 128>), grid, dim3(256), 0, s, A, W, C, M, N, K, per);
-  else hipLaunchKernelGGL((k_gemm_mfma<64, 64>), grid, dim3(256), 0, s, A, W, C, M, N, K, per);
+  GemmEpi ep{};
+  gemm_dispatch<EPI_PARTIAL>(A, W, C, M, N, K, p, ep, s);
+}
+
+// gate/up projection with the SwiGLU epilogue: act = silu(h Wg) * (h Wu), packed bf16 [M][F]
+void mfma_gemm_swiglu(const bf16_t* A, const bf16_t* Wgu, bf16_t* act, int M, int F, int K, GemmPlan p, hipStream_t s) {
+  GemmEpi ep{};
+  ep.act = act; ep.F = F;
+  p.splits = 1;
+  gemm_dispatch<EPI_SWIGLU>(A, Wgu, nullptr, M, 2 * F, K, p, ep, s);
+}
+
+// fused q/k/v projection with the rotary + cache-write epilogue
+void mfma_gemm_qkv(Ctx* c, int layer, const bf16_t* A, const bf16_t* Wqkv, const TreeDesc& tree, const PosDesc& pos, int T, GemmPlan p,
+                   hipStream_t s) {
+  GemmEpi ep{};
+  ep.q = (bf16_t*)(c->ws + c->w.q);
+  ep.kc = (bf16_t*)c->kv + c->kv_layer_stride * layer;
+  ep.vc = (bf16_t*)c->kv + c->kv_v_off + c->kv_layer_stride * layer;
+  ep.rope = (const float*)(c->ws + c->w.rope_tab);
+  ep.T = T; ep.d = c->d; ep.dh = c->dh; ep.S_cap = c->S_cap; ep.rope_pos = c->rope_pos;
+  ep.row_stride = c->kv_row_stride; ep.head_stride = c->kv_head_stride;
+  ep.pos = pos; ep.tree = tree;
+  p.splits = 1;
+  gemm_dispatch<EPI_QKV>(A, Wqkv, nullptr, c->R * T, 3 * c->d, c->d, p, ep, s);
 }
 
 // ------------------------------------------------------------------------------------------------ attention
@@ -279,7 +389,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
             }
             pk[rr >> 1] = (uint32_t)f2bf(v0 * inv) | ((uint32_t)f2bf(v1 * inv) << 16);
           }
-          *(uint2*)(out + ((size_t)r * T + qi) * d + (size_t)hd * DH + dt * 16 + 4 * g) = make_uint2(pk[0], pk[1]);
+          *(uint2*)(out + pack_index(r * T + qi, hd * DH + dt * 16 + 4 * g, d)) = make_uint2(pk[0], pk[1]);   // O-projection operand layout
         }
       }
     }
