@@ -88,34 +88,40 @@ def algorithmic_counts(shape, S_mean):
                 attn_flops=attn_flops, M=M)
 
 
-def cpu_baseline(shape, weights, synth, n_forced, log_fn):
-    """The CPU checker as it stands, timed on a bounded sample: ONE prompt (2 CFG rows) of the same
-    workload, same draft tree, short cache (prefix + n_forced image tokens).  Only verify + commit are
-    timed; the value is emitted tokens per second of that call."""
+def cpu_baseline(shape, weights, synth, n_forced, u_first, parent, q, toks, u, mode, nbr, log_fn, n_sample=2, reps=5):
+    """The CPU checker as it stands, timed on a bounded sample of the same workload: the first
+    n_sample prompts (2 CFG rows each) at the same cache length, with the same tree, draft
+    distributions, drafted tokens and uniforms as the GPU run.  The prefill that builds the cache is
+    not timed; verify is timed `reps` times (it does not change the cache), commit once."""
     from oracle import vvs_oracle as vo
     try:
         from threadpoolctl import threadpool_info
         threads = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [os.cpu_count()])
     except Exception:
         threads = os.cpu_count()
-    s1 = shape.replace(n_prompts=1)
+    n_sample = min(n_sample, shape.n_prompts)
+    s1 = shape.replace(n_prompts=n_sample)
     o = vo.Oracle(dataclasses.asdict(s1), weights)
-    pc, pu = synth.make_prefix(s1)
+    if nbr is not None:
+        o.set_neighbors(nbr)
+    pc, pu = synth.make_prefix(shape)
+    forced = synth.make_forced_tokens(shape, n_forced) if n_forced > 0 else None
     t0 = time.perf_counter()
-    o.prefill(pc, pu, synth.make_forced_tokens(s1, n_forced), np.array([0.5]))
-    log_fn(f"cpu baseline: prefill of the sample took {time.perf_counter() - t0:.1f} s (not counted)")
-    parent = synth.tree_parents(s1.tree_widths, s1.n_nodes)
-    q, toks = synth.make_draft(s1, parent, 0)
-    u = synth.make_uniforms(s1, s1.n_nodes, 0)
+    o.prefill(pc[:n_sample], pu, None if forced is None else forced[:n_sample], u_first[:n_sample])
+    log_fn(f"cpu baseline: building the cache of the sample took {time.perf_counter() - t0:.1f} s (not counted)")
     t0 = time.perf_counter()
-    a, _, _ = o.verify(parent, toks, q, u)
+    for _ in range(reps):
+        a, _, _ = o.verify(parent, toks[:n_sample], q[:n_sample], u[:n_sample], mode)
+    t_verify = (time.perf_counter() - t0) / reps
+    t0 = time.perf_counter()
     o.kv_commit()
-    dt = time.perf_counter() - t0
+    t_commit = time.perf_counter() - t0
+    dt = t_verify + t_commit
     emitted = float(a.sum() + len(a))
     return {"value": emitted / dt, "unit": "verified tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"1 of {shape.n_prompts} prompts (2 CFG rows), same {s1.n_nodes}-node tree, cache length "
-                      f"{s1.prefix_len}+{n_forced}; verify+commit took {dt:.2f} s for {emitted:.0f} emitted / "
-                      f"{s1.n_nodes} scored draft tokens"}
+            "sample": f"{n_sample} of {shape.n_prompts} prompts ({2 * n_sample} CFG rows), same {s1.n_nodes}-node tree, drafts and "
+                      f"uniforms as the GPU run, cache length {s1.prefix_len}+{n_forced}; verify {t_verify:.2f} s (mean of {reps}) + "
+                      f"commit {t_commit:.3f} s for {emitted:.0f} emitted / {n_sample * s1.n_nodes} scored draft tokens"}
 
 
 def main():
@@ -165,7 +171,8 @@ def main():
         dpc, dpu = vb.to_device(pc, shape.dtype), vb.to_device(pu, shape.dtype)
     forced = torch.from_numpy(synth.make_forced_tokens(shape, n_forced)).to(dev) if n_forced > 0 else None
     first = torch.zeros(B, dtype=torch.int32, device=dev)
-    u0 = torch.from_numpy(np.random.default_rng(1).random(B, dtype=np.float32)).to(dev)
+    u0_host = np.random.default_rng(1).random(B, dtype=np.float32)
+    u0 = torch.from_numpy(u0_host).to(dev)
     t0 = time.perf_counter()
     ctx.vvs_prefill(dpc, dpu, forced, u0, first)
     torch.cuda.synchronize()
@@ -256,7 +263,8 @@ def main():
     del ctx
     if not args.no_cpu_baseline:
         try:
-            out["cpu_baseline"] = cpu_baseline(shape, weights, synth, 32, log)
+            nbr_host = synth.make_codebook_neighbours(shape.vocab, shape.relax_k) if shape.relax_k else None
+            out["cpu_baseline"] = cpu_baseline(shape, weights, synth, n_forced, u0_host, parent, q, toks, u, mode, nbr_host, log)
         except MemoryError as e:           # pragma: no cover
             out["cpu_baseline"] = {"value": None, "unit": "verified tokens/s", "cores": os.cpu_count(), "kind": "oracle",
                                    "sample": f"failed: {e}"}

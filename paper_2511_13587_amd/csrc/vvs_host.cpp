@@ -58,6 +58,7 @@ vvs_status plan_sizes(const vvs_config* cfg, Ctx* c, std::string* err) {
   int dh = g.d_model / g.n_heads;
   if (dh % 4) return fail(err, VVS_ESIZE, "config: head size must be a multiple of 4 (2D rotary pairs)");
   if (g.d_model % 8 || g.d_ff % 8) return fail(err, VVS_ESIZE, "config: d_model and d_ff must be multiples of 8");
+  if (g.d_model > 16384) return fail(err, VVS_ESIZE, "config: d_model above 16384 is not supported");
   if (dh > 256) return fail(err, VVS_ESIZE, "config: head size above 256 is not supported");
   int veff = g.logit_hi - g.logit_lo;
   if (g.dtype == VVS_BF16) {

@@ -194,29 +194,64 @@ void launch_build_tokens(Ctx* c, int T, const int32_t* d_draft, hipStream_t s) {
 // ------------------------------------------------------------------------------------------------ residual add + RMSNorm
 // Output row i reads x row (i * in_stride + in_off): x_row += sum of GEMM partials (if any), then
 // h_row = x_row / sqrt(mean(x_row^2) + eps) * g, rounded to the operand type.
-template <typename T>
-__global__ void k_add_rmsnorm(float* __restrict__ x, const float* __restrict__ partial, int splits, size_t split_stride, int d,
-                              const float* __restrict__ g, float eps, T* __restrict__ h, int in_stride, int in_off) {
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void k_add_rmsnorm(float* __restrict__ x, const float* __restrict__ partial, int splits,
+                                                     size_t split_stride, int d, const float* __restrict__ g, float eps,
+                                                     T* __restrict__ h, int in_stride, int in_off) {
+  // each thread owns NCH chunks of 8 consecutive values of the row (d <= NCH * 2048) and keeps them in
+  // registers between the sum of squares and the scaling
   __shared__ float red[16];
   const size_t row = (size_t)blockIdx.x * in_stride + in_off;
   float* xr = x + row * d;
+  float xv[NCH][8];
   float ss = 0.f;
-  for (int k = threadIdx.x; k < d; k += blockDim.x) {
-    float v = xr[k];
-    if (splits) {
-      for (int s = 0; s < splits; ++s) v += partial[s * split_stride + row * d + k];
-      xr[k] = v;
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int k0 = (threadIdx.x + 256 * j) * 8;
+    if (k0 < d) {
+      const float4 a = *(const float4*)(xr + k0), b = *(const float4*)(xr + k0 + 4);
+      float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+      if (splits) {
+        for (int s = 0; s < splits; ++s) {
+          const float* pr = partial + s * split_stride + row * d + k0;
+          const float4 pa = *(const float4*)pr, pb = *(const float4*)(pr + 4);
+          v[0] += pa.x; v[1] += pa.y; v[2] += pa.z; v[3] += pa.w; v[4] += pb.x; v[5] += pb.y; v[6] += pb.z; v[7] += pb.w;
+        }
+        *(float4*)(xr + k0) = make_float4(v[0], v[1], v[2], v[3]);
+        *(float4*)(xr + k0 + 4) = make_float4(v[4], v[5], v[6], v[7]);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { xv[j][i] = v[i]; ss += v[i] * v[i]; }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) xv[j][i] = 0.f;
     }
-    ss += v * v;
   }
   ss = block_sum(ss, red);
   const float scale = 1.0f / sqrtf(ss / (float)d + eps);
-  for (int k0 = threadIdx.x * 8; k0 < d; k0 += blockDim.x * 8) {
-    float v[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) v[i] = xr[k0 + i] * scale * g[k0 + i];
-    store8(h, (int)blockIdx.x, k0, d, v);
+  for (int j = 0; j < NCH; ++j) {
+    const int k0 = (threadIdx.x + 256 * j) * 8;
+    if (k0 < d) {
+      const float4 ga = *(const float4*)(g + k0), gb = *(const float4*)(g + k0 + 4);
+      const float gv[8] = {ga.x, ga.y, ga.z, ga.w, gb.x, gb.y, gb.z, gb.w};
+      float v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[i] = xv[j][i] * scale * gv[i];
+      store8(h, (int)blockIdx.x, k0, d, v);
+    }
   }
+}
+
+template <typename T>
+static void launch_add_rmsnorm(int rows, float* x, const float* partial, int splits, size_t split_stride, int d, const float* g, float eps,
+                               T* h, int in_stride, int in_off, hipStream_t s) {
+  if (d <= 2048)
+    hipLaunchKernelGGL((k_add_rmsnorm<T, 1>), dim3(rows), dim3(256), 0, s, x, partial, splits, split_stride, d, g, eps, h, in_stride, in_off);
+  else if (d <= 4096)
+    hipLaunchKernelGGL((k_add_rmsnorm<T, 2>), dim3(rows), dim3(256), 0, s, x, partial, splits, split_stride, d, g, eps, h, in_stride, in_off);
+  else
+    hipLaunchKernelGGL((k_add_rmsnorm<T, 8>), dim3(rows), dim3(256), 0, s, x, partial, splits, split_stride, d, g, eps, h, in_stride, in_off);
 }
 
 // ------------------------------------------------------------------------------------------------ RoPE + KV write
@@ -386,8 +421,7 @@ static void forward_t(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, 
     T* kc = (T*)c->kv + c->kv_layer_stride * l;
     T* vc = (T*)c->kv + c->kv_v_off + c->kv_layer_stride * l;
     { Timed timed(c, VVS_K_ELEMENTWISE, s);
-    hipLaunchKernelGGL(k_add_rmsnorm<T>, dim3(M), dim3(256), 0, s, x, go, splits, sstride, d, (const float*)(lw + c->p.g1),
-                       c->cfg.rms_eps, h, 1, 0);
+    launch_add_rmsnorm<T>(M, x, go, splits, sstride, d, (const float*)(lw + c->p.g1), c->cfg.rms_eps, h, 1, 0, s);
     }
     int sp;
     GemmPlan pq = plan_gemm(c, M, 3 * d, d);
@@ -411,8 +445,7 @@ static void forward_t(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, 
     }
     sp = run_gemm(c, attn, lw + c->p.wo, go, M, d, d, true, s);
     { Timed timed(c, VVS_K_ELEMENTWISE, s);
-    hipLaunchKernelGGL(k_add_rmsnorm<T>, dim3(M), dim3(256), 0, s, x, go, sp, (size_t)M * d, d, (const float*)(lw + c->p.g2),
-                       c->cfg.rms_eps, h, 1, 0);
+    launch_add_rmsnorm<T>(M, x, go, sp, (size_t)M * d, d, (const float*)(lw + c->p.g2), c->cfg.rms_eps, h, 1, 0, s);
     }
     GemmPlan pg = plan_gemm(c, M, 2 * F, d);
     if (c->cfg.dtype == VVS_BF16 && pg.splits == 1) {
@@ -436,12 +469,12 @@ static void forward_t(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, 
   if (logits_mode == 1) {     // every token
     Ml = M;
     { Timed timed(c, VVS_K_ELEMENTWISE, s);
-    hipLaunchKernelGGL(k_add_rmsnorm<T>, dim3(Ml), dim3(256), 0, s, x, go, splits, sstride, d, gf, c->cfg.rms_eps, hf, 1, 0);
+    launch_add_rmsnorm<T>(Ml, x, go, splits, sstride, d, gf, c->cfg.rms_eps, hf, 1, 0, s);
     }
   } else {                    // last token of every row
     Ml = c->R;
     { Timed timed(c, VVS_K_ELEMENTWISE, s);
-    hipLaunchKernelGGL(k_add_rmsnorm<T>, dim3(Ml), dim3(256), 0, s, x, go, splits, sstride, d, gf, c->cfg.rms_eps, hf, Tq, Tq - 1);
+    launch_add_rmsnorm<T>(Ml, x, go, splits, sstride, d, gf, c->cfg.rms_eps, hf, Tq, Tq - 1, s);
     }
   }
   run_gemm(c, hf, c->pw + c->p.wout, logits, Ml, c->veff, d, false, s);

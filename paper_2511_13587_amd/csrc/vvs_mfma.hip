@@ -241,13 +241,13 @@ void mfma_gemm_qkv(Ctx* c, int layer, const bf16_t* A, const bf16_t* Wqkv, const
 // loaded straight from the cache into MFMA operand registers - every key is used by exactly one wave,
 // so there is nothing to share through LDS; the 4 waves take 32-key steps round-robin and merge their
 // partial (max, sum, O) through LDS at the end.  Only the last T keys (the block itself) are masked.
-template <int DH, int NQB>
-__global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc,
+template <int DH, int NQB, int NW>
+__global__ __launch_bounds__(NW * 64) void k_attn_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc,
                                                    const bf16_t* __restrict__ vc, bf16_t* __restrict__ out, TreeDesc tree,
                                                    PosDesc pos, int T, int d, size_t row_stride, size_t head_stride, float c_exp) {
   constexpr int KD = DH / 32, DT = DH / 16, NQ = NQB * 16;
-  __shared__ float s_m[3][NQ], s_l[3][NQ];
-  __shared__ float s_o[3][NQ][DH + 1];
+  __shared__ float s_m[NW - 1][NQ], s_l[NW - 1][NQ];
+  __shared__ float s_o[NW - 1][NQ][DH + 1];
   const int hd = blockIdx.x, r = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = lane >> 4, ql = lane & 15;
@@ -280,18 +280,24 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
     for (int dt = 0; dt < DT; ++dt) o[qb][dt] = floatx4{0.f, 0.f, 0.f, 0.f};
   }
 
-  for (int step = wave; step < nsteps; step += 4) {
+  // K rows / V block of one 32-key step, straight into MFMA operand registers.  S^T tile t, row i holds
+  // key 8*(i/4) + 4*t + i%4 of the step, so that a lane's 8 score values are 8 consecutive keys.
+#define VVS_ATTN_LOAD(STEP, KF, VF)                                                                                   \
+  {                                                                                                                   \
+    _Pragma("unroll") for (int t = 0; t < 2; ++t) {                                                                   \
+      const int key = ((STEP) << 5) + 8 * (ql >> 2) + 4 * t + (ql & 3);                                               \
+      _Pragma("unroll") for (int kd = 0; kd < KD; ++kd)                                                               \
+          KF[t][kd] = as_bf16x8(*(const uint4*)(kb + (size_t)key * DH + kd * 32 + g * 8));                            \
+    }                                                                                                                 \
+    _Pragma("unroll") for (int dt = 0; dt < DT; ++dt)                                                                 \
+        VF[dt] = as_bf16x8(*(const uint4*)(vb + ((size_t)(STEP) * DH + dt * 16 + ql) * 32 + g * 8));                  \
+  }
+  bf16x8 kf[2][KD], vf[DT], kn[2][KD], vn[DT];
+  VVS_ATTN_LOAD(min(wave, nsteps - 1), kf, vf);
+  for (int step = wave; step < nsteps; step += NW) {
     const int key0 = step << 5;
-    bf16x8 kf[2][KD], vf[DT];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int key = key0 + 8 * (ql >> 2) + 4 * t + (ql & 3);
-#pragma unroll
-      for (int kd = 0; kd < KD; ++kd) kf[t][kd] = as_bf16x8(*(const uint4*)(kb + (size_t)key * DH + kd * 32 + g * 8));
-    }
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-      vf[dt] = as_bf16x8(*(const uint4*)(vb + ((size_t)step * DH + dt * 16 + ql) * 32 + g * 8));
+    // next step's operands are requested before this step's are used (the last iteration re-requests its own)
+    VVS_ATTN_LOAD(step + NW < nsteps ? step + NW : step, kn, vn);
     const bool tail = key0 + 32 > S;
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
@@ -343,9 +349,16 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
         o[qb][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf, o[qb][dt], 0, 0, 0);
       }
     }
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int kd = 0; kd < KD; ++kd) kf[t][kd] = kn[t][kd];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) vf[dt] = vn[dt];
   }
+#undef VVS_ATTN_LOAD
 
-  // merge the four waves' partial results (waves 1..3 publish, wave 0 combines and writes)
+  // merge the waves' partial results (waves 1.. publish, wave 0 combines and writes)
   if (wave > 0) {
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
@@ -364,13 +377,13 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
       const int qi = qb * 16 + ql;
       float m = m_run[qb];
 #pragma unroll
-      for (int w = 0; w < 3; ++w) m = fmaxf(m, s_m[w][qi]);
+      for (int w = 0; w < NW - 1; ++w) m = fmaxf(m, s_m[w][qi]);
       const float m_safe = m == -INFINITY ? 0.f : m;
       const float a0 = exp2f((m_run[qb] - m_safe) * c_exp);
       float l = l_run[qb] * a0;
-      float aw[3];
+      float aw[NW - 1];
 #pragma unroll
-      for (int w = 0; w < 3; ++w) {
+      for (int w = 0; w < NW - 1; ++w) {
         aw[w] = exp2f((s_m[w][qi] - m_safe) * c_exp);
         l += s_l[w][qi] * aw[w];
       }
@@ -383,7 +396,7 @@ __global__ __launch_bounds__(256) void k_attn_mfma(const bf16_t* __restrict__ q,
           for (int rr = 0; rr < 4; rr += 2) {
             float v0 = o[qb][dt][rr] * a0, v1 = o[qb][dt][rr + 1] * a0;
 #pragma unroll
-            for (int w = 0; w < 3; ++w) {
+            for (int w = 0; w < NW - 1; ++w) {
               v0 += s_o[w][qi][dt * 16 + 4 * g + rr] * aw[w];
               v1 += s_o[w][qi][dt * 16 + 4 * g + rr + 1] * aw[w];
             }
@@ -404,13 +417,15 @@ void mfma_attention(Ctx* c, int layer, const TreeDesc& tree, const PosDesc& pos,
   const float c_exp = 1.4426950408889634f / sqrtf((float)c->dh);
   dim3 grid(c->H, c->R);
   const int nqb = T <= 16 ? 1 : (T <= 32 ? 2 : 4);
-#define VVS_ATTN(DH, NQB)                                                                                             \
-  hipLaunchKernelGGL((k_attn_mfma<DH, NQB>), grid, dim3(256), 0, s, q, kc, vc, out, tree, pos, T, c->d, c->kv_row_stride, \
+#define VVS_ATTN(DH, NQB, NW)                                                                                                  \
+  hipLaunchKernelGGL((k_attn_mfma<DH, NQB, NW>), grid, dim3(NW * 64), 0, s, q, kc, vc, out, tree, pos, T, c->d, c->kv_row_stride, \
                      c->kv_head_stride, c_exp)
+  // 4 waves per workgroup keep the register footprint low enough for 2-3 workgroups per CU, so that
+  // every (head, row) pair of a call is resident at once
   if (c->dh == 64) {
-    if (nqb == 1) VVS_ATTN(64, 1); else if (nqb == 2) VVS_ATTN(64, 2); else VVS_ATTN(64, 4);
+    if (nqb == 1) VVS_ATTN(64, 1, 4); else if (nqb == 2) VVS_ATTN(64, 2, 4); else VVS_ATTN(64, 4, 4);
   } else {
-    if (nqb == 1) VVS_ATTN(128, 1); else VVS_ATTN(128, 2);   // T <= 32 is enforced at context creation for head size 128
+    if (nqb == 1) VVS_ATTN(128, 1, 4); else VVS_ATTN(128, 2, 4);   // T <= 32 is enforced at context creation for head size 128
   }
 #undef VVS_ATTN
 }

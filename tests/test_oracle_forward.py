@@ -257,3 +257,29 @@ def test_synthetic_tree_shapes():
         assert (np.diag(m) == 1).all() and (m[:, 0] == 1).all() and np.triu(m, 1).sum() == 0
         assert (m.sum(1) == synth.node_depths(parent) + 1).all()
     assert (synth.ancestor_mask(synth.tree_parents(None, 5)) == np.tril(np.ones((6, 6)))).all()
+
+
+def test_bf16_rounding_noise_floor():
+    """Why bf16 shapes are compared with a logit tolerance of a few 1e-2: a relative perturbation of
+    1e-7 (fp32-vs-float64 summation order) in front of the bf16 rounding points is amplified to bf16
+    rounding noise within a couple of layers, while the same perturbation leaves a model without
+    operand rounding unchanged to ~1e-6."""
+    shape = synth.Shape("noise", 2, 256, 4, 512, 512, 0, 512, 8, 8, 4, synth.PREFIX_DENSE, 1, 6, None,
+                        synth.DTYPE_BF16, 7.5, seed=5)
+    w = synth.make_weights(shape)
+    outs = {}
+    for dtype in (synth.DTYPE_BF16, synth.DTYPE_FP32):
+        for eps in (0.0, 1e-7):
+            o = vo.Oracle(dataclasses.asdict(shape.replace(dtype=dtype)), w)
+            if eps:
+                base, rng = o.rb, np.random.default_rng(1)
+                o.rb = lambda x, base=base, rng=rng: base(np.asarray(x, dtype=np.float64) * (1 + eps * rng.standard_normal(np.shape(x))))
+            run_prefill(o, shape, n_forced=10)
+            parent = synth.tree_parents(None, shape.n_nodes)
+            q, toks = synth.make_draft(shape, parent, 0)
+            o.verify(parent, toks, q, synth.make_uniforms(shape, shape.n_nodes, 0))
+            outs[(dtype, eps)] = o.raw_logits.copy()
+    noise_bf16 = np.abs(outs[(1, 1e-7)] - outs[(1, 0.0)]).max()
+    noise_exact = np.abs(outs[(0, 1e-7)] - outs[(0, 0.0)]).max()
+    assert noise_exact < 1e-5
+    assert 1e-3 < noise_bf16 < 3e-2, noise_bf16
