@@ -134,6 +134,8 @@ def main():
     ap.add_argument("--draft-noise", type=float, default=1.0, help="std of the noise between draft and target logits")
     ap.add_argument("--mode", choices=["strict", "relaxed"], default="strict")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch a plain 256 MiB copy kernel (k_copy_bytes) three times, for scaling hardware traffic counters")
     ap.add_argument("--layers", type=int, default=0, help="override depth (debugging only; the result is then not the named workload)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -193,6 +195,13 @@ def main():
         ctx.vvs_verify(N, parent, mask, dtoks, dq, du, mode, bufs["a"], bufs["path"], bufs["next"])
         ctx.vvs_kv_commit()
 
+    if args.calibrate_copy:
+        src = torch.ones(64 << 20, dtype=torch.float32, device=dev)      # 256 MiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            ctx.vvs_debug_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

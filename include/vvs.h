@@ -193,6 +193,10 @@ size_t vvs_debug_gemm_scratch_bytes(const vvs_ctx* ctx, int32_t m, int32_t n, in
 vvs_status vvs_debug_gemm(vvs_ctx* ctx, int32_t m, int32_t n, int32_t k, const void* d_a, const void* d_w,
                           void* d_scratch, float* d_c, vvs_stream s);
 
+/* Plain device-to-device copy of `bytes` bytes (multiple of 16; 16-byte aligned pointers) with one
+ * grid-stride kernel.  Reads and writes exactly `bytes`: used to calibrate hardware traffic counters. */
+vvs_status vvs_debug_copy(vvs_ctx* ctx, void* d_dst, const void* d_src, size_t bytes, vvs_stream s);
+
 #ifdef __cplusplus
 }
 #endif

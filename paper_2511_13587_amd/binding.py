@@ -63,6 +63,7 @@ def _load():
         "vvs_debug_kv": (i32, [vp, i32, i32, i32, vp, vp, vp]),
         "vvs_debug_gemm_scratch_bytes": (sz, [vp, i32, i32, i32]),
         "vvs_debug_gemm": (i32, [vp, i32, i32, i32, vp, vp, vp, vp, vp]),
+        "vvs_debug_copy": (i32, [vp, vp, vp, sz, vp]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)
@@ -241,6 +242,11 @@ class Context:
         v = torch.empty((n_slots, d), dtype=torch.float32, device=self.device)
         self._check(lib.vvs_debug_kv(self.h, layer, row, n_slots, _ptr(k), _ptr(v), _stream()))
         return k, v
+
+    def vvs_debug_copy(self, dst: torch.Tensor, src: torch.Tensor):
+        nbytes = src.numel() * src.element_size()
+        assert dst.numel() * dst.element_size() == nbytes
+        self._check(lib.vvs_debug_copy(self.h, _ptr(dst), _ptr(src), nbytes, _stream()))
 
     def vvs_debug_gemm(self, a: torch.Tensor, w: torch.Tensor, m: int, n: int, k: int) -> torch.Tensor:
         nbytes = lib.vvs_debug_gemm_scratch_bytes(self.h, m, n, k)

@@ -479,6 +479,15 @@ vvs_status vvs_debug_kv(vvs_ctx* ctx, int32_t layer, int32_t row, int32_t n_slot
   return check_launch(c, "debug_kv");
 }
 
+vvs_status vvs_debug_copy(vvs_ctx* ctx, void* d_dst, const void* d_src, size_t bytes, vvs_stream s) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return VVS_EINVAL;
+  if (!d_dst || !d_src || (bytes & 15) || (((uintptr_t)d_dst | (uintptr_t)d_src) & 15))
+    return fail(&c->err, VVS_EINVAL, "debug_copy: pointers and size must be multiples of 16");
+  launch_copy_bytes(d_dst, d_src, bytes, (hipStream_t)s);
+  return check_launch(c, "debug_copy");
+}
+
 size_t vvs_debug_gemm_scratch_bytes(const vvs_ctx* ctx, int32_t m, int32_t n, int32_t k) {
   const Ctx* c = reinterpret_cast<const Ctx*>(ctx);
   if (!c || m < 1 || n < 1 || k < 1) return 0;

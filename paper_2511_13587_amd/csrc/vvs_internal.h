@@ -90,6 +90,7 @@ vvs_status build_tree(int n_nodes, const int32_t* h_parent, const uint8_t* h_mas
 
 // ---- launchers (kernels_*.hip); all asynchronous on the stream
 void launch_fill_zero(void* p, size_t bytes, hipStream_t s);
+void launch_copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t s);
 void launch_pack_weights(Ctx* c, const void* const* tensors, hipStream_t s);
 void launch_forward(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int T, const int32_t* d_tokens_bt,
                     const void* d_prefix_cond, const void* d_prefix_uncond, int chunk_start,

@@ -24,6 +24,19 @@ void launch_fill_zero(void* p, size_t bytes, hipStream_t s) {
   hipLaunchKernelGGL(k_fill_zero, dim3(blocks), dim3(256), 0, s, (uint4*)p, n16);
 }
 
+__global__ void k_copy_bytes(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+void launch_copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t s) {
+  size_t n16 = bytes / 16;
+  if (!n16) return;
+  int blocks = (int)std::min<size_t>((n16 + 255) / 256, 256 * 32);
+  hipLaunchKernelGGL(k_copy_bytes, dim3(blocks), dim3(256), 0, s, (const uint4*)src, (uint4*)dst, n16);
+}
+
 // out[n][k] = in[k][col0 + n]   (in: [K][ld])
 template <typename T>
 __global__ void k_transpose(const T* __restrict__ in, T* __restrict__ out, int K, int N, int ld, int col0) {

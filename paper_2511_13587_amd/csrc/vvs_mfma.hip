@@ -53,6 +53,18 @@ __global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ A
   constexpr int BM = TM * 32, BN = TN * 32, LDC = BN + 4;
   extern __shared__ float red[];           // [4][BM][LDC]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // XCD-aware tile order.  Workgroups are dealt to the 8 XCDs round-robin by linear id, and each XCD
+  // has its own L2.  Column tiles are taken in groups of 8 (one per XCD); inside a group the row
+  // tiles of one column tile get ids 8 apart: they run at the same time on the same XCD, so a weight
+  // tile is fetched from HBM once and then hits in that XCD's L2.
+  const int MT = (M + BM - 1) / BM, NT = N / BN;
+  int tile_m, tile_n;
+  {
+    const int id = blockIdx.x, grp = id / (8 * MT), rem = id % (8 * MT);
+    const int cols = min(8, NT - grp * 8);
+    tile_m = rem / cols;
+    tile_n = grp * 8 + rem % cols;
+  }
   const int KB = K >> 4;
   const int s0 = blockIdx.z * kb_per_split, s1 = min(KB, s0 + kb_per_split);
   const int per_w = (max(s1 - s0, 0) + 3) >> 2;
@@ -61,9 +73,9 @@ __global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ A
   const uint4* ap[TM];
   const uint4* bp[TN];
 #pragma unroll
-  for (int t = 0; t < TM; ++t) ap[t] = Ap + ((size_t)(blockIdx.y * TM + t) * KB) * 64 + lane;
+  for (int t = 0; t < TM; ++t) ap[t] = Ap + ((size_t)(tile_m * TM + t) * KB) * 64 + lane;
 #pragma unroll
-  for (int t = 0; t < TN; ++t) bp[t] = Wp + ((size_t)(blockIdx.x * TN + t) * KB) * 64 + lane;
+  for (int t = 0; t < TN; ++t) bp[t] = Wp + ((size_t)(tile_n * TN + t) * KB) * 64 + lane;
   floatx16 acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
@@ -111,7 +123,7 @@ __global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ A
       for (int r = 0; r < 16; ++r)
         mine[(i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * LDC + j * 32 + (lane & 31)] = acc[i][j][r];
   __syncthreads();
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
   constexpr int PS = BM * LDC;   // stride between the waves' partial tiles
   if constexpr (EPI == EPI_PARTIAL) {
     float* Cs = C + (size_t)blockIdx.z * M * N;
@@ -134,7 +146,7 @@ __global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ A
         const float up = ((pg[32 + i] + pg[32 + i + PS]) + pg[32 + i + 2 * PS]) + pg[32 + i + 3 * PS];
         v[i] = g / (1.0f + expf(-g)) * up;
       }
-      store8(ep.act, m0 + row, blockIdx.x * 32 + f8, ep.F, v);
+      store8(ep.act, m0 + row, tile_n * 32 + f8, ep.F, v);
     }
   } else {
     const int half = ep.dh >> 1, np = ep.dh >> 2;
@@ -195,7 +207,7 @@ static void launch_gemm_direct(const bf16_t* A, const bf16_t* W, float* C, int M
   }
   const int KB = K / 16;
   const int per = (KB + splits - 1) / splits;
-  dim3 grid(N / (TN * 32), (M + TM * 32 - 1) / (TM * 32), splits);
+  dim3 grid((N / (TN * 32)) * ((M + TM * 32 - 1) / (TM * 32)), 1, splits);
   hipLaunchKernelGGL((k_gemm_direct<TM, TN, D, EPI>), grid, dim3(256), lds, s, (const uint4*)A, (const uint4*)W, C, M, N, K, per, ep);
 }
 

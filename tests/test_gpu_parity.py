@@ -273,3 +273,75 @@ def test_call_order_and_argument_errors(gc):
     assert e.value.status == vb.VVS_ESTATE                       # double commit
     torch.cuda.synchronize()
     pair.close()
+
+
+# ------------------------------------------------------------------------------------------------ full size, sampled
+def test_xl_full_size_sampled_against_checker(gc):
+    """Config 3 at its full size and in the launch configuration the benchmark times (36 layers, 8
+    prompts x 2 CFG rows, 26-node depth-6 tree, mid-image cache of 120 + 287 slots).  The checker
+    computes ONE prompt (its two rows) of the same batch, twice: as it is, and with a 1e-7 relative
+    perturbation in front of its rounding points, which measures how far two correct bf16 evaluations
+    of this 36-layer model drift apart.  The GPU rows of that prompt must agree with the checker within
+    max(3e-2, twice that drift); the acceptance outcome of every prompt must be well-formed; the cached
+    K/V of that prompt must agree."""
+    import dataclasses
+    from oracle import vvs_oracle as vo
+    shape = synth.XL_TREE
+    n_forced = shape.grid // 2 - 1
+    pair = gc.Pair(shape, with_oracle=False)
+    sample = 3                                            # which prompt the checker recomputes
+    pc, pu = synth.make_prefix(shape)
+    forced = synth.make_forced_tokens(shape, n_forced)
+    s1 = shape.replace(n_prompts=1)
+    o = vo.Oracle(dataclasses.asdict(s1), pair.w)
+    # first-token uniform in the middle of the checker's most probable token (robust against bf16 noise)
+    o.prefill(pc[sample:sample + 1], pu, forced[sample:sample + 1], np.array([0.5]))
+    p0 = o.prefill_probs[0]
+    u_first = np.full(shape.n_prompts, 0.5, dtype=np.float32)
+    u_first[sample] = np.float32(p0[:int(np.argmax(p0))].sum() + 0.5 * p0.max())
+    ofirst = o.prefill(pc[sample:sample + 1], pu, forced[sample:sample + 1], u_first[sample:sample + 1])
+    dpc, dpu = pair.dev_prefix(pc, pu)
+    first = torch.zeros(shape.n_prompts, dtype=torch.int32, device=pair.dev)
+    pair.ctx.vvs_prefill(dpc, dpu, torch.from_numpy(forced).to(pair.dev), torch.from_numpy(u_first).to(pair.dev), first)
+    torch.cuda.synchronize()
+    raw, _, _ = pair.gpu_logits()
+    assert first.cpu().numpy()[sample] == ofirst[0]
+    e_prefill = np.abs(raw[2 * sample:2 * sample + 2, 0] - o.prefill_logits).max()
+    parent = synth.tree_parents(shape.tree_widths, shape.n_nodes)
+    q, toks = synth.make_draft(shape, parent, 0)
+    u = synth.make_uniforms(shape, shape.n_nodes, 0)
+    out, _ = pair.verify(parent, toks, q, u, mask=synth.ancestor_mask(parent), run_oracle=False)
+    o.verify(parent, toks[sample:sample + 1], q[sample:sample + 1], u[sample:sample + 1])
+    # the checker against itself under an fp32-sized perturbation: the noise floor of this shape
+    o2 = gc.perturbed_rounding(vo.Oracle(dataclasses.asdict(s1), pair.w))
+    o2.prefill(pc[sample:sample + 1], pu, forced[sample:sample + 1], u_first[sample:sample + 1])
+    o2.pending[:] = o.pending
+    o2.verify(parent, toks[sample:sample + 1], q[sample:sample + 1], u[sample:sample + 1])
+    floor = max(np.abs(o2.raw_logits - o.raw_logits).max(), np.abs(o2.prefill_logits - o.prefill_logits).max())
+    tol = gc.logit_tol(shape, floor)
+    raw, mixed, probs = pair.gpu_logits()
+    e_raw = np.abs(raw[2 * sample:2 * sample + 2] - o.raw_logits).max()
+    e_mix = np.abs(mixed[sample] - o.mixed_logits[0]).max()
+    print(f"xl full size: raw logit max-abs error prefill {e_prefill:.4f} verify {e_raw:.4f}; checker noise floor {floor:.4f} "
+          f"-> bound {tol:.4f}; mixed {e_mix:.4f}")
+    assert e_prefill <= tol and e_raw <= tol and e_mix <= gc.mixed_tol(shape, floor)
+    assert np.isfinite(raw).all() and np.abs(probs.sum(-1) - 1).max() < 1e-4
+    a, path, nxt = out
+    depth = synth.node_depths(parent)
+    for b in range(shape.n_prompts):                      # well-formed outcome for every prompt
+        assert 0 <= a[b] <= depth.max() and path[b][0] == 0 and (path[b][a[b] + 1:] == -1).all()
+        for i in range(1, a[b] + 1):
+            assert parent[path[b][i] - 1] == path[b][i - 1]
+        assert shape.logit_lo <= nxt[b] < shape.logit_hi
+    # cache of the sampled prompt before the commit (prefix + forced tokens), first / middle / last layer
+    S = shape.prefix_len + n_forced
+    for layer in (0, shape.n_layers // 2, shape.n_layers - 1):
+        for i, row in enumerate((2 * sample, 2 * sample + 1)):
+            k, v = pair.ctx.vvs_debug_kv(layer, row, S)
+            ok, ov = o.kc[i][layer].reshape(S, -1), o.vc[i][layer].reshape(S, -1)
+            assert np.abs(k.cpu().numpy() - ok).max() <= 0.05 * max(1.0, np.abs(ok).max())
+            assert np.abs(v.cpu().numpy() - ov).max() <= 0.05 * max(1.0, np.abs(ov).max())
+    pair.commit(run_oracle=False)
+    st = pair.ctx.vvs_read_state()
+    assert (st[0] == S + a + 1).all() and (st[1] == n_forced + 1 + a + 1).all() and (st[2] == nxt).all()
+    pair.close()
