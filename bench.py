@@ -234,7 +234,7 @@ def main():
         n_launch = classes["gemm"]["launches_per_step"]
         t_launch = classes["gemm"]["ms_per_step"] * 1e-3 / n_launch
         bytes_launch, flops_launch = cnt["w_bytes"] / n_launch, cnt["gemm_flops"] / n_launch
-        kernel = "k_gemm_mfma (all bf16 projection GEMMs of one verify call)"
+        kernel = "k_gemm_direct (all bf16 projection GEMMs of one verify call)"
     else:
         n_launch = classes["attention"]["launches_per_step"]
         t_launch = classes["attention"]["ms_per_step"] * 1e-3 / n_launch
@@ -248,7 +248,13 @@ def main():
     else:
         ach = bytes_launch / t_launch / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS}
-    roof.update(traffic=None, kernel=kernel, launches_per_step=n_launch, avg_launch_us=t_launch * 1e6,
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", f"traffic_{shape.name}.json")
+    if dom == "gemm" and os.path.exists(tfile) and not args.layers:
+        # HBM bytes per launch from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command,
+        # scaled by the same counters' reading for a plain copy kernel
+        traffic = json.load(open(tfile)).get("hbm_bytes_per_launch")
+    roof.update(traffic=traffic, kernel=kernel, launches_per_step=n_launch, avg_launch_us=t_launch * 1e6,
                 algorithmic_bytes_per_launch=bytes_launch, algorithmic_flops_per_launch=flops_launch)
     total_bytes = cnt["w_bytes"] + cnt["kv_read"] + cnt["kv_write"] + cnt["q_read"]
 

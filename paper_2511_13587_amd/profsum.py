@@ -3,6 +3,11 @@
 
     python -m paper_2511_13587_amd.profsum kernels <results.db>
     python -m paper_2511_13587_amd.profsum counters <results.db>
+    python -m paper_2511_13587_amd.profsum traffic <fetch.db> <write.db> <kernel substring> <grid_x list, workgroups> [out.json]
+
+`traffic`: HBM bytes per launch of one kernel from a FETCH_SIZE run and a WRITE_SIZE run (KiB per
+dispatch), each scaled by what the same counter reads for the 256 MiB k_copy_bytes launches of the
+same run (bench.py --calibrate-copy).
 """
 import re
 import sqlite3
@@ -41,7 +46,36 @@ def counters(db: str) -> str:
     return "\n".join(out)
 
 
+def traffic(fetch_db: str, write_db: str, kernel: str, grids, out_json=None) -> str:
+    import json
+    res = {"kernel": kernel, "grids_x_workgroups": grids, "copy_bytes": 256 << 20}
+    total = 0.0
+    lines = []
+    for name, db in (("FETCH_SIZE", fetch_db), ("WRITE_SIZE", write_db)):
+        cur = sqlite3.connect(db).cursor()
+        cal = cur.execute("select avg(value) from counters_collection where kernel_name like '%k_copy_bytes%' and counter_name = ?",
+                          (name,)).fetchone()[0]
+        factor = (256 << 10) / cal            # the copy reads and writes 262144 KiB
+        q = ("select count(*), avg(value) from counters_collection where kernel_name like ? and counter_name = ? "
+             "and grid_size_x / workgroup_size_x in (%s)" % ",".join(str(int(g)) for g in grids))
+        n, avg = cur.execute(q, (f"%{kernel}%", name)).fetchone()
+        res[name] = {"copy_kernel_reads_KiB": cal, "scale_factor": factor, "dispatches": n, "avg_KiB_per_dispatch": avg,
+                     "scaled_bytes_per_launch": avg * 1024 * factor}
+        total += avg * 1024 * factor
+        lines.append(f"{name}: copy kernel reads {cal:.1f} KiB for 262144 KiB moved -> factor {factor:.3f}; {kernel}: {n} dispatches, "
+                     f"avg {avg:.1f} KiB -> {avg * 1024 * factor / 1e6:.2f} MB per launch")
+    res["hbm_bytes_per_launch"] = total
+    lines.append(f"HBM traffic per launch (fetch + write): {total / 1e6:.2f} MB")
+    if out_json:
+        json.dump(res, open(out_json, "w"), indent=1)
+    return "\n".join(lines)
+
+
 if __name__ == "__main__":
-    if len(sys.argv) != 3 or sys.argv[1] not in ("kernels", "counters"):
+    if len(sys.argv) >= 6 and sys.argv[1] == "traffic":
+        print(traffic(sys.argv[2], sys.argv[3], sys.argv[4], [int(g) for g in sys.argv[5].split(",")],
+                      sys.argv[6] if len(sys.argv) > 6 else None))
+    elif len(sys.argv) == 3 and sys.argv[1] in ("kernels", "counters"):
+        print(kernels(sys.argv[2]) if sys.argv[1] == "kernels" else counters(sys.argv[2]))
+    else:
         sys.exit(__doc__)
-    print(kernels(sys.argv[2]) if sys.argv[1] == "kernels" else counters(sys.argv[2]))
