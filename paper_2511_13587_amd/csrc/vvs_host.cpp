@@ -26,6 +26,12 @@ GemmPlan plan_gemm(const Ctx* c, int M, int N, int K) {
   // over its 4 waves.  Add grid-level K splits until there is about one workgroup per CU, keeping at
   // least 8 k-steps of 16 per wave.
   p.bm = M <= 32 ? 32 : 64;
+  // 64 x 128 tiles when they give one workgroup for (nearly) every CU and no second round: a CU then
+  // pulls (64 + 128) K-rows through its L1 instead of 2 x (64 + 64)
+  if (p.bm == 64 && N % 128 == 0) {
+    const int t128 = ((M + 63) / 64) * (N / 128);
+    if (t128 >= 160 && t128 <= 256) { p.bn = 128; return p; }
+  }
   const int tiles = ((M + p.bm - 1) / p.bm) * (N / 64);
   const int kb = K / 16;
   int splits = 1;

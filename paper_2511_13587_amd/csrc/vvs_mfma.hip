@@ -125,28 +125,30 @@ __global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ A
   __syncthreads();
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   constexpr int PS = BM * LDC;   // stride between the waves' partial tiles
+  // sum of the four waves' partial tiles for 4 consecutive columns, fixed order
+  auto sum4 = [&](const float* p) {
+    const float4 a = *(const float4*)p, b = *(const float4*)(p + PS), c = *(const float4*)(p + 2 * PS), d = *(const float4*)(p + 3 * PS);
+    return make_float4(((a.x + b.x) + c.x) + d.x, ((a.y + b.y) + c.y) + d.y, ((a.z + b.z) + c.z) + d.z, ((a.w + b.w) + c.w) + d.w);
+  };
   if constexpr (EPI == EPI_PARTIAL) {
     float* Cs = C + (size_t)blockIdx.z * M * N;
-    for (int e = threadIdx.x; e < BM * BN; e += 256) {
-      const int row = e / BN, col = e % BN;
-      const float* p = red + row * LDC + col;
-      const float v = ((p[0] + p[PS]) + p[2 * PS]) + p[3 * PS];
-      if (m0 + row < M) Cs[(size_t)(m0 + row) * N + n0 + col] = v;
+    for (int u = threadIdx.x; u < BM * (BN / 4); u += 256) {       // one unit = (row, 4 consecutive columns)
+      const int row = u / (BN / 4), col = (u % (BN / 4)) * 4;
+      if (m0 + row < M) *(float4*)(Cs + (size_t)(m0 + row) * N + n0 + col) = sum4(red + row * LDC + col);
     }
   } else if constexpr (EPI == EPI_SWIGLU) {
-    static_assert(TN == 2, "gate / up interleave assumes a 64-column tile");
-    for (int u = threadIdx.x; u < BM * 4; u += 256) {       // one unit = (row, 8 consecutive hidden units)
-      const int row = u >> 2, f8 = (u & 3) * 8;
+    static_assert(TN % 2 == 0, "gate / up blocks of 32 columns alternate inside the tile");
+    for (int u = threadIdx.x; u < BM * (BN / 16); u += 256) {       // one unit = (row, 8 consecutive hidden units)
+      const int row = u / (BN / 16), fl = (u % (BN / 16)) * 8;      // fl: hidden unit inside the tile, 0 .. BN/2
       if (m0 + row >= M) continue;
-      const float* pg = red + row * LDC + f8;
+      const float* pg = red + row * LDC + (fl >> 5) * 64 + (fl & 31);
+      const float4 g0 = sum4(pg), g1 = sum4(pg + 4), u0 = sum4(pg + 32), u1 = sum4(pg + 36);
+      const float gs[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+      const float us[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
       float v[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const float g = ((pg[i] + pg[i + PS]) + pg[i + 2 * PS]) + pg[i + 3 * PS];
-        const float up = ((pg[32 + i] + pg[32 + i + PS]) + pg[32 + i + 2 * PS]) + pg[32 + i + 3 * PS];
-        v[i] = g / (1.0f + expf(-g)) * up;
-      }
-      store8(ep.act, m0 + row, tile_n * 32 + f8, ep.F, v);
+      for (int i = 0; i < 8; ++i) v[i] = gs[i] / (1.0f + expf(-gs[i])) * us[i];
+      store8(ep.act, m0 + row, tile_n * (BN / 2) + fl, ep.F, v);
     }
   } else {
     const int half = ep.dh >> 1, np = ep.dh >> 2;
@@ -155,9 +157,8 @@ __global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ A
       const int m = m0 + row;
       if (m >= M) continue;
       const float* p = red + row * LDC + c0;
-      float v[16];
-#pragma unroll
-      for (int i = 0; i < 16; ++i) v[i] = ((p[i] + p[i + PS]) + p[i + 2 * PS]) + p[i + 3 * PS];
+      const float4 s0 = sum4(p), s1 = sum4(p + 4), s2 = sum4(p + 8), s3 = sum4(p + 12);
+      float v[16] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w, s2.x, s2.y, s2.z, s2.w, s3.x, s3.y, s3.z, s3.w};
       const int n = n0 + c0, sec = n / ep.d, eg = n % ep.d, hd = eg / ep.dh, e = eg % ep.dh;
       const int r = m / ep.T, t = m % ep.T;
       int slot, img;
@@ -214,6 +215,7 @@ static void launch_gemm_direct(const bf16_t* A, const bf16_t* W, float* C, int M
 template <int EPI>
 static void gemm_dispatch(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, GemmPlan p, const GemmEpi& ep, hipStream_t s) {
   if (p.bm == 32) launch_gemm_direct<1, 2, 8, EPI>(A, W, C, M, N, K, p.splits, ep, s);
+  else if (p.bn == 128) launch_gemm_direct<2, 4, 4, EPI>(A, W, C, M, N, K, p.splits, ep, s);
   else launch_gemm_direct<2, 2, 6, EPI>(A, W, C, M, N, K, p.splits, ep, s);
 }
 
