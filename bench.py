@@ -136,6 +136,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain 256 MiB copy kernel (k_copy_bytes) three times, for scaling hardware traffic counters")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step (set_state, verify, commit) in a HIP graph and time its replays instead of eager launches")
     ap.add_argument("--layers", type=int, default=0, help="override depth (debugging only; the result is then not the named workload)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -202,12 +204,22 @@ def main():
             ctx.vvs_debug_copy(dst, src)
         torch.cuda.synchronize()
         del src, dst
+    run = step
+    if args.graph:
+        # the library makes no allocation, copy or memset in these calls, so a step is one capturable chain of kernels
+        for _ in range(2):
+            step()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        run = graph.replay
     for _ in range(args.warmup):
-        step()
+        run()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
@@ -265,7 +277,8 @@ def main():
         "dtype": "bf16" if shape.dtype == synth.DTYPE_BF16 else "f32", "data": "synthetic",
         "config": {"workload": shape.name, "layers": shape.n_layers, "d_model": shape.d_model, "prompts": B,
                    "rows": shape.n_rows, "draft_nodes": N, "tree_depth": int(synth.node_depths(parent).max()),
-                   "cache_len_mean": S_mean, "mode": args.mode, "draft_noise_std": args.draft_noise},
+                   "cache_len_mean": S_mean, "mode": args.mode, "draft_noise_std": args.draft_noise,
+                   "launch": "hip graph replay" if args.graph else "eager"},
         "verify_latency_ms": ms_per_step, "mean_accept_len": float(accept.mean()),
         "emitted_tokens_per_step": emitted, "scored_draft_tokens_per_s": B * N / (ms_per_step * 1e-3),
         "whole_pass": {"algorithmic_GB": total_bytes / 1e9, "algorithmic_TFLOP": (cnt["gemm_flops"] + cnt["attn_flops"]) / 1e12,

@@ -114,9 +114,12 @@ __device__ __forceinline__ void token_pos(const PosDesc& pos, const TreeDesc& tr
 
 // MFMA attention / GEMM launchers (vvs_mfma.hip)
 void mfma_gemm(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, GemmPlan p, hipStream_t s);
-void mfma_gemm_swiglu(const bf16_t* A, const bf16_t* Wgu, bf16_t* act, int M, int F, int K, GemmPlan p, hipStream_t s);
-void mfma_gemm_qkv(Ctx* c, int layer, const bf16_t* A, const bf16_t* Wqkv, const TreeDesc& tree, const PosDesc& pos, int T, GemmPlan p,
-                   hipStream_t s);
+void mfma_gemm_scaled(Ctx* c, const bf16_t* A, const bf16_t* W, float* C, const float* ss, int M, int N, int K, GemmPlan p, hipStream_t s);
+void mfma_gemm_resid(Ctx* c, const bf16_t* A, const bf16_t* W, float* x, bf16_t* xb, float* ss_out, int M, int K, hipStream_t s);
+void mfma_gemm_swiglu(Ctx* c, const bf16_t* A, const bf16_t* Wgu, bf16_t* act, const float* ss, int M, int F, int K, GemmPlan p,
+                      hipStream_t s);
+void mfma_gemm_qkv(Ctx* c, int layer, const bf16_t* A, const bf16_t* Wqkv, const float* ss, const TreeDesc& tree, const PosDesc& pos, int T,
+                   GemmPlan p, hipStream_t s);
 void mfma_attention(Ctx* c, int layer, const TreeDesc& tree, const PosDesc& pos, int T, hipStream_t s);
 
 }  // namespace vvs

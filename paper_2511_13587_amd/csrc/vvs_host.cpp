@@ -117,6 +117,8 @@ vvs_status plan_sizes(const vvs_config* cfg, Ctx* c, std::string* err) {
   w.logits = take(sizeof(float) * (size_t)c->Mlog * veff);
   w.probs = take(sizeof(float) * (size_t)c->B * c->Tmax * veff);
   w.pq_work = take(sizeof(float) * (size_t)c->B * c->Tmax * 2 * veff);
+  w.ss = take(sizeof(float) * (size_t)c->Mmax * (((d + 63) / 64 + 3) & ~3));     // per-row, per-64-column sums of squares of the residual
+  w.ss2 = take(sizeof(float) * (size_t)c->Mlog * (((d + 63) / 64 + 3) & ~3));
   w.total = off;
   // packed weights
   PackedLayout& p = c->p;

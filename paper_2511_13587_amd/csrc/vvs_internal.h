@@ -36,7 +36,7 @@ struct GemmPlan { int bm, bn, splits; };
 // Byte offsets into the caller's workspace.
 struct Workspace {
   size_t state, outcome, node_result, tokens, rope_tab, x, h, gemm_out, q, attn, act, hf, logits, probs,
-      pq_work, total;
+      pq_work, ss, ss2, total;
 };
 
 struct PackedLayout {

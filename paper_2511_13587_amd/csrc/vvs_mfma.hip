@@ -35,11 +35,21 @@ __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast
 //                operand of the down projection (one K split only);
 //   EPI_QKV    : the tile lies inside the q, k or v third of the fused projection: apply the 2D
 //                rotary embedding to q and k, write q (bf16 row-major) and put k / v into the cache
-//                slots of their tokens (one K split only).
-enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_QKV = 2 };
+//                slots of their tokens (one K split only);
+//   EPI_RESID  : O / down projection: x += tile (fp32 residual stream, each element owned by one
+//                thread), also written as the packed bf16 operand of the next projection, plus the
+//                sum of squares of the tile's 64 columns per row (one K split only).
+// Row scale: RMSNorm is x * s_m * g with s_m = rsqrt(mean_k x_mk^2 + eps).  The gain g is folded into
+// the weights when they are packed, the operand is bf16(x) itself, and s_m - a per-row factor that
+// commutes with the contraction - multiplies the accumulated tile in the epilogue; s_m comes from the
+// per-64-column sums of squares that the producer of x (EPI_RESID or the embedding kernel) left in ss.
+// This removes the separate normalisation pass between two projections.
+enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_QKV = 2, EPI_RESID = 3 };
 
 struct GemmEpi {
+  const float* ss; int NS; float eps; int dnorm;           // row scale (ss == nullptr: no scaling); ss[M][NS]
   bf16_t* act; int F;                                      // EPI_SWIGLU
+  float* x; bf16_t* xb; float* ss_out;                     // EPI_RESID
   bf16_t* q; bf16_t* kc; bf16_t* vc; const float* rope;    // EPI_QKV
   int T, d, dh, S_cap, rope_pos;
   size_t row_stride, head_stride;
@@ -64,6 +74,25 @@ __global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ A
     const int cols = min(8, NT - grp * 8);
     tile_m = rem / cols;
     tile_n = grp * 8 + rem % cols;
+  }
+  __shared__ float rs[BM];                 // per-row RMSNorm factor of this tile's rows (loaded first: hidden behind the main loop)
+  if (threadIdx.x < BM * 4) {              // 4 lanes per row, each sums every 4th group of 4 slabs: all loads independent
+    const int row = threadIdx.x >> 2, part = threadIdx.x & 3;
+    const int m = tile_m * BM + row;
+    float t = 0.f;
+    if (ep.ss && m < M) {
+      const float4* p4 = (const float4*)(ep.ss + (size_t)m * ep.NS);     // rows are padded to a multiple of 4 slabs (zeros)
+      const int nq = ep.NS >> 2;
+      float4 v[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[i] = (part + 4 * i < nq) ? p4[part + 4 * i] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) t += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+      for (int qd = part + 16; qd < nq; qd += 4) { const float4 w = p4[qd]; t += (w.x + w.y) + (w.z + w.w); }
+    }
+    t += __shfl_xor(t, 1, 64);
+    t += __shfl_xor(t, 2, 64);
+    if (part == 0) rs[row] = (ep.ss && m < M) ? 1.0f / sqrtf(t / (float)ep.dnorm + ep.eps) : 1.f;
   }
   const int KB = K >> 4;
   const int s0 = blockIdx.z * kb_per_split, s1 = min(KB, s0 + kb_per_split);
@@ -134,7 +163,12 @@ __global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ A
     float* Cs = C + (size_t)blockIdx.z * M * N;
     for (int u = threadIdx.x; u < BM * (BN / 4); u += 256) {       // one unit = (row, 4 consecutive columns)
       const int row = u / (BN / 4), col = (u % (BN / 4)) * 4;
-      if (m0 + row < M) *(float4*)(Cs + (size_t)(m0 + row) * N + n0 + col) = sum4(red + row * LDC + col);
+      if (m0 + row < M) {
+        float4 v = sum4(red + row * LDC + col);
+        const float sc = rs[row];
+        v.x *= sc; v.y *= sc; v.z *= sc; v.w *= sc;
+        *(float4*)(Cs + (size_t)(m0 + row) * N + n0 + col) = v;
+      }
     }
   } else if constexpr (EPI == EPI_SWIGLU) {
     static_assert(TN % 2 == 0, "gate / up blocks of 32 columns alternate inside the tile");
@@ -147,8 +181,33 @@ __global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ A
       const float us[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
       float v[8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) v[i] = gs[i] / (1.0f + expf(-gs[i])) * us[i];
+      for (int i = 0; i < 8; ++i) {
+        const float g = gs[i] * rs[row], up = us[i] * rs[row];
+        v[i] = g / (1.0f + expf(-g)) * up;
+      }
       store8(ep.act, m0 + row, tile_n * (BN / 2) + fl, ep.F, v);
+    }
+  } else if constexpr (EPI == EPI_RESID) {
+    static_assert(BN == 64, "the sums of squares are kept per 64-column slab");
+    for (int u = threadIdx.x; u < BM * 8; u += 256) {              // one unit = (row, 8 consecutive columns); 8 lanes share a row
+      const int row = u >> 3, c8 = (u & 7) * 8;
+      const int m = m0 + row;
+      float sq = 0.f;
+      if (m < M) {
+        const float4 a = sum4(red + row * LDC + c8), b = sum4(red + row * LDC + c8 + 4);
+        float* xp = ep.x + (size_t)m * N + n0 + c8;
+        const float4 xa = *(const float4*)xp, xb4 = *(const float4*)(xp + 4);
+        float v[8] = {xa.x + a.x, xa.y + a.y, xa.z + a.z, xa.w + a.w, xb4.x + b.x, xb4.y + b.y, xb4.z + b.z, xb4.w + b.w};
+        *(float4*)xp = make_float4(v[0], v[1], v[2], v[3]);
+        *(float4*)(xp + 4) = make_float4(v[4], v[5], v[6], v[7]);
+        store8(ep.xb, m, n0 + c8, N, v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sq += v[i] * v[i];
+      }
+      sq += __shfl_xor(sq, 1, 64);
+      sq += __shfl_xor(sq, 2, 64);
+      sq += __shfl_xor(sq, 4, 64);
+      if (m < M && c8 == 0) ep.ss_out[(size_t)m * ep.NS + tile_n] = sq;
     }
   } else {
     const int half = ep.dh >> 1, np = ep.dh >> 2;
@@ -159,6 +218,8 @@ __global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ A
       const float* p = red + row * LDC + c0;
       const float4 s0 = sum4(p), s1 = sum4(p + 4), s2 = sum4(p + 8), s3 = sum4(p + 12);
       float v[16] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w, s2.x, s2.y, s2.z, s2.w, s3.x, s3.y, s3.z, s3.w};
+#pragma unroll
+      for (int i = 0; i < 16; ++i) v[i] *= rs[row];
       const int n = n0 + c0, sec = n / ep.d, eg = n % ep.d, hd = eg / ep.dh, e = eg % ep.dh;
       const int r = m / ep.T, t = m % ep.T;
       int slot, img;
@@ -219,23 +280,45 @@ static void gemm_dispatch(const bf16_t* A, const bf16_t* W, float* C, int M, int
   else launch_gemm_direct<2, 2, 6, EPI>(A, W, C, M, N, K, p.splits, ep, s);
 }
 
+static void set_scale(GemmEpi& ep, const Ctx* c, const float* ss) {
+  ep.ss = ss; ep.NS = (c->d / 64 + 3) & ~3; ep.eps = c->cfg.rms_eps; ep.dnorm = c->d;   // rows of ss are padded to 4 slabs
+}
+
 void mfma_gemm(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, GemmPlan p, hipStream_t s) {
   GemmEpi ep{};
   gemm_dispatch<EPI_PARTIAL>(A, W, C, M, N, K, p, ep, s);
 }
 
-// gate/up projection with the SwiGLU epilogue: act = silu(h Wg) * (h Wu), packed bf16 [M][F]
-void mfma_gemm_swiglu(const bf16_t* A, const bf16_t* Wgu, bf16_t* act, int M, int F, int K, GemmPlan p, hipStream_t s) {
+// C = s_m * (A W): projection of the un-normalised bf16 residual with the RMSNorm factor applied afterwards
+void mfma_gemm_scaled(Ctx* c, const bf16_t* A, const bf16_t* W, float* C, const float* ss, int M, int N, int K, GemmPlan p, hipStream_t s) {
   GemmEpi ep{};
+  set_scale(ep, c, ss);
+  p.splits = 1;
+  gemm_dispatch<EPI_PARTIAL>(A, W, C, M, N, K, p, ep, s);
+}
+
+// x += A W; also leaves bf16(x) packed and the per-slab sums of squares of the new x
+void mfma_gemm_resid(Ctx* c, const bf16_t* A, const bf16_t* W, float* x, bf16_t* xb, float* ss_out, int M, int K, hipStream_t s) {
+  GemmEpi ep{};
+  ep.x = x; ep.xb = xb; ep.ss_out = ss_out; ep.NS = (c->d / 64 + 3) & ~3;
+  launch_gemm_direct<2, 2, 6, EPI_RESID>(A, W, nullptr, M, c->d, K, 1, ep, s);
+}
+
+// gate/up projection with the SwiGLU epilogue: act = silu(h Wg) * (h Wu), packed bf16 [M][F]
+void mfma_gemm_swiglu(Ctx* c, const bf16_t* A, const bf16_t* Wgu, bf16_t* act, const float* ss, int M, int F, int K, GemmPlan p,
+                      hipStream_t s) {
+  GemmEpi ep{};
+  set_scale(ep, c, ss);
   ep.act = act; ep.F = F;
   p.splits = 1;
   gemm_dispatch<EPI_SWIGLU>(A, Wgu, nullptr, M, 2 * F, K, p, ep, s);
 }
 
 // fused q/k/v projection with the rotary + cache-write epilogue
-void mfma_gemm_qkv(Ctx* c, int layer, const bf16_t* A, const bf16_t* Wqkv, const TreeDesc& tree, const PosDesc& pos, int T, GemmPlan p,
-                   hipStream_t s) {
+void mfma_gemm_qkv(Ctx* c, int layer, const bf16_t* A, const bf16_t* Wqkv, const float* ss, const TreeDesc& tree, const PosDesc& pos, int T,
+                   GemmPlan p, hipStream_t s) {
   GemmEpi ep{};
+  set_scale(ep, c, ss);
   ep.q = (bf16_t*)(c->ws + c->w.q);
   ep.kc = (bf16_t*)c->kv + c->kv_layer_stride * layer;
   ep.vc = (bf16_t*)c->kv + c->kv_v_off + c->kv_layer_stride * layer;

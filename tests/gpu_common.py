@@ -1,12 +1,16 @@
 """Shared helpers of the GPU parity tests: build the HIP context and the CPU checker on the same
 seeded inputs and compare their outputs with the tolerances of the parity contract.
 
-Tolerances (max-abs): fp32 model: logits 1e-4, probabilities 1e-3.  bf16 model: raw logits 3e-2 for
-models of up to 12 layers.  A deeper bf16 model is chaotic at the level of a bf16 ulp (a 1e-7 relative
-difference in front of a rounding point grows to rounding noise within one layer and then adds up over
-the layers), so there the bound is the larger of 3e-2 and twice the checker's OWN logit change under a
-1e-7 relative perturbation of its rounding points, measured by the test on the same inputs
-(`checker_noise_floor`).  The CFG mix l_u + s (l_c - l_u) multiplies the error of each row by |s| and
+Tolerances (max-abs): fp32 model: logits 1e-4, probabilities 1e-3.  bf16 model: raw logits 3e-2, or
+three times the checker's OWN logit change under a 1e-7 relative perturbation in front of its rounding
+points if that is larger (measured by the test on the same inputs: `Pair(shadow=True)`).  A bf16
+model is chaotic at the level of a bf16 ulp - such a perturbation grows to rounding noise within one
+layer and then adds up over the layers - so two correct evaluations cannot agree better than that
+floor (1e-2 .. 5e-2 at the widths and depths tested).  The factor 3: the perturbed checker still
+rounds at the same points as the checker, whereas the kernels round some operands at other points
+(bf16(x) before the RMSNorm factor instead of after it, attention weights before normalisation), which
+makes their rounding noise independent of the checker's from the first layer on (a factor sqrt 2 in
+rms), and the maximum over ~1e6 logits of two such differences spreads by another ~1.5.  The CFG mix l_u + s (l_c - l_u) multiplies the error of each row by |s| and
 |s - 1|, hence the mixed-logit bound is (|s| + |s - 1|) times the raw one.  Decisions
 (accept length, path, next token) must be identical whenever every draw the checker consulted was
 farther than GUARD from its threshold; the final inverse-CDF draw is compared in interval form."""
@@ -28,8 +32,7 @@ def logit_tol(shape, noise_floor=None):
         return 1e-4
     if shape.n_layers > 12:
         assert noise_floor is not None, "deep bf16 shapes need the checker's measured noise floor"
-        return max(3e-2, 2.0 * noise_floor)
-    return 3e-2
+    return max(3e-2, 3.0 * (noise_floor or 0.0))
 
 
 def mixed_tol(shape, noise_floor=None):
@@ -48,13 +51,16 @@ def perturbed_rounding(oracle, eps=1e-7, seed=1):
 class Pair:
     """The HIP context and the checker, fed with identical inputs."""
 
-    def __init__(self, shape, weights=None, gain_jitter=0.0, std=0.02, with_oracle=True):
+    def __init__(self, shape, weights=None, gain_jitter=0.0, std=0.02, with_oracle=True, shadow=False):
         self.shape = shape
         self.w = weights if weights is not None else synth.make_weights(shape, std=std, gain_jitter=gain_jitter)
         self.cfg = vb.make_config(shape)
         self.ctx = vb.Context(self.cfg)
         self.ctx.load_weights_from_host(self.w, synth.weight_names(shape))
         self.oracle = vo.Oracle(dataclasses.asdict(shape), self.w) if with_oracle else None
+        # a second checker with perturbed rounding measures the noise floor of this shape on these inputs
+        self.shadow = perturbed_rounding(vo.Oracle(dataclasses.asdict(shape), self.w)) if shadow else None
+        self.floor = 0.0
         self.dev = self.ctx.device
         B = shape.n_prompts
         self.accept_len = torch.zeros(B, dtype=torch.int32, device=self.dev)
@@ -67,6 +73,8 @@ class Pair:
         self.ctx.vvs_set_neighbors(self.nbr)
         if self.oracle is not None:
             self.oracle.set_neighbors(nbr)
+        if self.shadow is not None:
+            self.shadow.set_neighbors(nbr)
 
     def dev_prefix(self, pc, pu):
         if self.shape.prefix_kind == synth.PREFIX_CLASS:
@@ -97,6 +105,9 @@ class Pair:
         ofirst = None
         if run_oracle and self.oracle is not None:
             ofirst = self.oracle.prefill(pc, pu, forced, u)
+            if self.shadow is not None:
+                self.shadow.prefill(pc, pu, forced, u)
+                self.floor = max(self.floor, float(np.abs(self.shadow.prefill_logits - self.oracle.prefill_logits).max()))
         return first.cpu().numpy(), ofirst, u
 
     def verify(self, parent, tokens, q, u, mode=0, run_oracle=True, mask=None):
@@ -112,7 +123,14 @@ class Pair:
             oparent = np.arange(N) if parent is None else parent
             otok = np.zeros((self.shape.n_prompts, 0), dtype=np.int64) if N == 0 else tokens
             oq = np.zeros((self.shape.n_prompts, 1, self.shape.v_eff)) if N == 0 else q
+            same_state = self.shadow is not None and all(
+                self.shadow.kv_len(b) == self.oracle.kv_len(b) for b in range(self.shape.n_prompts))
+            if same_state:
+                self.shadow.pending[:] = self.oracle.pending
             oout = self.oracle.verify(oparent, otok, oq, u, mode)
+            if same_state:
+                self.shadow.verify(oparent, otok, oq, u, mode)
+                self.floor = max(self.floor, float(np.abs(self.shadow.raw_logits - self.oracle.raw_logits).max()))
         return out, oout
 
     def commit(self, run_oracle=True):
@@ -120,6 +138,8 @@ class Pair:
         torch.cuda.synchronize()
         if run_oracle and self.oracle is not None:
             self.oracle.kv_commit()
+            if self.shadow is not None and self.shadow.last is not None:
+                self.shadow.kv_commit()
 
     def gpu_logits(self):
         raw, mixed, probs = self.ctx.vvs_debug_logits()
@@ -138,8 +158,8 @@ def check_logits(pair, label=""):
     e_mix = np.abs(mixed - o.mixed_logits).max()
     e_p = np.abs(probs - o.probs).max()
     assert np.isfinite(raw).all() and np.isfinite(probs).all(), label
-    assert e_raw <= logit_tol(shape), f"{label}: raw logits differ by {e_raw}"
-    assert e_mix <= mixed_tol(shape), f"{label}: mixed logits differ by {e_mix}"
+    assert e_raw <= logit_tol(shape, pair.floor), f"{label}: raw logits differ by {e_raw} (checker noise floor {pair.floor})"
+    assert e_mix <= mixed_tol(shape, pair.floor), f"{label}: mixed logits differ by {e_mix}"
     if shape.dtype == synth.DTYPE_FP32:
         assert e_p <= 1e-3, f"{label}: probabilities differ by {e_p}"
     assert np.abs(probs.sum(-1) - 1).max() < 1e-4

@@ -113,13 +113,16 @@ def test_tiny_plain_ar_and_finish(gc):
 
 
 # ------------------------------------------------------------------------------------------------ bf16 shapes
-def run_bf16_case(gc, shape, n_forced, calls=2, mode=0, nbr=None, correlated=True):
-    pair = gc.Pair(shape)
+def run_bf16_case(gc, shape, n_forced, calls=2, mode=0, nbr=None, correlated=True, sharp=None):
+    """sharp: optional extra bound on the raw-logit error as a multiple of the checker's noise floor
+    (for shallow models, where the floor is far below the 3e-2 of the contract)."""
+    pair = gc.Pair(shape, shadow=True)
     if nbr is not None:
         pair.set_neighbors(nbr)
     first, ofirst, _ = pair.prefill(n_forced=n_forced, robust_u=True)
     raw, mixed, probs = pair.gpu_logits()
-    assert np.abs(raw[:, 0] - pair.oracle.prefill_logits).max() <= gc.logit_tol(shape)
+    e0 = np.abs(raw[:, 0] - pair.oracle.prefill_logits).max()
+    assert e0 <= gc.logit_tol(shape, pair.floor), (e0, pair.floor)
     assert (first == ofirst).all()
     parent = synth.tree_parents(shape.tree_widths, shape.n_nodes)
     mask = synth.ancestor_mask(parent)
@@ -131,7 +134,9 @@ def run_bf16_case(gc, shape, n_forced, calls=2, mode=0, nbr=None, correlated=Tru
         q, toks = synth.make_draft(shape, parent, it, base_logits=base)
         u = synth.make_uniforms(shape, shape.n_nodes, it)
         out, oout = pair.verify(parent, toks, q, u, mode=mode, mask=mask)
-        stats.append(gc.check_logits(pair, f"{shape.name} call {it}"))
+        stats.append(gc.check_logits(pair, f"{shape.name} call {it}") + (pair.floor,))
+        if sharp is not None:
+            assert stats[-1][0] <= max(sharp * pair.floor, 2e-3), stats[-1]
         # cache contents of the draft block (before commit): slots S .. S + T - 1
         S = pair.oracle.kv_len(0)
         k, v = pair.ctx.vvs_debug_kv(shape.n_layers - 1, 1, S)
@@ -154,6 +159,14 @@ def test_b_shape_full_depth(gc):
     """Config 2 at full size (12 layers, 8 rows, chain K = 5) at a mid-image cache length."""
     stats = run_bf16_case(gc, synth.B_SHAPE, n_forced=70, calls=2)
     print("llamagen_b: max-abs raw/mixed/prob errors per call:", stats)
+
+
+def test_xl_tree_one_layer_sharp(gc):
+    """One layer of config 3's shape at full batch (432 GEMM rows: the path without separate
+    normalisation kernels).  The noise floor of a one-layer model is small, so the comparison is sharp:
+    the GPU may differ from the checker by at most 4x what the checker differs from itself."""
+    stats = run_bf16_case(gc, synth.XL_TREE.replace(n_layers=1), n_forced=45, calls=2, sharp=4.0)
+    print("xl_tree L=1 (raw, mixed, prob, floor):", stats)
 
 
 def test_xl_tree_reduced_depth(gc):
@@ -282,7 +295,7 @@ def test_xl_full_size_sampled_against_checker(gc):
     computes ONE prompt (its two rows) of the same batch, twice: as it is, and with a 1e-7 relative
     perturbation in front of its rounding points, which measures how far two correct bf16 evaluations
     of this 36-layer model drift apart.  The GPU rows of that prompt must agree with the checker within
-    max(3e-2, twice that drift); the acceptance outcome of every prompt must be well-formed; the cached
+    max(3e-2, three times that drift); the acceptance outcome of every prompt must be well-formed; the cached
     K/V of that prompt must agree."""
     import dataclasses
     from oracle import vvs_oracle as vo
