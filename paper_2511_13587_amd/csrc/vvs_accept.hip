@@ -26,6 +26,9 @@ struct AcceptArgs {
   float scale, delta;
 };
 
+// Largest 2 * veff * 4 bytes that is kept in LDS (160 KiB per CU, a few hundred bytes are static).
+constexpr size_t kAcceptLdsMax = 144 * 1024;
+
 // Inverse CDF in ascending id: first id whose running sum exceeds u * total; if rounding runs past
 // the end, the last id with mass.  Each thread owns a contiguous chunk.
 __device__ int inverse_cdf(const float* __restrict__ P, int n, float u, float* red, int* ired, float* scan) {
@@ -65,7 +68,11 @@ __device__ int inverse_cdf(const float* __restrict__ P, int n, float u, float* r
   return win;
 }
 
+// LDS_PQ: the running target and draft distributions of the node live in (dynamic) LDS, 2 * veff
+// floats; otherwise in the global scratch rows.
+template <bool LDS_PQ>
 __global__ __launch_bounds__(1024) void k_accept_node(AcceptArgs a, TreeDesc tree) {
+  extern __shared__ float pq_lds[];
   __shared__ float red[16];
   __shared__ int ired[16];
   __shared__ float scan[16];
@@ -77,7 +84,7 @@ __global__ __launch_bounds__(1024) void k_accept_node(AcceptArgs a, TreeDesc tre
   const int T = a.T, V = a.veff;
   const float* lc = a.logits + ((size_t)(2 * b) * T + j) * V;
   const float* lu = a.logits + ((size_t)(2 * b + 1) * T + j) * V;
-  float* P = a.work + ((size_t)(b * T + j) * 2) * V;
+  float* P = LDS_PQ ? pq_lds : a.work + ((size_t)(b * T + j) * 2) * V;
   float* Q = P + V;
   float* prow = a.probs + (size_t)(b * T + j) * V;
 
@@ -181,29 +188,36 @@ __global__ __launch_bounds__(1024) void k_accept_node(AcceptArgs a, TreeDesc tre
   if (tid == 0) { res[0] = 0; res[1] = a.lo + tok; }
 }
 
-// Follows accepted children from the root.
-__global__ void k_walk(const int32_t* __restrict__ node_result, int B, int32_t* __restrict__ accept_len,
-                       int32_t* __restrict__ path, int32_t* __restrict__ next_token, int32_t* __restrict__ keep) {
-  const int b = blockIdx.x * blockDim.x + threadIdx.x;
-  if (b >= B) return;
-  int cur = 0, a = 0;
-  int p[VVS_MAX_T];
-  p[0] = 0;
-  while (a < VVS_MAX_T - 1) {
-    const int nxt = node_result[((size_t)b * VVS_MAX_T + cur) * 2];
-    if (nxt <= cur) break;               // 0 = nothing accepted (children always have larger ids)
-    cur = nxt;
-    p[++a] = cur;
+// Follows accepted children from the root: one wave per prompt, lane 0 walks (at most tree-depth
+// dependent reads), then the lanes write one path entry each.
+__global__ __launch_bounds__(64) void k_walk(const int32_t* __restrict__ node_result, int B, int32_t* __restrict__ accept_len,
+                                             int32_t* __restrict__ path, int32_t* __restrict__ next_token, int32_t* __restrict__ keep) {
+  static_assert(VVS_MAX_T == 64, "one lane per path entry");
+  __shared__ int p[VVS_MAX_T];
+  __shared__ int s_a, s_tok;
+  const int b = blockIdx.x, i = threadIdx.x;
+  if (i == 0) {
+    int cur = 0, a = 0;
+    p[0] = 0;
+    while (a < VVS_MAX_T - 1) {
+      const int nxt = node_result[((size_t)b * VVS_MAX_T + cur) * 2];
+      if (nxt <= cur) break;               // 0 = nothing accepted (children always have larger ids)
+      cur = nxt;
+      p[++a] = cur;
+    }
+    s_a = a;
+    s_tok = node_result[((size_t)b * VVS_MAX_T + cur) * 2 + 1];
   }
-  const int tok = node_result[((size_t)b * VVS_MAX_T + cur) * 2 + 1];
-  if (accept_len) accept_len[b] = a;
-  if (next_token) next_token[b] = tok;
-  if (keep) { keep[b] = a; keep[B + b] = tok; }
-  for (int i = 0; i < VVS_MAX_T; ++i) {
-    const int v = i <= a ? p[i] : -1;
-    if (path) path[b * VVS_MAX_T + i] = v;
-    if (keep) keep[2 * B + b * VVS_MAX_T + i] = v;
+  __syncthreads();
+  const int a = s_a, tok = s_tok;
+  if (i == 0) {
+    if (accept_len) accept_len[b] = a;
+    if (next_token) next_token[b] = tok;
+    if (keep) { keep[b] = a; keep[B + b] = tok; }
   }
+  const int v = i <= a ? p[i] : -1;
+  if (path) path[b * VVS_MAX_T + i] = v;
+  if (keep) keep[2 * B + b * VVS_MAX_T + i] = v;
 }
 
 void launch_accept(Ctx* c, const TreeDesc& tree, int T, const float* d_logits, const int32_t* d_draft_tokens, const float* d_q,
@@ -220,10 +234,22 @@ void launch_accept(Ctx* c, const TreeDesc& tree, int T, const float* d_logits, c
   a.node_result = (int32_t*)(c->ws + c->w.node_result);
   a.T = T; a.veff = c->veff; a.lo = c->lo; a.mode = mode; a.relax_k = c->cfg.relax_k; a.G = c->G;
   a.scale = c->cfg.cfg_scale; a.delta = c->cfg.relax_delta;
-  hipLaunchKernelGGL(k_accept_node, dim3(T, c->B), dim3(1024), 0, s, a, tree);
+  const size_t pq_bytes = (size_t)2 * c->veff * sizeof(float);
+  if (pq_bytes <= kAcceptLdsMax) {
+    // more than 64 KiB of dynamic LDS has to be asked for once per device
+    static bool raised[64] = {};
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    if (pq_bytes > 64 * 1024 && dev >= 0 && dev < 64 && !raised[dev]) {
+      (void)hipFuncSetAttribute((const void*)k_accept_node<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAcceptLdsMax);
+      raised[dev] = true;
+    }
+    hipLaunchKernelGGL(k_accept_node<true>, dim3(T, c->B), dim3(1024), pq_bytes, s, a, tree);
+  } else {
+    hipLaunchKernelGGL(k_accept_node<false>, dim3(T, c->B), dim3(1024), 0, s, a, tree);
+  }
   int32_t* keep = keep_outcome ? (int32_t*)(c->ws + c->w.outcome) : nullptr;
-  hipLaunchKernelGGL(k_walk, dim3((c->B + 63) / 64), dim3(64), 0, s, (const int32_t*)a.node_result, c->B, d_accept_len, d_path,
-                     d_next, keep);
+  hipLaunchKernelGGL(k_walk, dim3(c->B), dim3(64), 0, s, (const int32_t*)a.node_result, c->B, d_accept_len, d_path, d_next, keep);
 }
 
 __global__ void k_prefill_finish(const int32_t* __restrict__ node_result, int32_t* __restrict__ state, int32_t* __restrict__ first,

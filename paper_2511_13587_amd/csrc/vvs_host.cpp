@@ -26,6 +26,9 @@ GemmPlan plan_gemm(const Ctx* c, int M, int N, int K) {
   // over its 4 waves.  Add grid-level K splits until there is about one workgroup per CU, keeping at
   // least 8 k-steps of 16 per wave.
   p.bm = M <= 32 ? 32 : 64;
+  // 128 x 128 tiles with the operands shared through LDS when that still gives most CUs a workgroup:
+  // half the operand bytes per MFMA come through a CU's L1
+  if (M > 192 && N % 128 == 0 && K % 32 == 0 && ((M + 127) / 128) * (N / 128) >= 160) { p.bm = p.bn = 128; return p; }
   // 64 x 128 tiles when they give one workgroup for (nearly) every CU and no second round: a CU then
   // pulls (64 + 128) K-rows through its L1 instead of 2 x (64 + 64)
   if (p.bm == 64 && N % 128 == 0) {

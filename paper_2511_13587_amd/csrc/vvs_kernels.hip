@@ -615,28 +615,59 @@ void launch_forward(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int T, con
 }
 
 // ------------------------------------------------------------------------------------------------ KV commit
-// One thread owns one (head, dim) column and walks the accepted path in order: slot S + path[i]
-// moves to slot S + i.  path is strictly increasing with path[i] >= i, so a destination is never a
-// source that is still needed.
-template <typename T>
-__global__ void k_commit_kv(T* __restrict__ kcache, T* __restrict__ vcache, const int32_t* __restrict__ kv_len,
-                            const int32_t* __restrict__ accept_len, const int32_t* __restrict__ next_token,
-                            const int32_t* __restrict__ path, int H, int dh, size_t layer_stride, size_t row_stride,
-                            size_t head_stride, int S_cap) {
+// Slot S + path[i] moves to slot S + i for the accepted positions i = 1..a.  path is strictly
+// increasing with path[i] >= i, so a destination is never a source of a later position.  A thread
+// owns either one chunk (CT: 16 bytes, or one element when the head size does not allow that) of a K
+// row or one V element of a head for every accepted position; it reads the sources of up to 8
+// positions before it writes them, which leaves one memory round trip per 8 positions.
+template <typename T, typename CT>
+__global__ __launch_bounds__(256) void k_commit_kv(T* __restrict__ kcache, T* __restrict__ vcache, const int32_t* __restrict__ kv_len,
+                                                   const int32_t* __restrict__ accept_len, const int32_t* __restrict__ next_token,
+                                                   const int32_t* __restrict__ path, int H, int dh, size_t layer_stride,
+                                                   size_t row_stride, size_t head_stride, int S_cap) {
+  constexpr int CH = sizeof(CT) / sizeof(T);   // elements per K chunk
+  __shared__ int s_src[VVS_MAX_T];
   const int r = blockIdx.x, l = blockIdx.y, b = r >> 1;
   if (next_token[b] < 0) return;
   const int S = kv_len[b], a = accept_len[b];
+  if (threadIdx.x < VVS_MAX_T) s_src[threadIdx.x] = path[b * VVS_MAX_T + threadIdx.x];
+  __syncthreads();
   T* kb = kcache + l * layer_stride + r * row_stride;
   T* vb = vcache + l * layer_stride + r * row_stride;
-  for (int col = threadIdx.x; col < H * dh; col += blockDim.x) {
-    const int hd = col / dh, e = col % dh;
-    T* kh = kb + hd * head_stride;
-    T* vh = vb + hd * head_stride;
-    for (int i = 1; i <= a; ++i) {
-      const int src = S + path[b * VVS_MAX_T + i], dst = S + i;
-      if (src == dst || src >= S_cap) continue;
-      kh[(size_t)dst * dh + e] = kh[(size_t)src * dh + e];
-      vh[v_index(dst, e, dh)] = vh[v_index(src, e, dh)];
+  const int n_k = H * dh / CH, n_v = H * dh;
+  for (int item = threadIdx.x; item < n_k + n_v; item += blockDim.x) {
+    if (item < n_k) {
+      const int col = item * CH, hd = col / dh, e = col % dh;
+      T* kh = kb + hd * head_stride + e;
+      for (int i0 = 1; i0 <= a; i0 += 8) {
+        CT tmp[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const int i = min(i0 + k, a);
+          tmp[k] = *(const CT*)(kh + (size_t)min(S + s_src[i], S_cap - 1) * dh);
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const int i = i0 + k;
+          if (i <= a && s_src[i] != i && S + s_src[i] < S_cap) *(CT*)(kh + (size_t)(S + i) * dh) = tmp[k];
+        }
+      }
+    } else {
+      const int col = item - n_k, hd = col / dh, e = col % dh;
+      T* vh = vb + hd * head_stride;
+      for (int i0 = 1; i0 <= a; i0 += 8) {
+        T tmp[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const int i = min(i0 + k, a);
+          tmp[k] = vh[v_index(min(S + s_src[i], S_cap - 1), e, dh)];
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const int i = i0 + k;
+          if (i <= a && s_src[i] != i && S + s_src[i] < S_cap) vh[v_index(S + i, e, dh)] = tmp[k];
+        }
+      }
     }
   }
 }
@@ -658,11 +689,18 @@ void launch_commit(Ctx* c, hipStream_t s) {
   const int32_t* next_token = oc + c->B;
   const int32_t* path = oc + 2 * c->B;
   dim3 grid(c->R, c->L);
-  if (c->cfg.dtype == VVS_BF16)
-    hipLaunchKernelGGL(k_commit_kv<bf16_t>, grid, dim3(256), 0, s, (bf16_t*)c->kv, (bf16_t*)c->kv + c->kv_v_off, state, accept_len,
+  const bool vec = (c->dh * c->esz) % 16 == 0;
+  if (c->cfg.dtype == VVS_BF16 && vec)
+    hipLaunchKernelGGL((k_commit_kv<bf16_t, uint4>), grid, dim3(256), 0, s, (bf16_t*)c->kv, (bf16_t*)c->kv + c->kv_v_off, state, accept_len,
+                       next_token, path, c->H, c->dh, c->kv_layer_stride, c->kv_row_stride, c->kv_head_stride, c->S_cap);
+  else if (c->cfg.dtype == VVS_BF16)
+    hipLaunchKernelGGL((k_commit_kv<bf16_t, bf16_t>), grid, dim3(256), 0, s, (bf16_t*)c->kv, (bf16_t*)c->kv + c->kv_v_off, state, accept_len,
+                       next_token, path, c->H, c->dh, c->kv_layer_stride, c->kv_row_stride, c->kv_head_stride, c->S_cap);
+  else if (vec)
+    hipLaunchKernelGGL((k_commit_kv<float, uint4>), grid, dim3(256), 0, s, (float*)c->kv, (float*)c->kv + c->kv_v_off, state, accept_len,
                        next_token, path, c->H, c->dh, c->kv_layer_stride, c->kv_row_stride, c->kv_head_stride, c->S_cap);
   else
-    hipLaunchKernelGGL(k_commit_kv<float>, grid, dim3(256), 0, s, (float*)c->kv, (float*)c->kv + c->kv_v_off, state, accept_len,
+    hipLaunchKernelGGL((k_commit_kv<float, float>), grid, dim3(256), 0, s, (float*)c->kv, (float*)c->kv + c->kv_v_off, state, accept_len,
                        next_token, path, c->H, c->dh, c->kv_layer_stride, c->kv_row_stride, c->kv_head_stride, c->S_cap);
   hipLaunchKernelGGL(k_commit_state, dim3((c->B + 63) / 64), dim3(64), 0, s, state, accept_len, next_token, c->B);
 }

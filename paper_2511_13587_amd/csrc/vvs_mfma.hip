@@ -14,8 +14,15 @@ namespace vvs {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes as a native vector (plain register moves)
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// Phase marks: a profiling build may define VVS_PHASE_MARK(i) to record a time stamp at the i-th
+// point of a kernel (entry, operands requested, main loop done, tile in LDS, end); normally nothing.
+#ifndef VVS_PHASE_MARK
+#define VVS_PHASE_MARK(i)
+#endif
 
 // ------------------------------------------------------------------------------------------------ GEMM
 // C[split][M][N] (fp32) = A[M][K] * W[N][K]^T with both operands pre-packed in MFMA fragment order:
@@ -57,11 +64,280 @@ struct GemmEpi {
   TreeDesc tree;
 };
 
+// Per-row RMSNorm factor of a tile's rows, from the per-slab sums of squares (1 when the GEMM is not
+// scaled), in two phases: the loads are issued when the kernel starts and their values are only used
+// after the main loop, so their latency is never waited for.  4 lanes per row (unit = row * 4 + part),
+// each takes every 4th group of 4 slabs; RU = BM * 4 / 256 units per thread.
+template <int BM>
+struct RowScale {
+  static constexpr int RU = (BM * 4 + 255) / 256;
+  float4 v[RU][4];
+  __device__ __forceinline__ void load(int tile_m, int M, const GemmEpi& ep) {
+#pragma unroll
+    for (int j = 0; j < RU; ++j) {
+      const int u = threadIdx.x + 256 * j, row = u >> 2, part = u & 3;
+      const int m = min(tile_m * BM + row, M - 1);                       // clamped rows are never stored
+      const int nq = ep.NS >> 2;                                         // rows of ss are padded to a multiple of 4 slabs (zeros)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        v[j][i] = (ep.ss && part + 4 * i < nq) ? ((const float4*)(ep.ss + (size_t)m * ep.NS))[part + 4 * i] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  }
+  __device__ __forceinline__ void finish(float* rs, int tile_m, int M, const GemmEpi& ep) {
+#pragma unroll
+    for (int j = 0; j < RU; ++j) {
+      const int u = threadIdx.x + 256 * j, row = u >> 2, part = u & 3;
+      const int m = min(tile_m * BM + row, M - 1);
+      float t = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) t += (v[j][i].x + v[j][i].y) + (v[j][i].z + v[j][i].w);
+      if (ep.ss)
+        for (int qd = part + 16; qd < (ep.NS >> 2); qd += 4) {           // more than 64 slabs: the rest is read here
+          const float4 w = ((const float4*)(ep.ss + (size_t)m * ep.NS))[qd];
+          t += (w.x + w.y) + (w.z + w.w);
+        }
+      t += __shfl_xor(t, 1, 64);
+      t += __shfl_xor(t, 2, 64);
+      if (part == 0 && row < BM) rs[row] = ep.ss ? 1.0f / sqrtf(t / (float)ep.dnorm + ep.eps) : 1.f;
+    }
+  }
+};
+
+// Epilogue inputs that do not depend on the accumulators are requested early, so that their latency
+// hides behind the main loop instead of being paid after it.
+//   EPI_RESID: the residual values the tile will be added to (requested behind the first operand loads).
+//   EPI_QKV  : a thread owns tile row tid % BM.  first() requests the cache length / emitted count
+//              behind that row's position before any operand load (loads return in order, so these
+//              come back first); after the first operand loads are on their way, rope() turns them
+//              into (slot, image index) and requests this thread's share of the row's rotary factors -
+//              contiguous 16-byte pieces of the table rows of the token's grid row and column;
+//              to_lds() leaves slot, image index and factors in LDS for the epilogue, which so reads
+//              them with a few wide LDS loads instead of 16 scattered global loads per unit.
+constexpr int kRopeNpMax = 16;   // rotary pairs per position kept in LDS (head size 64); other head sizes read the table directly
+template <int BM, int BN, int EPI>
+struct EpiPre {
+  static constexpr int UR = (BM * (BN / 8) + 255) / 256;    // EPI_RESID units (row, 8 columns) per thread
+  static constexpr int G = 256 / BM;                        // threads per tile row
+  static constexpr int NR = 2 * kRopeNpMax / G / 2;         // float4 (two factor pairs) per thread
+  int kv, ne, slot, img;
+  float4 rp[NR];
+  float4 x0[UR], x1[UR];
+
+  // m / T for 0 <= m < 2^20 (the quotient of the rounded product cannot cross an integer: the exact
+  // value is at least 0.5 / T away from one)
+  __device__ __forceinline__ static int div_T(int m, const GemmEpi& ep) { return (int)(((float)m + 0.5f) * (1.0f / (float)ep.T)); }
+
+  __device__ __forceinline__ void first(int tile_m, int M, const GemmEpi& ep) {
+    if constexpr (EPI == EPI_QKV) {
+      kv = ne = 0;
+      if (ep.pos.kv_len) {
+        const int b = div_T(min(tile_m * BM + (int)threadIdx.x % BM, M - 1), ep) >> 1;
+        kv = ep.pos.kv_len[b];
+        ne = ep.pos.n_emitted[b];
+      }
+    }
+  }
+  __device__ __forceinline__ void start(int tile_m, int tile_n, int M, int N, const GemmEpi& ep) {
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    if constexpr (EPI == EPI_QKV) {
+      const int m = min(m0 + (int)threadIdx.x % BM, M - 1), t = m - div_T(m, ep) * ep.T;
+      if (ep.pos.kv_len) {
+        slot = kv + t;
+        img = ne - 1 + ep.tree.depth[t];
+      } else {
+        slot = ep.pos.kv_base + t;
+        img = slot - ep.pos.prefix_len;
+      }
+      const int np = ep.dh >> 2;
+      if (n0 / ep.d < 2 && np == kRopeNpMax) {               // q and k columns are rotated
+        const int im = max(img, 0), gr = min(im / ep.pos.grid_w, ep.rope_pos - 1), gc = im % ep.pos.grid_w;
+        // the row's 2 * np pairs, [grid row: np][grid column: np], are dealt to its G threads in order
+        const int per = 2 * np / G, p0 = ((int)threadIdx.x / BM) * per;   // pairs per thread (even), first pair
+#pragma unroll
+        for (int i = 0; i < NR; ++i) {
+          const int pr = min(p0 + 2 * i, 2 * np - 2), pv = pr >= np ? gc : gr, ip = pr >= np ? pr - np : pr;
+          rp[i] = *(const float4*)(ep.rope + ((size_t)pv * np + ip) * 2);
+        }
+      }
+    } else if constexpr (EPI == EPI_RESID) {
+#pragma unroll
+      for (int j = 0; j < UR; ++j) {
+        const int u = threadIdx.x + 256 * j, row = min(u / (BN / 8), BM - 1), c8 = (u % (BN / 8)) * 8;
+        const float* xp = ep.x + (size_t)min(m0 + row, M - 1) * N + n0 + c8;   // clamped rows are never stored
+        x0[j] = *(const float4*)xp;
+        x1[j] = *(const float4*)(xp + 4);
+      }
+    }
+  }
+  // s_pos[BM][2] = (slot, image index); s_rope[BM][2 * kRopeNpMax] = (cos, sin) pairs, grid-row half then grid-column half
+  __device__ __forceinline__ void to_lds(int* s_pos, float2* s_rope, const GemmEpi& ep) const {
+    if constexpr (EPI == EPI_QKV) {
+      const int row = threadIdx.x % BM, g = threadIdx.x / BM, np = ep.dh >> 2;
+      if (g == 0) { s_pos[2 * row] = slot; s_pos[2 * row + 1] = img; }
+      if (np == kRopeNpMax) {
+        const int per = 2 * np / G, p0 = g * per;
+#pragma unroll
+        for (int i = 0; i < NR; ++i)
+          if (2 * i < per) *(float4*)(s_rope + row * 2 * kRopeNpMax + p0 + 2 * i) = rp[i];
+      }
+    }
+  }
+};
+
+// Epilogue of a BM x BN tile whose NP partial sums lie in LDS as red[NP][BM][BN + 4] (added in a fixed
+// order); rs holds the row factors.  Called by all 256 threads after a barrier.
+template <int BM, int BN, int NP, int EPI>
+__device__ __forceinline__ void tile_epilogue(const float* red, const float* rs, int tile_m, int tile_n, int M, int N, float* C,
+                                              const GemmEpi& ep, const EpiPre<BM, BN, EPI>& pre, const int* s_pos, const float2* s_rope) {
+  constexpr int LDC = BN + 4;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  constexpr int PS = BM * LDC;   // stride between the partial tiles
+  // sum of the partial tiles for 4 consecutive columns, fixed order
+  auto sum4 = [&](const float* p) {
+    float4 a = *(const float4*)p;
+#pragma unroll
+    for (int w = 1; w < NP; ++w) {
+      const float4 b = *(const float4*)(p + w * PS);
+      a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    return a;
+  };
+  if constexpr (EPI == EPI_PARTIAL) {
+    float* Cs = C + (size_t)blockIdx.z * M * N;
+    for (int u = threadIdx.x; u < BM * (BN / 4); u += 256) {       // one unit = (row, 4 consecutive columns)
+      const int row = u / (BN / 4), col = (u % (BN / 4)) * 4;
+      if (m0 + row < M) {
+        float4 v = sum4(red + row * LDC + col);
+        const float sc = rs[row];
+        v.x *= sc; v.y *= sc; v.z *= sc; v.w *= sc;
+        *(float4*)(Cs + (size_t)(m0 + row) * N + n0 + col) = v;
+      }
+    }
+  } else if constexpr (EPI == EPI_SWIGLU) {
+    static_assert(BN % 64 == 0, "gate / up blocks of 32 columns alternate inside the tile");
+    for (int u = threadIdx.x; u < BM * (BN / 16); u += 256) {       // one unit = (row, 8 consecutive hidden units)
+      const int row = u / (BN / 16), fl = (u % (BN / 16)) * 8;      // fl: hidden unit inside the tile, 0 .. BN/2
+      if (m0 + row >= M) continue;
+      const float* pg = red + row * LDC + (fl >> 5) * 64 + (fl & 31);
+      const float4 g0 = sum4(pg), g1 = sum4(pg + 4), u0 = sum4(pg + 32), u1 = sum4(pg + 36);
+      const float gs[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+      const float us[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+      float v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float g = gs[i] * rs[row], up = us[i] * rs[row];
+        v[i] = g / (1.0f + expf(-g)) * up;
+      }
+      store8(ep.act, m0 + row, tile_n * (BN / 2) + fl, ep.F, v);
+    }
+  } else if constexpr (EPI == EPI_RESID) {
+    static_assert(BN % 64 == 0, "the sums of squares are kept per 64-column slab");
+#pragma unroll
+    for (int j = 0; j < EpiPre<BM, BN, EPI>::UR; ++j) {            // one unit = (row, 8 consecutive columns); 8 lanes share a row and slab
+      const int u = threadIdx.x + 256 * j, row = u / (BN / 8), c8 = (u % (BN / 8)) * 8;
+      const int m = m0 + row;
+      float sq = 0.f;
+      if (row < BM && m < M) {
+        const float4 a = sum4(red + row * LDC + c8), b = sum4(red + row * LDC + c8 + 4);
+        float* xp = ep.x + (size_t)m * N + n0 + c8;
+        const float4 xa = pre.x0[j], xb4 = pre.x1[j];
+        float v[8] = {xa.x + a.x, xa.y + a.y, xa.z + a.z, xa.w + a.w, xb4.x + b.x, xb4.y + b.y, xb4.z + b.z, xb4.w + b.w};
+        *(float4*)xp = make_float4(v[0], v[1], v[2], v[3]);
+        *(float4*)(xp + 4) = make_float4(v[4], v[5], v[6], v[7]);
+        store8(ep.xb, m, n0 + c8, N, v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sq += v[i] * v[i];
+      }
+      sq += __shfl_xor(sq, 1, 64);
+      sq += __shfl_xor(sq, 2, 64);
+      sq += __shfl_xor(sq, 4, 64);
+      if (row < BM && m < M && (c8 & 63) == 0) ep.ss_out[(size_t)m * ep.NS + tile_n * (BN / 64) + (c8 >> 6)] = sq;
+    }
+  } else {
+    const int sec = n0 / ep.d;                                     // the tile lies inside the q (0), k (1) or v (2) third
+    if (sec < 2) {
+      const int half = ep.dh >> 1, np = ep.dh >> 2;
+      for (int u = threadIdx.x; u < BM * (BN / 16); u += 256) {    // one unit = (row, 16 consecutive columns)
+        const int row = u / (BN / 16), c0 = (u % (BN / 16)) * 16;
+        const int m = m0 + row;
+        if (m >= M) continue;
+        const float* p = red + row * LDC + c0;
+        const float4 s0 = sum4(p), s1 = sum4(p + 4), s2 = sum4(p + 8), s3 = sum4(p + 12);
+        float v[16] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w, s2.x, s2.y, s2.z, s2.w, s3.x, s3.y, s3.z, s3.w};
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] *= rs[row];
+        const int eg = (n0 + c0) % ep.d, hd = eg / ep.dh, e = eg % ep.dh;
+        const int slot = s_pos[2 * row], img = s_pos[2 * row + 1];
+        if (img >= 0) {
+          float2 cs[8];
+          if (np == kRopeNpMax) {
+            // 16 columns = 8 pairs inside one half of the head: 8 consecutive pairs of the row's LDS table
+            const float4* t4 = (const float4*)(s_rope + row * 2 * kRopeNpMax + (e / half) * np + ((e % half) >> 1));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float4 c4 = t4[i];
+              cs[2 * i] = make_float2(c4.x, c4.y);
+              cs[2 * i + 1] = make_float2(c4.z, c4.w);
+            }
+          } else {
+            const int gr = min(img / ep.pos.grid_w, ep.rope_pos - 1), gc = img % ep.pos.grid_w;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+              const int ei = e + 2 * i, pv = (ei / half) ? gc : gr, ip = (ei % half) >> 1;
+              cs[i] = *(const float2*)(ep.rope + ((size_t)pv * np + ip) * 2);
+            }
+          }
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const float a = v[2 * i], b = v[2 * i + 1];
+            v[2 * i] = a * cs[i].x - b * cs[i].y;
+            v[2 * i + 1] = a * cs[i].y + b * cs[i].x;
+          }
+        }
+        uint32_t w[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) w[i] = (uint32_t)f2bf(v[2 * i]) | ((uint32_t)f2bf(v[2 * i + 1]) << 16);
+        uint4* dst = nullptr;
+        if (sec == 0) dst = (uint4*)(ep.q + (size_t)m * ep.d + eg);
+        else if (slot >= 0 && slot < ep.S_cap)
+          dst = (uint4*)(ep.kc + (size_t)EpiPre<BM, BN, EPI>::div_T(m, ep) * ep.row_stride + (size_t)hd * ep.head_stride + (size_t)slot * ep.dh + e);
+        if (dst) {
+          dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+          dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+        }
+      }
+    } else {
+      // v: the cache keeps the 32 slots of a dim contiguous, so a lane takes one row (token) and the lanes of
+      // a wave cover consecutive tokens: one store instruction then writes runs of consecutive slots of one
+      // dim instead of 64 different lines.  A thread reads 4 consecutive columns (float4) of its row.
+      constexpr int G = 256 / BM;                                  // threads per row
+      const int row = threadIdx.x % BM, g = threadIdx.x / BM, m = m0 + row;
+      const int slot = pre.slot;                                   // this thread's row is the one it looked up
+      if (m < M && slot >= 0 && slot < ep.S_cap) {
+        const float sc = rs[row];
+        bf16_t* vrow = ep.vc + (size_t)EpiPre<BM, BN, EPI>::div_T(m, ep) * ep.row_stride;
+#pragma unroll 4
+        for (int c4 = g * 4; c4 < BN; c4 += G * 4) {
+          const float4 v = sum4(red + row * LDC + c4);
+          const int eg = (n0 + c4) % ep.d, hd = eg / ep.dh, e = eg % ep.dh;   // 4 columns stay inside one head (head size % 4 == 0)
+          bf16_t* vh = vrow + (size_t)hd * ep.head_stride;
+          vh[v_index(slot, e, ep.dh)] = f2bf(v.x * sc);
+          vh[v_index(slot, e + 1, ep.dh)] = f2bf(v.y * sc);
+          vh[v_index(slot, e + 2, ep.dh)] = f2bf(v.z * sc);
+          vh[v_index(slot, e + 3, ep.dh)] = f2bf(v.w * sc);
+        }
+      }
+    }
+  }
+}
+
+
 template <int TM, int TN, int D, int EPI>
 __global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ Ap, const uint4* __restrict__ Wp, float* __restrict__ C,
                                                      int M, int N, int K, int kb_per_split, const GemmEpi ep) {
   constexpr int BM = TM * 32, BN = TN * 32, LDC = BN + 4;
   extern __shared__ float red[];           // [4][BM][LDC]
+  VVS_PHASE_MARK(0);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   // XCD-aware tile order.  Workgroups are dealt to the 8 XCDs round-robin by linear id, and each XCD
   // has its own L2.  Column tiles are taken in groups of 8 (one per XCD); inside a group the row
@@ -75,25 +351,12 @@ __global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ A
     tile_m = rem / cols;
     tile_n = grp * 8 + rem % cols;
   }
-  __shared__ float rs[BM];                 // per-row RMSNorm factor of this tile's rows (loaded first: hidden behind the main loop)
-  if (threadIdx.x < BM * 4) {              // 4 lanes per row, each sums every 4th group of 4 slabs: all loads independent
-    const int row = threadIdx.x >> 2, part = threadIdx.x & 3;
-    const int m = tile_m * BM + row;
-    float t = 0.f;
-    if (ep.ss && m < M) {
-      const float4* p4 = (const float4*)(ep.ss + (size_t)m * ep.NS);     // rows are padded to a multiple of 4 slabs (zeros)
-      const int nq = ep.NS >> 2;
-      float4 v[4];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) v[i] = (part + 4 * i < nq) ? p4[part + 4 * i] : make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) t += (v[i].x + v[i].y) + (v[i].z + v[i].w);
-      for (int qd = part + 16; qd < nq; qd += 4) { const float4 w = p4[qd]; t += (w.x + w.y) + (w.z + w.w); }
-    }
-    t += __shfl_xor(t, 1, 64);
-    t += __shfl_xor(t, 2, 64);
-    if (part == 0) rs[row] = (ep.ss && m < M) ? 1.0f / sqrtf(t / (float)ep.dnorm + ep.eps) : 1.f;
-  }
+  __shared__ float rs[BM];                 // per-row RMSNorm factor of this tile's rows
+  __shared__ int s_pos[EPI == EPI_QKV ? 2 * BM : 2];                                  // EPI_QKV: (slot, image index) per tile row
+  __shared__ __align__(16) float2 s_rope[EPI == EPI_QKV ? BM * 2 * kRopeNpMax : 2];   // EPI_QKV: rotary factors per tile row
+  EpiPre<BM, BN, EPI> pre;
+  pre.first(tile_m, M, ep);
+  __builtin_amdgcn_sched_barrier(0);
   const int KB = K >> 4;
   const int s0 = blockIdx.z * kb_per_split, s1 = min(KB, s0 + kb_per_split);
   const int per_w = (max(s1 - s0, 0) + 3) >> 2;
@@ -102,7 +365,7 @@ __global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ A
   const uint4* ap[TM];
   const uint4* bp[TN];
 #pragma unroll
-  for (int t = 0; t < TM; ++t) ap[t] = Ap + ((size_t)(tile_m * TM + t) * KB) * 64 + lane;
+  for (int t = 0; t < TM; ++t) ap[t] = Ap + ((size_t)min(tile_m * TM + t, (M - 1) >> 5) * KB) * 64 + lane;   // row blocks past the end repeat the last one
 #pragma unroll
   for (int t = 0; t < TN; ++t) bp[t] = Wp + ((size_t)(tile_n * TN + t) * KB) * 64 + lane;
   floatx16 acc[TM][TN];
@@ -124,6 +387,12 @@ __global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ A
     // (D-1) younger groups", never "everything"
     __builtin_amdgcn_sched_barrier(0);
   }
+  // epilogue inputs: requested behind the first operand loads (nothing waits for them before the main loop ends)
+  RowScale<BM> rowscale;
+  rowscale.load(tile_m, M, ep);
+  pre.start(tile_m, tile_n, M, N, ep);
+  __builtin_amdgcn_sched_barrier(0);
+  VVS_PHASE_MARK(1);
   for (int kb = 0; kb < nk; kb += D) {
 #pragma unroll
     for (int i = 0; i < D; ++i) {
@@ -142,6 +411,9 @@ __global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ A
       __builtin_amdgcn_sched_barrier(0);
     }
   }
+  VVS_PHASE_MARK(2);
+  pre.to_lds(s_pos, s_rope, ep);
+  rowscale.finish(rs, tile_m, M, ep);
   // publish the partial tile: acc[i][j][r] is row i*32 + 8*(r/4) + 4*(lane/32) + r%4, col j*32 + lane%32
   float* mine = red + (size_t)wave * BM * LDC;
 #pragma unroll
@@ -152,109 +424,164 @@ __global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ A
       for (int r = 0; r < 16; ++r)
         mine[(i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * LDC + j * 32 + (lane & 31)] = acc[i][j][r];
   __syncthreads();
-  const int m0 = tile_m * BM, n0 = tile_n * BN;
-  constexpr int PS = BM * LDC;   // stride between the waves' partial tiles
-  // sum of the four waves' partial tiles for 4 consecutive columns, fixed order
-  auto sum4 = [&](const float* p) {
-    const float4 a = *(const float4*)p, b = *(const float4*)(p + PS), c = *(const float4*)(p + 2 * PS), d = *(const float4*)(p + 3 * PS);
-    return make_float4(((a.x + b.x) + c.x) + d.x, ((a.y + b.y) + c.y) + d.y, ((a.z + b.z) + c.z) + d.z, ((a.w + b.w) + c.w) + d.w);
-  };
-  if constexpr (EPI == EPI_PARTIAL) {
-    float* Cs = C + (size_t)blockIdx.z * M * N;
-    for (int u = threadIdx.x; u < BM * (BN / 4); u += 256) {       // one unit = (row, 4 consecutive columns)
-      const int row = u / (BN / 4), col = (u % (BN / 4)) * 4;
-      if (m0 + row < M) {
-        float4 v = sum4(red + row * LDC + col);
-        const float sc = rs[row];
-        v.x *= sc; v.y *= sc; v.z *= sc; v.w *= sc;
-        *(float4*)(Cs + (size_t)(m0 + row) * N + n0 + col) = v;
-      }
-    }
-  } else if constexpr (EPI == EPI_SWIGLU) {
-    static_assert(TN % 2 == 0, "gate / up blocks of 32 columns alternate inside the tile");
-    for (int u = threadIdx.x; u < BM * (BN / 16); u += 256) {       // one unit = (row, 8 consecutive hidden units)
-      const int row = u / (BN / 16), fl = (u % (BN / 16)) * 8;      // fl: hidden unit inside the tile, 0 .. BN/2
-      if (m0 + row >= M) continue;
-      const float* pg = red + row * LDC + (fl >> 5) * 64 + (fl & 31);
-      const float4 g0 = sum4(pg), g1 = sum4(pg + 4), u0 = sum4(pg + 32), u1 = sum4(pg + 36);
-      const float gs[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
-      const float us[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
-      float v[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const float g = gs[i] * rs[row], up = us[i] * rs[row];
-        v[i] = g / (1.0f + expf(-g)) * up;
-      }
-      store8(ep.act, m0 + row, tile_n * (BN / 2) + fl, ep.F, v);
-    }
-  } else if constexpr (EPI == EPI_RESID) {
-    static_assert(BN == 64, "the sums of squares are kept per 64-column slab");
-    for (int u = threadIdx.x; u < BM * 8; u += 256) {              // one unit = (row, 8 consecutive columns); 8 lanes share a row
-      const int row = u >> 3, c8 = (u & 7) * 8;
-      const int m = m0 + row;
-      float sq = 0.f;
-      if (m < M) {
-        const float4 a = sum4(red + row * LDC + c8), b = sum4(red + row * LDC + c8 + 4);
-        float* xp = ep.x + (size_t)m * N + n0 + c8;
-        const float4 xa = *(const float4*)xp, xb4 = *(const float4*)(xp + 4);
-        float v[8] = {xa.x + a.x, xa.y + a.y, xa.z + a.z, xa.w + a.w, xb4.x + b.x, xb4.y + b.y, xb4.z + b.z, xb4.w + b.w};
-        *(float4*)xp = make_float4(v[0], v[1], v[2], v[3]);
-        *(float4*)(xp + 4) = make_float4(v[4], v[5], v[6], v[7]);
-        store8(ep.xb, m, n0 + c8, N, v);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) sq += v[i] * v[i];
-      }
-      sq += __shfl_xor(sq, 1, 64);
-      sq += __shfl_xor(sq, 2, 64);
-      sq += __shfl_xor(sq, 4, 64);
-      if (m < M && c8 == 0) ep.ss_out[(size_t)m * ep.NS + tile_n] = sq;
-    }
-  } else {
-    const int half = ep.dh >> 1, np = ep.dh >> 2;
-    for (int u = threadIdx.x; u < BM * (BN / 16); u += 256) {   // one unit = (row, 16 consecutive columns)
-      const int row = u / (BN / 16), c0 = (u % (BN / 16)) * 16;
-      const int m = m0 + row;
-      if (m >= M) continue;
-      const float* p = red + row * LDC + c0;
-      const float4 s0 = sum4(p), s1 = sum4(p + 4), s2 = sum4(p + 8), s3 = sum4(p + 12);
-      float v[16] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w, s2.x, s2.y, s2.z, s2.w, s3.x, s3.y, s3.z, s3.w};
-#pragma unroll
-      for (int i = 0; i < 16; ++i) v[i] *= rs[row];
-      const int n = n0 + c0, sec = n / ep.d, eg = n % ep.d, hd = eg / ep.dh, e = eg % ep.dh;
-      const int r = m / ep.T, t = m % ep.T;
-      int slot, img;
-      token_pos(ep.pos, ep.tree, r, t, &slot, &img);
-      if (sec < 2 && img >= 0) {
-        const int gr = min(img / ep.pos.grid_w, ep.rope_pos - 1), gc = img % ep.pos.grid_w;
-#pragma unroll
-        for (int i = 0; i < 16; i += 2) {
-          const int ei = e + i, pv = (ei / half) ? gc : gr, ip = (ei % half) >> 1;
-          const float cs = ep.rope[((size_t)pv * np + ip) * 2], sn = ep.rope[((size_t)pv * np + ip) * 2 + 1];
-          const float a = v[i], b = v[i + 1];
-          v[i] = a * cs - b * sn;
-          v[i + 1] = a * sn + b * cs;
-        }
-      }
-      uint32_t w[8];
-#pragma unroll
-      for (int i = 0; i < 8; ++i) w[i] = (uint32_t)f2bf(v[2 * i]) | ((uint32_t)f2bf(v[2 * i + 1]) << 16);
-      if (sec == 0) {
-        uint4* dst = (uint4*)(ep.q + (size_t)m * ep.d + eg);
-        dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
-        dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
-      } else if (slot >= 0 && slot < ep.S_cap) {
-        const size_t hb = (size_t)r * ep.row_stride + (size_t)hd * ep.head_stride;
-        if (sec == 1) {
-          uint4* dst = (uint4*)(ep.kc + hb + (size_t)slot * ep.dh + e);
-          dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
-          dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
-        } else {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) ep.vc[hb + v_index(slot, e + i, ep.dh)] = (bf16_t)(w[i >> 1] >> ((i & 1) * 16));
-        }
-      }
-    }
+  VVS_PHASE_MARK(3);
+  tile_epilogue<BM, BN, 4, EPI>(red, rs, tile_m, tile_n, M, N, C, ep, pre, s_pos, s_rope);
+  VVS_PHASE_MARK(4);
+}
+
+// Shared-operand variant for projections with enough output tiles: a workgroup owns a
+// (2*WM*32) x (2*WN*32) tile, its 4 waves form a 2 x 2 grid of (WM*32) x (WN*32) sub-tiles and all of
+// them read the A and B fragments from LDS, so every operand byte that comes through the CU's L1 feeds
+// twice as many MFMAs as in k_gemm_direct.  A stage is 32 contraction indices = 2 fragment blocks per
+// 32 rows; the blocks are copied global -> registers -> LDS as they are (the packed layout is already
+// the LDS layout the MFMA lanes want).
+// Software pipeline (one wave per SIMD, so nothing else hides latencies): global loads run D stages
+// ahead in registers; LDS holds 3 stages; in iteration s a wave requests the second half of stage s from
+// LDS, moves stage s+2 from registers to LDS and re-requests those registers from memory, multiplies
+// the first half of stage s, requests the first half of stage s+1 and multiplies the second half:
+// every MFMA group runs on fragments requested one group earlier.  One barrier per stage: it orders
+// the LDS writes of stage s+2 before their reads in iteration s+1 and the reads of stage s before the
+// slot is overwritten in iteration s+1.  The epilogues are the same as above with a single partial tile.
+template <int WM, int WN, int D, int EPI>
+__global__ __launch_bounds__(256) void k_gemm_shared(const uint4* __restrict__ Ap, const uint4* __restrict__ Wp, float* __restrict__ C,
+                                                     int M, int N, int K, const GemmEpi ep) {
+  constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32, LDC = BN + 4;
+  constexpr int NA = 2 * (BM / 32), NBLK = NA + 2 * (BN / 32), PER = NBLK / 4;   // 1 KiB blocks per stage; per wave
+  static_assert(NBLK % 4 == 0, "blocks of a stage are dealt to 4 waves");
+  static_assert(D % 3 == 0, "register ring and LDS ring indices are both static after unrolling by D");
+  extern __shared__ float red[];           // main loop: u32x4 stage[3][NBLK][64]; afterwards: float [BM][LDC]
+  u32x4* stage = (u32x4*)red;
+  VVS_PHASE_MARK(0);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wr = wave >> 1, wc = wave & 1;
+  const int MT = (M + BM - 1) / BM, NT = N / BN;
+  int tile_m, tile_n;
+  {                                        // same XCD-aware order as k_gemm_direct
+    const int id = blockIdx.x, grp = id / (8 * MT), rem = id % (8 * MT);
+    const int cols = min(8, NT - grp * 8);
+    tile_m = rem / cols;
+    tile_n = grp * 8 + rem % cols;
   }
+  __shared__ float rs[BM];
+  __shared__ int s_pos[EPI == EPI_QKV ? 2 * BM : 2];                                  // EPI_QKV: (slot, image index) per tile row
+  __shared__ __align__(16) float2 s_rope[EPI == EPI_QKV ? BM * 2 * kRopeNpMax : 2];   // EPI_QKV: rotary factors per tile row
+  EpiPre<BM, BN, EPI> pre;
+  pre.first(tile_m, M, ep);
+  __builtin_amdgcn_sched_barrier(0);
+  const int KB = K >> 4, nst = KB >> 1;
+  const int last_rb = (M - 1) >> 5;        // row blocks past the end of A repeat the last one (their rows are never stored)
+  // block j of a stage: j < NA: A row block j/2, else B row block (j-NA)/2; contraction block 2*s + j%2
+  const u32x4* src[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int j = wave + 4 * i;
+    const int rb = j < NA ? min(tile_m * (BM / 32) + (j >> 1), last_rb) : tile_n * (BN / 32) + ((j - NA) >> 1);
+    src[i] = (const u32x4*)(j < NA ? Ap : Wp) + ((size_t)rb * KB + (j & 1)) * 64 + lane;
+  }
+  floatx16 acc[WM][WN];
+#pragma unroll
+  for (int i = 0; i < WM; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  // stage t lives in st[t % D] until it is written to LDS slot t % 3; stages past the end repeat the last one
+  u32x4 st[D][PER];
+#define VVS_G2R(RD, T)                                                                                                \
+  {                                                                                                                   \
+    const size_t kk = (size_t)min((T), nst - 1) * 128;                                                                \
+    _Pragma("unroll") for (int i = 0; i < PER; ++i) st[RD][i] = src[i][kk];                                           \
+    __builtin_amdgcn_sched_barrier(0); /* load groups stay in program order: waits are partial */                     \
+  }
+#define VVS_R2S(RD, SL) \
+  { _Pragma("unroll") for (int i = 0; i < PER; ++i) stage[((SL) * NBLK + wave + 4 * i) * 64 + lane] = st[RD][i]; }
+#define VVS_S2F(FA, FB, SL, KBO)                                                                                      \
+  {                                                                                                                   \
+    _Pragma("unroll") for (int t = 0; t < WM; ++t)                                                                    \
+        FA[t] = __builtin_bit_cast(bf16x8, stage[((SL) * NBLK + (wr * WM + t) * 2 + (KBO)) * 64 + lane]);             \
+    _Pragma("unroll") for (int t = 0; t < WN; ++t)                                                                    \
+        FB[t] = __builtin_bit_cast(bf16x8, stage[((SL) * NBLK + NA + (wc * WN + t) * 2 + (KBO)) * 64 + lane]);        \
+  }
+#define VVS_MMA(FA, FB)                                                                                               \
+  {                                                                                                                   \
+    _Pragma("unroll") for (int ti = 0; ti < WM; ++ti)                                                                 \
+        _Pragma("unroll") for (int tj = 0; tj < WN; ++tj)                                                             \
+            acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FA[ti], FB[tj], acc[ti][tj], 0, 0, 0);              \
+  }
+#pragma unroll
+  for (int d = 0; d < D; ++d) VVS_G2R(d, d)
+  // epilogue inputs: requested behind the first operand loads (nothing waits for them before the main loop ends)
+  RowScale<BM> rowscale;
+  rowscale.load(tile_m, M, ep);
+  pre.start(tile_m, tile_n, M, N, ep);
+  __builtin_amdgcn_sched_barrier(0);
+  VVS_PHASE_MARK(1);
+  VVS_R2S(0, 0)
+  VVS_G2R(0, D)
+  VVS_R2S(1, 1)
+  VVS_G2R(1, D + 1)
+  __syncthreads();
+  bf16x8 fa0[WM], fb0[WN], fa1[WM], fb1[WN];
+  VVS_S2F(fa0, fb0, 0, 0)
+  // iteration S with d = S % D (so S % 3 == d % 3)
+#define VVS_ITER(S)                                                                                                   \
+  {                                                                                                                   \
+    VVS_S2F(fa1, fb1, d % 3, 1)                                                                                       \
+    __builtin_amdgcn_sched_barrier(0);                                                                                \
+    VVS_R2S((d + 2) % D, (d + 2) % 3)                                                                                 \
+    VVS_G2R((d + 2) % D, (S) + 2 + D)                                                                                 \
+    VVS_MMA(fa0, fb0)                                                                                                 \
+    __builtin_amdgcn_sched_barrier(0);                                                                                \
+    VVS_S2F(fa0, fb0, (d + 1) % 3, 0)                                                                                 \
+    __builtin_amdgcn_sched_barrier(0);                                                                                \
+    VVS_MMA(fa1, fb1)                                                                                                 \
+    __syncthreads();                                                                                                  \
+  }
+  // whole groups of D iterations run without any condition, so that the wait before a stage's LDS
+  // write is "all but the D-1 younger load groups"
+  int s0 = 0;
+  for (; s0 + D <= nst; s0 += D) {
+#pragma unroll
+    for (int d = 0; d < D; ++d) VVS_ITER(s0 + d)
+  }
+#pragma unroll
+  for (int d = 0; d < D; ++d)
+    if (s0 + d < nst) VVS_ITER(s0 + d)                         // uniform over the workgroup
+#undef VVS_ITER
+#undef VVS_MMA
+#undef VVS_S2F
+#undef VVS_R2S
+#undef VVS_G2R
+  VVS_PHASE_MARK(2);
+  pre.to_lds(s_pos, s_rope, ep);
+  rowscale.finish(rs, tile_m, M, ep);
+  __syncthreads();                         // the stage buffers become the output tile
+#pragma unroll
+  for (int i = 0; i < WM; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        red[((wr * WM + i) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * LDC + (wc * WN + j) * 32 + (lane & 31)] = acc[i][j][r];
+  __syncthreads();
+  VVS_PHASE_MARK(3);
+  tile_epilogue<BM, BN, 1, EPI>(red, rs, tile_m, tile_n, M, N, C, ep, pre, s_pos, s_rope);
+  VVS_PHASE_MARK(4);
+}
+
+template <int WM, int WN, int D, int EPI>
+static void launch_gemm_shared(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, const GemmEpi& ep, hipStream_t s) {
+  constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32;
+  constexpr size_t lds_tile = (size_t)BM * (BN + 4) * sizeof(float), lds_stage = (size_t)3 * (2 * (BM + BN) / 32) * 1024;
+  constexpr size_t lds = lds_tile > lds_stage ? lds_tile : lds_stage;
+  static bool configured = false;
+  if (!configured) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_shared<WM, WN, D, EPI>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)lds);
+    configured = true;
+  }
+  dim3 grid((N / BN) * ((M + BM - 1) / BM), 1, 1);
+  hipLaunchKernelGGL((k_gemm_shared<WM, WN, D, EPI>), grid, dim3(256), lds, s, (const uint4*)A, (const uint4*)W, C, M, N, K, ep);
 }
 
 template <int TM, int TN, int D, int EPI>
@@ -275,6 +602,9 @@ static void launch_gemm_direct(const bf16_t* A, const bf16_t* W, float* C, int M
 
 template <int EPI>
 static void gemm_dispatch(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, GemmPlan p, const GemmEpi& ep, hipStream_t s) {
+  if constexpr (EPI != EPI_RESID) {
+    if (p.bm == 128 && p.bn == 128) { launch_gemm_shared<2, 2, 6, EPI>(A, W, C, M, N, K, ep, s); return; }
+  }
   if (p.bm == 32) launch_gemm_direct<1, 2, 8, EPI>(A, W, C, M, N, K, p.splits, ep, s);
   else if (p.bn == 128) launch_gemm_direct<2, 4, 4, EPI>(A, W, C, M, N, K, p.splits, ep, s);
   else launch_gemm_direct<2, 2, 6, EPI>(A, W, C, M, N, K, p.splits, ep, s);
@@ -338,13 +668,14 @@ void mfma_gemm_qkv(Ctx* c, int layer, const bf16_t* A, const bf16_t* Wqkv, const
 // loaded straight from the cache into MFMA operand registers - every key is used by exactly one wave,
 // so there is nothing to share through LDS; the 4 waves take 32-key steps round-robin and merge their
 // partial (max, sum, O) through LDS at the end.  Only the last T keys (the block itself) are masked.
-template <int DH, int NQB, int NW>
-__global__ __launch_bounds__(NW * 64) void k_attn_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc,
+template <int DH, int NQB, int NW, int PD>
+__global__ __launch_bounds__(NW * 64, (DH * NQB >= 256 ? 1 : 2)) void k_attn_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc,
                                                    const bf16_t* __restrict__ vc, bf16_t* __restrict__ out, TreeDesc tree,
                                                    PosDesc pos, int T, int d, size_t row_stride, size_t head_stride, float c_exp) {
   constexpr int KD = DH / 32, DT = DH / 16, NQ = NQB * 16;
   __shared__ float s_m[NW - 1][NQ], s_l[NW - 1][NQ];
   __shared__ float s_o[NW - 1][NQ][DH + 1];
+  VVS_PHASE_MARK(0);
   const int hd = blockIdx.x, r = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = lane >> 4, ql = lane & 15;
@@ -389,72 +720,78 @@ __global__ __launch_bounds__(NW * 64) void k_attn_mfma(const bf16_t* __restrict_
     _Pragma("unroll") for (int dt = 0; dt < DT; ++dt)                                                                 \
         VF[dt] = as_bf16x8(*(const uint4*)(vb + ((size_t)(STEP) * DH + dt * 16 + ql) * 32 + g * 8));                  \
   }
-  bf16x8 kf[2][KD], vf[DT], kn[2][KD], vn[DT];
-  VVS_ATTN_LOAD(min(wave, nsteps - 1), kf, vf);
-  for (int step = wave; step < nsteps; step += NW) {
-    const int key0 = step << 5;
-    // next step's operands are requested before this step's are used (the last iteration re-requests its own)
-    VVS_ATTN_LOAD(step + NW < nsteps ? step + NW : step, kn, vn);
-    const bool tail = key0 + 32 > S;
+  // A wave requests the operands of PD of its steps at once and then works through them, so that one
+  // memory latency covers PD steps (a whole call at the usual cache lengths).
+  for (int base = wave; base < nsteps; base += NW * PD) {
+    bf16x8 kf[PD][2][KD], vf[PD][DT];
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-      floatx4 s2[2];
+    for (int p = 0; p < PD; ++p) {
+      const int st = min(base + p * NW, nsteps - 1);   // clamped: past the end the previous request is repeated
+      VVS_ATTN_LOAD(st, kf[p], vf[p]);
+    }
+    VVS_PHASE_MARK(1);
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        s2[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int p = 0; p < PD; ++p) {
+      const int step = base + p * NW;
+      if (step >= nsteps) break;
+      const int key0 = step << 5;
+      const bool tail = key0 + 32 > S;
 #pragma unroll
-        for (int kd = 0; kd < KD; ++kd) s2[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t][kd], qf[qb][kd], s2[t], 0, 0, 0);
-      }
-      float sv[8];
+      for (int qb = 0; qb < NQB; ++qb) {
+        floatx4 s2[2];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) sv[i] = s2[i >> 2][i & 3];
-      if (tail) {
+        for (int t = 0; t < 2; ++t) {
+          s2[t] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const int key = key0 + 8 * g + i;
-          bool vis = key < S;
-          if (!vis && key < n_keys) vis = (mask[qb] >> (key - S)) & 1ull;
-          if (!vis) sv[i] = -INFINITY;
+          for (int kd = 0; kd < KD; ++kd)
+            s2[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[p][t][kd], qf[qb][kd], s2[t], 0, 0, 0);
+        }
+        float sv[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) sv[i] = s2[i >> 2][i & 3];
+        if (tail) {
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const int key = key0 + 8 * g + i;
+            bool vis = key < S;
+            if (!vis && key < n_keys) vis = (mask[qb] >> (key - S)) & 1ull;
+            if (!vis) sv[i] = -INFINITY;
+          }
+        }
+        float mx = sv[0];
+#pragma unroll
+        for (int i = 1; i < 8; ++i) mx = fmaxf(mx, sv[i]);
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run[qb], mx);
+        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = exp2f((m_run[qb] - m_safe) * c_exp);
+        uint32_t pk[4];
+        float rs = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; i += 2) {
+          const bf16_t p0 = f2bf(exp2f((sv[i] - m_safe) * c_exp));
+          const bf16_t p1 = f2bf(exp2f((sv[i + 1] - m_safe) * c_exp));
+          rs += bf2f(p0) + bf2f(p1);
+          pk[i >> 1] = (uint32_t)p0 | ((uint32_t)p1 << 16);
+        }
+        rs += __shfl_xor(rs, 16, 64);
+        rs += __shfl_xor(rs, 32, 64);
+        l_run[qb] = l_run[qb] * alpha + rs;
+        m_run[qb] = m_new;
+        const bf16x8 pf = as_bf16x8(make_uint4(pk[0], pk[1], pk[2], pk[3]));
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) o[qb][dt][rr] *= alpha;
+          o[qb][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[p][dt], pf, o[qb][dt], 0, 0, 0);
         }
       }
-      float mx = sv[0];
-#pragma unroll
-      for (int i = 1; i < 8; ++i) mx = fmaxf(mx, sv[i]);
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run[qb], mx);
-      const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-      const float alpha = exp2f((m_run[qb] - m_safe) * c_exp);
-      uint32_t pk[4];
-      float rs = 0.f;
-#pragma unroll
-      for (int i = 0; i < 8; i += 2) {
-        const bf16_t p0 = f2bf(exp2f((sv[i] - m_safe) * c_exp));
-        const bf16_t p1 = f2bf(exp2f((sv[i + 1] - m_safe) * c_exp));
-        rs += bf2f(p0) + bf2f(p1);
-        pk[i >> 1] = (uint32_t)p0 | ((uint32_t)p1 << 16);
-      }
-      rs += __shfl_xor(rs, 16, 64);
-      rs += __shfl_xor(rs, 32, 64);
-      l_run[qb] = l_run[qb] * alpha + rs;
-      m_run[qb] = m_new;
-      const bf16x8 pf = as_bf16x8(make_uint4(pk[0], pk[1], pk[2], pk[3]));
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr) o[qb][dt][rr] *= alpha;
-        o[qb][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf, o[qb][dt], 0, 0, 0);
-      }
     }
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int kd = 0; kd < KD; ++kd) kf[t][kd] = kn[t][kd];
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) vf[dt] = vn[dt];
   }
 #undef VVS_ATTN_LOAD
 
+  VVS_PHASE_MARK(2);
   // merge the waves' partial results (waves 1.. publish, wave 0 combines and writes)
   if (wave > 0) {
 #pragma unroll
@@ -468,6 +805,7 @@ __global__ __launch_bounds__(NW * 64) void k_attn_mfma(const bf16_t* __restrict_
     }
   }
   __syncthreads();
+  VVS_PHASE_MARK(3);
   if (wave == 0) {
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
@@ -504,6 +842,7 @@ __global__ __launch_bounds__(NW * 64) void k_attn_mfma(const bf16_t* __restrict_
       }
     }
   }
+  VVS_PHASE_MARK(4);
 }
 
 void mfma_attention(Ctx* c, int layer, const TreeDesc& tree, const PosDesc& pos, int T, hipStream_t s) {
@@ -514,15 +853,15 @@ void mfma_attention(Ctx* c, int layer, const TreeDesc& tree, const PosDesc& pos,
   const float c_exp = 1.4426950408889634f / sqrtf((float)c->dh);
   dim3 grid(c->H, c->R);
   const int nqb = T <= 16 ? 1 : (T <= 32 ? 2 : 4);
-#define VVS_ATTN(DH, NQB, NW)                                                                                                  \
-  hipLaunchKernelGGL((k_attn_mfma<DH, NQB, NW>), grid, dim3(NW * 64), 0, s, q, kc, vc, out, tree, pos, T, c->d, c->kv_row_stride, \
+#define VVS_ATTN(DH, NQB, NW, PD)                                                                                                 \
+  hipLaunchKernelGGL((k_attn_mfma<DH, NQB, NW, PD>), grid, dim3(NW * 64), 0, s, q, kc, vc, out, tree, pos, T, c->d, c->kv_row_stride, \
                      c->kv_head_stride, c_exp)
   // 4 waves per workgroup keep the register footprint low enough for 2-3 workgroups per CU, so that
   // every (head, row) pair of a call is resident at once
   if (c->dh == 64) {
-    if (nqb == 1) VVS_ATTN(64, 1, 4); else if (nqb == 2) VVS_ATTN(64, 2, 4); else VVS_ATTN(64, 4, 4);
+    if (nqb == 1) VVS_ATTN(64, 1, 4, 4); else if (nqb == 2) VVS_ATTN(64, 2, 4, 4); else VVS_ATTN(64, 4, 4, 2);
   } else {
-    if (nqb == 1) VVS_ATTN(128, 1, 4); else VVS_ATTN(128, 2, 4);   // T <= 32 is enforced at context creation for head size 128
+    if (nqb == 1) VVS_ATTN(128, 1, 4, 2); else VVS_ATTN(128, 2, 4, 2);   // T <= 32 is enforced at context creation for head size 128
   }
 #undef VVS_ATTN
 }
