@@ -246,7 +246,7 @@ def main():
         n_launch = classes["gemm"]["launches_per_step"]
         t_launch = classes["gemm"]["ms_per_step"] * 1e-3 / n_launch
         bytes_launch, flops_launch = cnt["w_bytes"] / n_launch, cnt["gemm_flops"] / n_launch
-        kernel = "k_gemm_direct (all bf16 projection GEMMs of one verify call)"
+        kernel = "k_gemm_direct + k_gemm_shared (all bf16 projection GEMMs of one verify call)"
     else:
         n_launch = classes["attention"]["launches_per_step"]
         t_launch = classes["attention"]["ms_per_step"] * 1e-3 / n_launch

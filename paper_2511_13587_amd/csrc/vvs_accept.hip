@@ -88,25 +88,62 @@ __global__ __launch_bounds__(1024) void k_accept_node(AcceptArgs a, TreeDesc tre
   float* Q = P + V;
   float* prow = a.probs + (size_t)(b * T + j) * V;
 
-  // CFG mix + softmax (temperature 1) over the allowed slice
-  float mx = -INFINITY;
-  for (int v = tid; v < V; v += nt) {
-    const float m = lu[v] + a.scale * (lc[v] - lu[v]);
-    P[v] = m;
-    mx = fmaxf(mx, m);
-  }
-  mx = block_max(mx, red);
-  float sum = 0.f;
-  for (int v = tid; v < V; v += nt) {
-    const float e = expf(P[v] - mx);
-    P[v] = e;
-    sum += e;
-  }
-  sum = block_sum(sum, red);
-  for (int v = tid; v < V; v += nt) {
-    const float p = P[v] / sum;
-    P[v] = p;
-    prow[v] = p;
+  // CFG mix + softmax (temperature 1) over the allowed slice.  Up to 16 ids per thread (the usual
+  // codebook sizes) stay in registers: all logits are requested at once instead of one dependent
+  // memory round trip per pass of a loop; larger slices take the generic loops.
+  constexpr int RK = 16;
+  if (V <= RK * nt) {
+    float m[RK];
+    float lcv[RK], luv[RK];
+#pragma unroll
+    for (int k = 0; k < RK; ++k) {
+      const int v = min(tid + k * nt, V - 1);                // clamped: repeats are masked below
+      lcv[k] = lc[v];
+      luv[k] = lu[v];
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < RK; ++k) {
+      m[k] = tid + k * nt < V ? luv[k] + a.scale * (lcv[k] - luv[k]) : -INFINITY;
+      mx = fmaxf(mx, m[k]);
+    }
+    mx = block_max(mx, red);
+    float sum = 0.f;
+#pragma unroll
+    for (int k = 0; k < RK; ++k) {
+      m[k] = tid + k * nt < V ? expf(m[k] - mx) : 0.f;
+      sum += m[k];
+    }
+    sum = block_sum(sum, red);
+#pragma unroll
+    for (int k = 0; k < RK; ++k) {
+      const int v = tid + k * nt;
+      if (v < V) {
+        const float pv = m[k] / sum;
+        P[v] = pv;
+        prow[v] = pv;
+      }
+    }
+  } else {
+    float mx = -INFINITY;
+    for (int v = tid; v < V; v += nt) {
+      const float m = lu[v] + a.scale * (lc[v] - lu[v]);
+      P[v] = m;
+      mx = fmaxf(mx, m);
+    }
+    mx = block_max(mx, red);
+    float sum = 0.f;
+    for (int v = tid; v < V; v += nt) {
+      const float e = expf(P[v] - mx);
+      P[v] = e;
+      sum += e;
+    }
+    sum = block_sum(sum, red);
+    for (int v = tid; v < V; v += nt) {
+      const float p = P[v] / sum;
+      P[v] = p;
+      prow[v] = p;
+    }
   }
   __syncthreads();
 
@@ -124,7 +161,14 @@ __global__ __launch_bounds__(1024) void k_accept_node(AcceptArgs a, TreeDesc tre
   int accepted = 0;
   if (tree.first_child[j] >= 0 && tree.depth[j] < cap) {
     const float* qrow = a.q + (size_t)(b * T + j) * V;
-    for (int v = tid; v < V; v += nt) Q[v] = qrow[v];
+    for (int v0 = tid; v0 < V; v0 += 8 * nt) {               // 8 independent requests per thread and pass
+      float qv[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) qv[k] = qrow[min(v0 + k * nt, V - 1)];
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        if (v0 + k * nt < V) Q[v0 + k * nt] = qv[k];
+    }
     __syncthreads();
     const int N = T - 1;
     for (int c = tree.first_child[j]; c >= 0; c = tree.next_sibling[c]) {

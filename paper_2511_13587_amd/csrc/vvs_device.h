@@ -16,10 +16,26 @@ __device__ __forceinline__ float ld(const bf16_t* p) { return bf2f(*p); }
 __device__ __forceinline__ void st(float* p, float v) { *p = v; }
 __device__ __forceinline__ void st(bf16_t* p, float v) { *p = f2bf(v); }
 
-// V cache: per (layer,row,head) blocks of 32 slots, inside a block [dim][slot % 32] so that the 32
-// keys of one dim are contiguous (the contraction index of P*V).
+// KV cache layout inside one (layer, row, head) region of S_cap * dh elements.  Both halves are kept
+// in the operand order of the attention MFMAs (16x16x32: lane l = 16*g + i supplies 8 consecutive
+// contraction values of group g for tile row i), so that one wave-wide 16-byte load reads 1 KiB of
+// contiguous memory.  A region is a sequence of steps of 32 slots.
+//   K (S^T = K Q^T, contraction over dims): step -> 2 tiles t of 16 keys -> dh/32 blocks kd of 32 dims
+//     -> [g = dim%32 / 8][i][dim % 8]; slot w of the step is tile t = (w/4)%2, row i = 4*(w/8) + w%4, so
+//     that the 8 scores a lane holds after both tiles are 8 consecutive keys.
+//   V (O^T = V^T P^T, contraction over keys): step -> dh/16 blocks dt of 16 dims
+//     -> [g = w / 8][i = dim % 16][w % 8].
+// Head sizes that are not a multiple of 32 (K) / 16 (V) are only served by the plain kernels and use
+// [slot][dim] (K) and [step][dim][32 slots] (V).
+__device__ __forceinline__ size_t k_index(int slot, int dim, int dh) {
+  if (dh & 31) return (size_t)slot * dh + dim;
+  const int w = slot & 31, i = ((w >> 3) << 2) | (w & 3), t = (w >> 2) & 1;
+  return ((((size_t)((slot >> 5) * 2 + t) * (dh >> 5) + (dim >> 5)) * 4 + ((dim >> 3) & 3)) * 16 + i) * 8 + (dim & 7);
+}
 __device__ __forceinline__ size_t v_index(int slot, int dim, int dh) {
-  return ((size_t)(slot >> 5) * dh + dim) * 32 + (slot & 31);
+  if (dh & 15) return ((size_t)(slot >> 5) * dh + dim) * 32 + (slot & 31);
+  const int w = slot & 31;
+  return ((((size_t)(slot >> 5) * (dh >> 4) + (dim >> 4)) * 4 + (w >> 3)) * 16 + (dim & 15)) * 8 + (w & 7);
 }
 
 // GEMM operands of the bf16 path are stored in MFMA fragment order: 1 KiB blocks of 32 rows x 16

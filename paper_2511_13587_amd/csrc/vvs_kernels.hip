@@ -356,8 +356,8 @@ __global__ void k_rope_kv(const float* __restrict__ qkv, int splits, size_t spli
     st(q + (size_t)m * d + e0 + 1, v[0] * sn + v[1] * cs);
     if (in_cache) {
       const size_t hb = (size_t)r * row_stride + (size_t)hd * head_stride;
-      st(kc + hb + (size_t)slot * dh + e, v[2] * cs - v[3] * sn);
-      st(kc + hb + (size_t)slot * dh + e + 1, v[2] * sn + v[3] * cs);
+      st(kc + hb + k_index(slot, e, dh), v[2] * cs - v[3] * sn);
+      st(kc + hb + k_index(slot, e + 1, dh), v[2] * sn + v[3] * cs);
       st(vc + hb + v_index(slot, e, dh), v[4]);
       st(vc + hb + v_index(slot, e + 1, dh), v[5]);
     }
@@ -384,7 +384,7 @@ __global__ void k_attn_simple(const T* __restrict__ q, const T* __restrict__ kc,
     float sv = -INFINITY;
     if (vis) {
       float dot = 0.f;
-      for (int e = 0; e < dh; ++e) dot += ld(qv + e) * ld(kb + (size_t)k * dh + e);
+      for (int e = 0; e < dh; ++e) dot += ld(qv + e) * ld(kb + k_index(k, e, dh));
       sv = dot * scale;
     }
     sc[k] = sv;
@@ -638,18 +638,18 @@ __global__ __launch_bounds__(256) void k_commit_kv(T* __restrict__ kcache, T* __
   for (int item = threadIdx.x; item < n_k + n_v; item += blockDim.x) {
     if (item < n_k) {
       const int col = item * CH, hd = col / dh, e = col % dh;
-      T* kh = kb + hd * head_stride + e;
+      T* kh = kb + hd * head_stride;
       for (int i0 = 1; i0 <= a; i0 += 8) {
         CT tmp[8];
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
           const int i = min(i0 + k, a);
-          tmp[k] = *(const CT*)(kh + (size_t)min(S + s_src[i], S_cap - 1) * dh);
+          tmp[k] = *(const CT*)(kh + k_index(min(S + s_src[i], S_cap - 1), e, dh));
         }
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
           const int i = i0 + k;
-          if (i <= a && s_src[i] != i && S + s_src[i] < S_cap) *(CT*)(kh + (size_t)(S + i) * dh) = tmp[k];
+          if (i <= a && s_src[i] != i && S + s_src[i] < S_cap) *(CT*)(kh + k_index(S + i, e, dh)) = tmp[k];
         }
       }
     } else {
@@ -746,7 +746,7 @@ __global__ void k_debug_kv(const T* __restrict__ kh, const T* __restrict__ vh, f
   const size_t d = (size_t)H * dh;
   if (i >= (size_t)n_slots * d) return;
   const int slot = (int)(i / d), col = (int)(i % d), hd = col / dh, e = col % dh;
-  dk[i] = ld(kh + hd * head_stride + (size_t)slot * dh + e);
+  dk[i] = ld(kh + hd * head_stride + k_index(slot, e, dh));
   dv[i] = ld(vh + hd * head_stride + v_index(slot, e, dh));
 }
 

@@ -255,9 +255,9 @@ __device__ __forceinline__ void tile_epilogue(const float* red, const float* rs,
     }
   } else {
     const int sec = n0 / ep.d;                                     // the tile lies inside the q (0), k (1) or v (2) third
-    if (sec < 2) {
+    if (sec == 0) {
       const int half = ep.dh >> 1, np = ep.dh >> 2;
-      for (int u = threadIdx.x; u < BM * (BN / 16); u += 256) {    // one unit = (row, 16 consecutive columns)
+      for (int u = threadIdx.x; u < BM * (BN / 16); u += 256) {    // q: one unit = (row, 16 consecutive columns), row-major output
         const int row = u / (BN / 16), c0 = (u % (BN / 16)) * 16;
         const int m = m0 + row;
         if (m >= M) continue;
@@ -266,8 +266,8 @@ __device__ __forceinline__ void tile_epilogue(const float* red, const float* rs,
         float v[16] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w, s2.x, s2.y, s2.z, s2.w, s3.x, s3.y, s3.z, s3.w};
 #pragma unroll
         for (int i = 0; i < 16; ++i) v[i] *= rs[row];
-        const int eg = (n0 + c0) % ep.d, hd = eg / ep.dh, e = eg % ep.dh;
-        const int slot = s_pos[2 * row], img = s_pos[2 * row + 1];
+        const int eg = (n0 + c0) % ep.d, e = eg % ep.dh;
+        const int img = s_pos[2 * row + 1];
         if (img >= 0) {
           float2 cs[8];
           if (np == kRopeNpMax) {
@@ -294,16 +294,53 @@ __device__ __forceinline__ void tile_epilogue(const float* red, const float* rs,
             v[2 * i + 1] = a * cs[i].y + b * cs[i].x;
           }
         }
-        uint32_t w[8];
+        uint4* dst = (uint4*)(ep.q + (size_t)m * ep.d + eg);
+        dst[0] = make_uint4((uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16), (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16),
+                            (uint32_t)f2bf(v[4]) | ((uint32_t)f2bf(v[5]) << 16), (uint32_t)f2bf(v[6]) | ((uint32_t)f2bf(v[7]) << 16));
+        dst[1] = make_uint4((uint32_t)f2bf(v[8]) | ((uint32_t)f2bf(v[9]) << 16), (uint32_t)f2bf(v[10]) | ((uint32_t)f2bf(v[11]) << 16),
+                            (uint32_t)f2bf(v[12]) | ((uint32_t)f2bf(v[13]) << 16), (uint32_t)f2bf(v[14]) | ((uint32_t)f2bf(v[15]) << 16));
+      }
+    } else if (sec == 1) {
+      // k: in the cache's operand order 4 consecutive slots of one 8-dim piece are contiguous, so a lane
+      // takes one row (token) and the lanes of a wave cover consecutive tokens; a thread handles
+      // 8-column pieces (one 16-byte store each) of its row.
+      constexpr int G = 256 / BM;                                  // threads per row
+      const int half = ep.dh >> 1, np = ep.dh >> 2;
+      const int row = threadIdx.x % BM, g4 = threadIdx.x / BM, m = m0 + row;
+      const int slot = pre.slot, img = pre.img;                    // this thread's row is the one it looked up
+      if (m < M && slot >= 0 && slot < ep.S_cap) {
+        const float sc = rs[row];
+        bf16_t* krow = ep.kc + (size_t)EpiPre<BM, BN, EPI>::div_T(m, ep) * ep.row_stride;
+        const int gr = min(max(img, 0) / ep.pos.grid_w, ep.rope_pos - 1), gc = max(img, 0) % ep.pos.grid_w;
+#pragma unroll 2
+        for (int c8 = g4 * 8; c8 < BN; c8 += G * 8) {
+          const float4 a = sum4(red + row * LDC + c8), b = sum4(red + row * LDC + c8 + 4);
+          float v[8] = {a.x * sc, a.y * sc, a.z * sc, a.w * sc, b.x * sc, b.y * sc, b.z * sc, b.w * sc};
+          const int eg = (n0 + c8) % ep.d, hd = eg / ep.dh, e = eg % ep.dh;
+          if (img >= 0) {
+            float2 cs[4];
+            if (np == kRopeNpMax) {
+              const float4* t4 = (const float4*)(s_rope + row * 2 * kRopeNpMax + (e / half) * np + ((e % half) >> 1));
+              const float4 c0 = t4[0], c1 = t4[1];
+              cs[0] = make_float2(c0.x, c0.y); cs[1] = make_float2(c0.z, c0.w);
+              cs[2] = make_float2(c1.x, c1.y); cs[3] = make_float2(c1.z, c1.w);
+            } else {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) w[i] = (uint32_t)f2bf(v[2 * i]) | ((uint32_t)f2bf(v[2 * i + 1]) << 16);
-        uint4* dst = nullptr;
-        if (sec == 0) dst = (uint4*)(ep.q + (size_t)m * ep.d + eg);
-        else if (slot >= 0 && slot < ep.S_cap)
-          dst = (uint4*)(ep.kc + (size_t)EpiPre<BM, BN, EPI>::div_T(m, ep) * ep.row_stride + (size_t)hd * ep.head_stride + (size_t)slot * ep.dh + e);
-        if (dst) {
-          dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
-          dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+              for (int i = 0; i < 4; ++i) {
+                const int ei = e + 2 * i, pv = (ei / half) ? gc : gr, ip = (ei % half) >> 1;
+                cs[i] = *(const float2*)(ep.rope + ((size_t)pv * np + ip) * 2);
+              }
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float x0 = v[2 * i], x1 = v[2 * i + 1];
+              v[2 * i] = x0 * cs[i].x - x1 * cs[i].y;
+              v[2 * i + 1] = x0 * cs[i].y + x1 * cs[i].x;
+            }
+          }
+          *(uint4*)(krow + (size_t)hd * ep.head_stride + k_index(slot, e, ep.dh)) =
+              make_uint4((uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16), (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16),
+                         (uint32_t)f2bf(v[4]) | ((uint32_t)f2bf(v[5]) << 16), (uint32_t)f2bf(v[6]) | ((uint32_t)f2bf(v[7]) << 16));
         }
       }
     } else {
@@ -664,14 +701,16 @@ void mfma_gemm_qkv(Ctx* c, int layer, const bf16_t* A, const bf16_t* Wqkv, const
 // One workgroup per (head, row).  Scores are computed transposed, S^T[key][query] = K * Q^T, so the
 // accumulator layout (lane = query, registers = keys) is directly the B operand of
 // O^T[dim][query] = V^T[dim][key] * P^T[key][query] and the online-softmax state of a query lives in
-// one lane.  K rows ([slot][dim], dim contiguous) and V blocks ([dim][32 slots], slot contiguous) are
-// loaded straight from the cache into MFMA operand registers - every key is used by exactly one wave,
-// so there is nothing to share through LDS; the 4 waves take 32-key steps round-robin and merge their
-// partial (max, sum, O) through LDS at the end.  Only the last T keys (the block itself) are masked.
+// one lane.  The cache keeps K and V in the operand order of these MFMAs (k_index / v_index), so they
+// are loaded straight into operand registers with fully contiguous wave-wide loads - every key is used
+// by exactly one wave, so there is nothing to share through LDS; the 4 waves take 32-key steps
+// round-robin and merge their partial (max, sum, O) through LDS at the end.  Only the last T keys (the
+// block itself) are masked.
 template <int DH, int NQB, int NW, int PD>
 __global__ __launch_bounds__(NW * 64, (DH * NQB >= 256 ? 1 : 2)) void k_attn_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc,
                                                    const bf16_t* __restrict__ vc, bf16_t* __restrict__ out, TreeDesc tree,
-                                                   PosDesc pos, int T, int d, size_t row_stride, size_t head_stride, float c_exp) {
+                                                   PosDesc pos, int T, int d, size_t row_stride, size_t head_stride, float c_exp,
+                                                   int cap_steps) {
   constexpr int KD = DH / 32, DT = DH / 16, NQ = NQB * 16;
   __shared__ float s_m[NW - 1][NQ], s_l[NW - 1][NQ];
   __shared__ float s_o[NW - 1][NQ][DH + 1];
@@ -689,14 +728,13 @@ __global__ __launch_bounds__(NW * 64, (DH * NQB >= 256 ? 1 : 2)) void k_attn_mfm
   uint64_t mask[NQB];
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
-    const int tq = qb * 16 + ql;
-    mask[qb] = tq < T ? tree.anc[tq] : 0ull;
+    // query rows past T repeat row T - 1: a query only ever touches its own lanes' columns and rows >= T
+    // are not stored, so nothing has to be zeroed - and no load result is needed before the first MFMA
+    const int tq = min(qb * 16 + ql, T - 1);
+    mask[qb] = tree.anc[tq];
 #pragma unroll
-    for (int kd = 0; kd < KD; ++kd) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (tq < T) v = *(const uint4*)(q + ((size_t)r * T + tq) * d + (size_t)hd * DH + kd * 32 + g * 8);
-      qf[qb][kd] = as_bf16x8(v);
-    }
+    for (int kd = 0; kd < KD; ++kd)
+      qf[qb][kd] = as_bf16x8(*(const uint4*)(q + ((size_t)r * T + tq) * d + (size_t)hd * DH + kd * 32 + g * 8));
   }
   float m_run[NQB], l_run[NQB];
   floatx4 o[NQB][DT];
@@ -708,85 +746,90 @@ __global__ __launch_bounds__(NW * 64, (DH * NQB >= 256 ? 1 : 2)) void k_attn_mfm
     for (int dt = 0; dt < DT; ++dt) o[qb][dt] = floatx4{0.f, 0.f, 0.f, 0.f};
   }
 
-  // K rows / V block of one 32-key step, straight into MFMA operand registers.  S^T tile t, row i holds
-  // key 8*(i/4) + 4*t + i%4 of the step, so that a lane's 8 score values are 8 consecutive keys.
+  // K and V of one 32-key step, straight into MFMA operand registers: the cache is kept in operand
+  // order (k_index / v_index), so every load instruction of a wave reads 1 KiB of contiguous memory.
+  // S^T tile t, row i holds key 8*(i/4) + 4*t + i%4 of the step: a lane's 8 score values are 8 consecutive keys.
 #define VVS_ATTN_LOAD(STEP, KF, VF)                                                                                   \
   {                                                                                                                   \
-    _Pragma("unroll") for (int t = 0; t < 2; ++t) {                                                                   \
-      const int key = ((STEP) << 5) + 8 * (ql >> 2) + 4 * t + (ql & 3);                                               \
-      _Pragma("unroll") for (int kd = 0; kd < KD; ++kd)                                                               \
-          KF[t][kd] = as_bf16x8(*(const uint4*)(kb + (size_t)key * DH + kd * 32 + g * 8));                            \
-    }                                                                                                                 \
+    _Pragma("unroll") for (int t = 0; t < 2; ++t)                                                                     \
+        _Pragma("unroll") for (int kd = 0; kd < KD; ++kd)                                                             \
+            KF[t][kd] = as_bf16x8(*(const uint4*)(kb + ((((size_t)(STEP) * 2 + t) * KD + kd) * 64 + lane) * 8));      \
     _Pragma("unroll") for (int dt = 0; dt < DT; ++dt)                                                                 \
-        VF[dt] = as_bf16x8(*(const uint4*)(vb + ((size_t)(STEP) * DH + dt * 16 + ql) * 32 + g * 8));                  \
+        VF[dt] = as_bf16x8(*(const uint4*)(vb + (((size_t)(STEP) * DT + dt) * 64 + lane) * 8));                       \
   }
-  // A wave requests the operands of PD of its steps at once and then works through them, so that one
-  // memory latency covers PD steps (a whole call at the usual cache lengths).
-  for (int base = wave; base < nsteps; base += NW * PD) {
-    bf16x8 kf[PD][2][KD], vf[PD][DT];
+  // Ring of PD operand sets: a wave's steps wave, wave + NW, ... ; the operands of a step are requested
+  // PD steps ahead, right after the set's previous step has been multiplied, so that the cache streams
+  // in while the wave computes.  Requests past the row's last step repeat that step (never used).
+  bf16x8 kf[PD][2][KD], vf[PD][DT];
 #pragma unroll
-    for (int p = 0; p < PD; ++p) {
-      const int st = min(base + p * NW, nsteps - 1);   // clamped: past the end the previous request is repeated
-      VVS_ATTN_LOAD(st, kf[p], vf[p]);
-    }
-    VVS_PHASE_MARK(1);
+  for (int p = 0; p < PD; ++p) {
+    // first requests: clamped to the cache capacity, not to the row's length, so that their addresses do
+    // not wait for the length (a memory read); steps past the end are valid memory that is never used
+    VVS_ATTN_LOAD(min(wave + p * NW, cap_steps - 1), kf[p], vf[p]);
+    __builtin_amdgcn_sched_barrier(0);               // request groups stay in program order: waits are partial
+  }
+  VVS_PHASE_MARK(1);
+  for (int base = wave; base < nsteps; base += NW * PD) {
 #pragma unroll
     for (int p = 0; p < PD; ++p) {
       const int step = base + p * NW;
-      if (step >= nsteps) break;
-      const int key0 = step << 5;
-      const bool tail = key0 + 32 > S;
+      if (step < nsteps) {
+        const int key0 = step << 5;
+        const bool tail = key0 + 32 > S;
 #pragma unroll
-      for (int qb = 0; qb < NQB; ++qb) {
-        floatx4 s2[2];
+        for (int qb = 0; qb < NQB; ++qb) {
+          floatx4 s2[2];
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-          s2[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+          for (int t = 0; t < 2; ++t) {
+            s2[t] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int kd = 0; kd < KD; ++kd)
-            s2[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[p][t][kd], qf[qb][kd], s2[t], 0, 0, 0);
-        }
-        float sv[8];
+            for (int kd = 0; kd < KD; ++kd)
+              s2[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[p][t][kd], qf[qb][kd], s2[t], 0, 0, 0);
+          }
+          float sv[8];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) sv[i] = s2[i >> 2][i & 3];
-        if (tail) {
+          for (int i = 0; i < 8; ++i) sv[i] = s2[i >> 2][i & 3];
+          if (tail) {
 #pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            const int key = key0 + 8 * g + i;
-            bool vis = key < S;
-            if (!vis && key < n_keys) vis = (mask[qb] >> (key - S)) & 1ull;
-            if (!vis) sv[i] = -INFINITY;
+            for (int i = 0; i < 8; ++i) {
+              const int key = key0 + 8 * g + i;
+              bool vis = key < S;
+              if (!vis && key < n_keys) vis = (mask[qb] >> (key - S)) & 1ull;
+              if (!vis) sv[i] = -INFINITY;
+            }
+          }
+          float mx = sv[0];
+#pragma unroll
+          for (int i = 1; i < 8; ++i) mx = fmaxf(mx, sv[i]);
+          mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+          const float m_new = fmaxf(m_run[qb], mx);
+          const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+          const float alpha = exp2f((m_run[qb] - m_safe) * c_exp);
+          uint32_t pk[4];
+          float rs = 0.f;
+#pragma unroll
+          for (int i = 0; i < 8; i += 2) {
+            const bf16_t p0 = f2bf(exp2f((sv[i] - m_safe) * c_exp));
+            const bf16_t p1 = f2bf(exp2f((sv[i + 1] - m_safe) * c_exp));
+            rs += bf2f(p0) + bf2f(p1);
+            pk[i >> 1] = (uint32_t)p0 | ((uint32_t)p1 << 16);
+          }
+          rs += __shfl_xor(rs, 16, 64);
+          rs += __shfl_xor(rs, 32, 64);
+          l_run[qb] = l_run[qb] * alpha + rs;
+          m_run[qb] = m_new;
+          const bf16x8 pf = as_bf16x8(make_uint4(pk[0], pk[1], pk[2], pk[3]));
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) o[qb][dt][rr] *= alpha;
+            o[qb][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[p][dt], pf, o[qb][dt], 0, 0, 0);
           }
         }
-        float mx = sv[0];
-#pragma unroll
-        for (int i = 1; i < 8; ++i) mx = fmaxf(mx, sv[i]);
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run[qb], mx);
-        const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = exp2f((m_run[qb] - m_safe) * c_exp);
-        uint32_t pk[4];
-        float rs = 0.f;
-#pragma unroll
-        for (int i = 0; i < 8; i += 2) {
-          const bf16_t p0 = f2bf(exp2f((sv[i] - m_safe) * c_exp));
-          const bf16_t p1 = f2bf(exp2f((sv[i + 1] - m_safe) * c_exp));
-          rs += bf2f(p0) + bf2f(p1);
-          pk[i >> 1] = (uint32_t)p0 | ((uint32_t)p1 << 16);
-        }
-        rs += __shfl_xor(rs, 16, 64);
-        rs += __shfl_xor(rs, 32, 64);
-        l_run[qb] = l_run[qb] * alpha + rs;
-        m_run[qb] = m_new;
-        const bf16x8 pf = as_bf16x8(make_uint4(pk[0], pk[1], pk[2], pk[3]));
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-#pragma unroll
-          for (int rr = 0; rr < 4; ++rr) o[qb][dt][rr] *= alpha;
-          o[qb][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[p][dt], pf, o[qb][dt], 0, 0, 0);
-        }
       }
+      VVS_ATTN_LOAD(min(step + PD * NW, nsteps - 1), kf[p], vf[p]);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 #undef VVS_ATTN_LOAD
@@ -855,11 +898,11 @@ void mfma_attention(Ctx* c, int layer, const TreeDesc& tree, const PosDesc& pos,
   const int nqb = T <= 16 ? 1 : (T <= 32 ? 2 : 4);
 #define VVS_ATTN(DH, NQB, NW, PD)                                                                                                 \
   hipLaunchKernelGGL((k_attn_mfma<DH, NQB, NW, PD>), grid, dim3(NW * 64), 0, s, q, kc, vc, out, tree, pos, T, c->d, c->kv_row_stride, \
-                     c->kv_head_stride, c_exp)
+                     c->kv_head_stride, c_exp, c->S_cap >> 5)
   // 4 waves per workgroup keep the register footprint low enough for 2-3 workgroups per CU, so that
   // every (head, row) pair of a call is resident at once
   if (c->dh == 64) {
-    if (nqb == 1) VVS_ATTN(64, 1, 4, 4); else if (nqb == 2) VVS_ATTN(64, 2, 4, 4); else VVS_ATTN(64, 4, 4, 2);
+    if (nqb == 1) VVS_ATTN(64, 1, 4, 2); else if (nqb == 2) VVS_ATTN(64, 2, 4, 2); else VVS_ATTN(64, 4, 4, 2);
   } else {
     if (nqb == 1) VVS_ATTN(128, 1, 4, 2); else VVS_ATTN(128, 2, 4, 2);   // T <= 32 is enforced at context creation for head size 128
   }
