@@ -25,6 +25,14 @@ What it follows
   neighbours, taken in ascending distance while the added mass stays within a budget delta.
 * KV cache upkeep (Section 4.1): the keys/values of accepted tokens join the cache so that the next
   call is conditioned exactly as plain AR decoding would be.
+* Post verification (Section 4.1): tokens that were accepted without verification in the previous
+  step are put in front of the new candidates and go through the same target pass; they are not
+  tested again (they are already part of the output) - the pass only gives them their keys/values,
+  which restores exact AR conditioning for everything behind them.  Here they are the first n_post
+  nodes of the tree, a chain below the root, accepted unconditionally.
+* Token-level feature cache (Section 4.3; Algorithm 2, "UpdateCache"): the target's hidden state
+  in front of the output head ("feature") of every token that joins the sequence is kept in a ring
+  of the most recent few (the supplementary material uses 5) per row.
 
 Readings where the paper is silent (architecture, CFG, RoPE, tree rule) are listed in the project's
 design notes; each is marked "reading:" below.
@@ -139,6 +147,8 @@ class Oracle:
         self.relax_k = int(c.get("relax_k", 0))
         self.relax_delta = float(c.get("relax_delta", 0.0))
         self.rb = round_bf16 if c["dtype"] == 1 else _ident
+        self.ring_slots = int(c.get("feature_slots", 5))
+        self.feature_pre_norm = bool(c.get("feature_pre_norm", 0))   # reading: feature = input of the output head (after the final norm) unless switched
         self.w = _W64(weights)                # float32 arrays [in, out], read as float64
         self.nbr = None
         self.reset()
@@ -150,6 +160,7 @@ class Oracle:
         self.n_emitted = np.zeros(self.B, dtype=np.int64)
         self.pending = -np.ones(self.B, dtype=np.int64)
         self.last = None
+        self.ring = [[] for _ in range(self.R)]      # per row: the most recent features, oldest first
 
     def set_neighbors(self, nbr):
         self.nbr = np.asarray(nbr)
@@ -198,10 +209,19 @@ class Oracle:
             act = rb(silu(h2 @ w[f"l{l}.wg"]) * (h2 @ w[f"l{l}.wu"]))
             x = x + act @ w[f"l{l}.wd"]
         logits = None
+        self.one_feature = self._feature(x)
         if want_logits:
             hf = rb(rmsnorm(x, w["gf"], self.eps))
             logits = hf @ w["wout"][:, self.lo:self.hi]
         return logits, new_kv
+
+    def _feature(self, x):
+        """Feature of a token = its hidden state in front of the output head, in the model's storage
+        format.  reading: after the final norm (exactly what the head multiplies); the switch
+        feature_pre_norm keeps the residual stream itself instead."""
+        if self.feature_pre_norm:
+            return self.rb(np.asarray(x, dtype=F64))
+        return self.rb(rmsnorm(x, self.w["gf"], self.eps))
 
     def forward_block(self, row, x_in, img_index, mask, logits_for=None):
         """The same computation for T tokens of one row at once.  x_in [T, d]; img_index [T];
@@ -237,6 +257,7 @@ class Oracle:
             h2 = rb(rmsnorm(x, w[f"l{l}.g2"], self.eps))
             act = rb(silu(h2 @ w[f"l{l}.wg"]) * (h2 @ w[f"l{l}.wu"]))
             x = x + act @ w[f"l{l}.wd"]
+        self.block_features = self._feature(x)                      # [T, d]
         sel = np.arange(T) if logits_for is None else np.asarray(logits_for)
         logits = np.full((T, self.hi - self.lo), np.nan)
         hf = rb(rmsnorm(x[sel], w["gf"], self.eps))
@@ -309,6 +330,9 @@ class Oracle:
                     self.vc[row][l] = np.concatenate([self.vc[row][l], v], axis=0)
                 rows_logits.append(logits[T - 1])
                 self.prefill_logits[row] = logits[T - 1]
+                # reading: the cache starts with the feature of the last prefilled position (the one the
+                # first token is sampled from)
+                self._push_features(row, self.block_features[T - 1:T])
             _, p = self.mix(rows_logits[0], rows_logits[1])
             self.prefill_probs[b] = p
             first[b] = self.lo + inverse_cdf(p, float(uniforms[b]))
@@ -316,14 +340,21 @@ class Oracle:
             self.n_emitted[b] = n_forced + 1
         return first
 
-    def verify(self, parent, draft_tokens, draft_probs, uniforms, mode=0):
+    def verify(self, parent, draft_tokens, draft_probs, uniforms, mode=0, n_post=0):
         """One verification pass.  parent int [N] (None = chain over draft_tokens.shape[1] nodes);
         draft_tokens int [B, N] (full-vocabulary ids); draft_probs [B, T, V_eff]; uniforms
         [B, T, 2]; mode 0 strict, 1 relaxed.  Returns accept_len [B], path (list of node-id lists),
-        next_token [B].  Keeps the per-node K/V and the outcome for kv_commit()."""
+        next_token [B].  Keeps the per-node K/V, features and the outcome for kv_commit().
+        n_post > 0 (Section 4.1, post verification): nodes 1..n_post are the tokens accepted without
+        verification in the previous step, a chain below the root; every other node descends from
+        node n_post.  They are accepted without a test (their draft rows and uniforms are not read)
+        and count in accept_len."""
         draft_tokens = np.asarray(draft_tokens, dtype=np.int64).reshape(self.B, -1)
         N = draft_tokens.shape[1]
         parent = np.arange(N) if parent is None else np.asarray(parent, dtype=np.int64)
+        assert 0 <= n_post <= N
+        assert all(int(parent[i - 1]) == i - 1 for i in range(1, n_post + 1)), "post-verified tokens form a chain below the root"
+        assert all(int(parent[j - 1]) >= n_post for j in range(n_post + 1, N + 1)), "candidates descend from the last post-verified token"
         T = N + 1
         depth = np.zeros(T, dtype=np.int64)
         mask = np.zeros((T, T), dtype=np.uint8)
@@ -338,7 +369,7 @@ class Oracle:
                 depth[j] = depth[parent[j - 1]] + 1
         accept_len = np.zeros(self.B, dtype=np.int64)
         next_token = -np.ones(self.B, dtype=np.int64)
-        paths, node_kv = [], []
+        paths, node_kv, node_feat = [], [], []
         self.traces = [None] * self.B
         self.mixed_logits = np.zeros((self.B, T, self.hi - self.lo))
         self.raw_logits = np.zeros((self.R, T, self.hi - self.lo))
@@ -347,12 +378,14 @@ class Oracle:
             toks = np.concatenate([[self.pending[b]], draft_tokens[b]])
             x_in = self.embed_tokens(np.maximum(toks, 0))
             idx = self.n_emitted[b] - 1 + depth
-            kv_rows = []
+            kv_rows, feat_rows = [], []
             for row in (2 * b, 2 * b + 1):
                 logits, new_kv = self.forward_block(row, x_in, idx, mask)
                 self.raw_logits[row] = logits
                 kv_rows.append(new_kv)
+                feat_rows.append(self.block_features)
             node_kv.append(kv_rows)
+            node_feat.append(feat_rows)
             mixed, p = self.mix(self.raw_logits[2 * b], self.raw_logits[2 * b + 1])
             self.mixed_logits[b], self.probs[b] = mixed, p
             if self.n_emitted[b] >= self.G:          # image finished: nothing to verify
@@ -362,11 +395,11 @@ class Oracle:
             tr = {}
             a, path, nxt = decide(p, np.asarray(draft_probs[b], dtype=F64), draft_tokens[b] - self.lo, parent,
                                   np.asarray(uniforms[b], dtype=F64), cap, mode,
-                                  self.nbr, self.relax_k, self.relax_delta, self.lo, trace=tr)
+                                  self.nbr, self.relax_k, self.relax_delta, self.lo, trace=tr, n_forced=n_post)
             self.traces[b] = tr
             accept_len[b], next_token[b] = a, self.lo + nxt
             paths.append(path)
-        self.last = dict(paths=paths, node_kv=node_kv, tokens=draft_tokens, accept_len=accept_len,
+        self.last = dict(paths=paths, node_kv=node_kv, node_feat=node_feat, tokens=draft_tokens, accept_len=accept_len,
                          next_token=next_token)
         return accept_len, paths, next_token
 
@@ -382,9 +415,19 @@ class Oracle:
                 for l, (k, v) in enumerate(self.last["node_kv"][b][i]):
                     self.kc[row][l] = np.concatenate([self.kc[row][l], k[path]], axis=0)
                     self.vc[row][l] = np.concatenate([self.vc[row][l], v[path]], axis=0)
+                self._push_features(row, self.last["node_feat"][b][i][path])
             self.n_emitted[b] += len(path)
             self.pending[b] = self.last["next_token"][b]
         self.last = None
+
+    def _push_features(self, row, feats):
+        """Section 4.3 / Algorithm 2 "UpdateCache": the features of the tokens that just joined the
+        cache are appended in sequence order; only the most recent ring_slots stay."""
+        self.ring[row] = (self.ring[row] + [np.array(f, dtype=F64) for f in feats])[-self.ring_slots:] if self.ring_slots else []
+
+    def features(self, row):
+        """The cached features of a row, oldest first: array [n <= ring_slots, d]."""
+        return np.stack(self.ring[row]) if self.ring[row] else np.zeros((0, self.d))
 
     def emitted_tokens(self, b):
         """Tokens that the last verify emitted for prompt b: accepted draft tokens, then the
@@ -427,7 +470,7 @@ def relaxed_target(P, x, nbr_row, k, delta, trace=None):
     return Pt[x], Pt
 
 
-def decide(p_rows, q_rows, tok_local, parent, u, cap, mode=0, nbr=None, relax_k=0, relax_delta=0.0, lo=0, trace=None):
+def decide(p_rows, q_rows, tok_local, parent, u, cap, mode=0, nbr=None, relax_k=0, relax_delta=0.0, lo=0, trace=None, n_forced=0):
     """Acceptance walk for one prompt.
 
     p_rows [T, V] target distributions at the root (0) and at every draft node; q_rows [T, V]:
@@ -440,6 +483,8 @@ def decide(p_rows, q_rows, tok_local, parent, u, cap, mode=0, nbr=None, relax_k=
     positive part of target - draft, the rejected token leaves the draft distribution, which is
     renormalised).  A chain is the one-child case and is exactly the procedure of Section 2.
     Uniform u[c, 0] decides node c; u[j, 1] draws the final token when the walk ends at node j.
+    Nodes 1..n_forced (post verification, Section 4.1) are accepted without a test: no uniform is
+    consumed and the target is left as it is.  The end-of-image cap still holds for them.
     Returns (accept_len, path node ids starting with 0, next token id inside the slice).
     `trace` (a dict, optional) only records how close each decision was to flipping - the distance of
     every consulted uniform to its threshold, of every budget test to delta, and the CDF of the final
@@ -454,7 +499,9 @@ def decide(p_rows, q_rows, tok_local, parent, u, cap, mode=0, nbr=None, relax_k=
     while True:
         P = np.asarray(p_rows[cur], dtype=F64).copy()
         accepted = None
-        if a < cap and children[cur]:
+        if a < cap and children[cur] and children[cur][0] <= n_forced:
+            accepted = children[cur][0]
+        elif a < cap and children[cur]:
             Q = np.asarray(q_rows[cur], dtype=F64).copy()
             for c in children[cur]:
                 x = int(tok_local[c - 1])
