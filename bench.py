@@ -31,7 +31,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_correlated_draft(ctx, vb, synth, shape, parent, torch, noise_std, bufs):
+def build_correlated_draft(ctx, vb, synth, shape, parent, torch, noise_std, bufs, n_post=0):
     """Synthetic drafter of tunable quality.  Level by level: run a verify pass, read the target's
     mixed logits at the nodes of depth k, let the draft distribution of those nodes be the normalised
     exponential of (target logits + Gaussian noise), and draw their children from it without
@@ -51,8 +51,8 @@ def build_correlated_draft(ctx, vb, synth, shape, parent, torch, noise_std, bufs
         children.setdefault(int(parent[j - 1]), []).append(j)
     for level in range(int(depth.max())):
         ctx.vvs_set_state(state)
-        ctx.vvs_verify(N, parent, None, torch.from_numpy(toks).to(dev), torch.from_numpy(q).to(dev),
-                       torch.from_numpy(u).to(dev), vb.VVS_STRICT, bufs["a"], bufs["path"], bufs["next"])
+        ctx.vvs_verify_post(N, n_post, parent, None, torch.from_numpy(toks).to(dev), torch.from_numpy(q).to(dev),
+                            torch.from_numpy(u).to(dev), vb.VVS_STRICT, bufs["a"], bufs["path"], bufs["next"])
         _, mixed, _ = ctx.vvs_debug_logits()
         mixed = mixed.cpu().numpy()
         for j in [j for j in range(T) if depth[j] == level and j in children]:
@@ -88,7 +88,7 @@ def algorithmic_counts(shape, S_mean):
                 attn_flops=attn_flops, M=M)
 
 
-def cpu_baseline(shape, weights, synth, n_forced, u_first, parent, q, toks, u, mode, nbr, log_fn, n_sample=2, reps=5):
+def cpu_baseline(shape, weights, synth, n_forced, u_first, parent, q, toks, u, mode, nbr, log_fn, n_sample=2, reps=5, n_post=0):
     """The CPU checker as it stands, timed on a bounded sample of the same workload: the first
     n_sample prompts (2 CFG rows each) at the same cache length, with the same tree, draft
     distributions, drafted tokens and uniforms as the GPU run.  The prefill that builds the cache is
@@ -111,7 +111,7 @@ def cpu_baseline(shape, weights, synth, n_forced, u_first, parent, q, toks, u, m
     log_fn(f"cpu baseline: building the cache of the sample took {time.perf_counter() - t0:.1f} s (not counted)")
     t0 = time.perf_counter()
     for _ in range(reps):
-        a, _, _ = o.verify(parent, toks[:n_sample], q[:n_sample], u[:n_sample], mode)
+        a, _, _ = o.verify(parent, toks[:n_sample], q[:n_sample], u[:n_sample], mode, n_post=n_post)
     t_verify = (time.perf_counter() - t0) / reps
     t0 = time.perf_counter()
     o.kv_commit()
@@ -138,6 +138,9 @@ def main():
                     help="also launch a plain 256 MiB copy kernel (k_copy_bytes) three times, for scaling hardware traffic counters")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (set_state, verify, commit) in a HIP graph and time its replays instead of eager launches")
+    ap.add_argument("--post", type=int, default=0,
+                    help="post verification: this many unverified tokens of a previous verification-free step ride in front of the "
+                         "draft tree (vvs_verify_post); 0 = the plain verify pass of the headline workload")
     ap.add_argument("--layers", type=int, default=0, help="override depth (debugging only; the result is then not the named workload)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -152,6 +155,8 @@ def main():
     shape = synth.SHAPES[args.workload]
     if args.layers:
         shape = shape.replace(n_layers=args.layers)
+    if args.post:
+        shape = shape.replace(n_nodes=shape.n_nodes + args.post)
     n_emitted = shape.grid // 2 if args.image_tokens < 0 else args.image_tokens
     n_forced = n_emitted - 1
     mode = vb.VVS_RELAXED if args.mode == "relaxed" else vb.VVS_STRICT
@@ -186,15 +191,17 @@ def main():
     bufs = dict(state=state, a=torch.zeros(B, dtype=torch.int32, device=dev),
                 path=torch.zeros((B, vb.VVS_MAX_T), dtype=torch.int32, device=dev),
                 next=torch.zeros(B, dtype=torch.int32, device=dev))
-    parent = synth.tree_parents(shape.tree_widths, shape.n_nodes)
+    parent = synth.tree_parents(shape.tree_widths, shape.n_nodes - args.post)
+    if args.post:                                   # the draft tree hangs below a chain of unverified tokens
+        parent = np.array(list(range(args.post)) + [int(p) + args.post for p in parent], dtype=np.int32)
     mask = synth.ancestor_mask(parent)
-    q, toks, u = build_correlated_draft(ctx, vb, synth, shape, parent, torch, args.draft_noise, bufs)
+    q, toks, u = build_correlated_draft(ctx, vb, synth, shape, parent, torch, args.draft_noise, bufs, args.post)
     dq, dtoks, du = torch.from_numpy(q).to(dev), torch.from_numpy(toks).to(dev), torch.from_numpy(u).to(dev)
     N = shape.n_nodes
 
     def step():
         ctx.vvs_set_state(state)
-        ctx.vvs_verify(N, parent, mask, dtoks, dq, du, mode, bufs["a"], bufs["path"], bufs["next"])
+        ctx.vvs_verify_post(N, args.post, parent, mask, dtoks, dq, du, mode, bufs["a"], bufs["path"], bufs["next"])
         ctx.vvs_kv_commit()
 
     if args.calibrate_copy:
@@ -262,7 +269,7 @@ def main():
         roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS}
     traffic = None
     tfile = os.path.join(ROOT, "profiles", f"traffic_{shape.name}.json")
-    if dom == "gemm" and os.path.exists(tfile) and not args.layers:
+    if dom == "gemm" and os.path.exists(tfile) and not args.layers and not args.post:
         # HBM bytes per launch from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command,
         # scaled by the same counters' reading for a plain copy kernel
         traffic = json.load(open(tfile)).get("hbm_bytes_per_launch")
@@ -278,7 +285,7 @@ def main():
         "config": {"workload": shape.name, "layers": shape.n_layers, "d_model": shape.d_model, "prompts": B,
                    "rows": shape.n_rows, "draft_nodes": N, "tree_depth": int(synth.node_depths(parent).max()),
                    "cache_len_mean": S_mean, "mode": args.mode, "draft_noise_std": args.draft_noise,
-                   "launch": "hip graph replay" if args.graph else "eager"},
+                   "launch": "hip graph replay" if args.graph else "eager", "post_verified_tokens": args.post},
         "verify_latency_ms": ms_per_step, "mean_accept_len": float(accept.mean()),
         "emitted_tokens_per_step": emitted, "scored_draft_tokens_per_s": B * N / (ms_per_step * 1e-3),
         "whole_pass": {"algorithmic_GB": total_bytes / 1e9, "algorithmic_TFLOP": (cnt["gemm_flops"] + cnt["attn_flops"]) / 1e12,
@@ -292,7 +299,7 @@ def main():
     if not args.no_cpu_baseline:
         try:
             nbr_host = synth.make_codebook_neighbours(shape.vocab, shape.relax_k) if shape.relax_k else None
-            out["cpu_baseline"] = cpu_baseline(shape, weights, synth, n_forced, u0_host, parent, q, toks, u, mode, nbr_host, log)
+            out["cpu_baseline"] = cpu_baseline(shape, weights, synth, n_forced, u0_host, parent, q, toks, u, mode, nbr_host, log, n_post=args.post)
         except MemoryError as e:           # pragma: no cover
             out["cpu_baseline"] = {"value": None, "unit": "verified tokens/s", "cores": os.cpu_count(), "kind": "oracle",
                                    "sample": f"failed: {e}"}

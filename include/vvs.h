@@ -71,7 +71,12 @@ typedef struct {
   float rope_base;
   int32_t relax_k;               /* neighbours per id in the table given to vvs_set_neighbors */
   float relax_delta;             /* budget of target mass the relaxed rule may absorb */
+  int32_t feature_slots;         /* token-level feature cache (Section 4.3): features kept per row,
+                                    0 .. VVS_MAX_FEATURE_SLOTS (0 = none; the paper keeps 5) */
+  int32_t feature_pre_norm;      /* 0: a feature is the input of the output head (after the final
+                                    norm); 1: the residual stream in front of the final norm */
 } vvs_config;
+#define VVS_MAX_FEATURE_SLOTS 8
 
 /* Sizes in bytes of the three device buffers a context needs.  VVS_ESIZE if the shape is not
  * supported (bf16 needs d_model % 64 == 0, d_ff % 64 == 0, V_eff % 64 == 0, head size 64 or 128;
@@ -143,6 +148,20 @@ vvs_status vvs_verify(vvs_ctx* ctx, int32_t n_nodes, const int32_t* h_parent, co
                       int32_t mode, int32_t* d_accept_len, int32_t* d_path, int32_t* d_next_token,
                       vvs_stream s);
 
+/* Verification with post verification (Section 4.1): the tokens that the previous, verification-free
+ * step accepted without asking the target model ride in front of the new candidates and go through
+ * the same pass.  They are nodes 1 .. n_post of the tree, a chain below the root (h_parent[j-1] = j-1
+ * for j <= n_post), and every other node descends from node n_post; anything else is VVS_EINVAL.
+ * They are accepted without a test (their d_draft_probs rows and d_uniforms entries are not read) and
+ * count in accept_len / path; the end-of-image cap applies to them like to any accepted token.  The
+ * pass gives them their K/V (committed by vvs_kv_commit like every accepted node), which restores
+ * exact AR conditioning for the candidates behind them.  d_draft_tokens[b][0 .. n_post-1] are their
+ * ids.  n_post = 0 is vvs_verify.  Everything else as in vvs_verify. */
+vvs_status vvs_verify_post(vvs_ctx* ctx, int32_t n_nodes, int32_t n_post, const int32_t* h_parent,
+                           const uint8_t* h_tree_mask, const int32_t* d_draft_tokens, const float* d_draft_probs,
+                           const float* d_uniforms, int32_t mode, int32_t* d_accept_len, int32_t* d_path,
+                           int32_t* d_next_token, vvs_stream s);
+
 /* The acceptance stage alone (CFG mix, softmax, accept / resample, path walk) on logits supplied by
  * the caller: d_raw_logits float [R, T, V_eff] (row-major, row r = 2b + {0: conditional,
  * 1: unconditional}).  Same outputs as vvs_verify; does not touch the KV cache, and the outcome is
@@ -157,6 +176,16 @@ vvs_status vvs_accept_from_logits(vvs_ctx* ctx, int32_t n_nodes, const int32_t* 
  * into consecutive cache slots S_b .. S_b + a_b, advances S_b and n_emitted_b by a_b + 1 and makes
  * next_token the pending token.  Exactly one commit per verify. */
 vvs_status vvs_kv_commit(vvs_ctx* ctx, vvs_stream s);
+
+/* Token-level feature cache (Section 4.3; Algorithm 2, "UpdateCache").  vvs_prefill stores the feature
+ * of the last prefilled position of every row, vvs_kv_commit appends the features of the tokens it
+ * commits (pending token, then the accepted path, in order); a row keeps its feature_slots most
+ * recent ones.  A feature is [d_model] values in the context's dtype rounding (bf16 contexts: bf16
+ * values).  Reads them out oldest first:
+ *   d_features float [R, feature_slots, d_model] out, row r: entries 0 .. count-1 valid, rest zero
+ *   d_count    int32 [B] out, valid entries per row of prompt b (both of its rows hold the same number)
+ * vvs_set_state does not touch the cache. */
+vvs_status vvs_read_features(vvs_ctx* ctx, float* d_features, int32_t* d_count, vvs_stream s);
 
 /* Per-prompt state: int32 [3, B] out = cached length S_b, emitted image tokens, pending token. */
 vvs_status vvs_read_state(vvs_ctx* ctx, int32_t* d_state, vvs_stream s);

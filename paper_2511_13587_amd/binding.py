@@ -27,7 +27,8 @@ class VvsConfig(C.Structure):
                                          "grid_h", "grid_w", "prefix_len", "prefix_kind", "n_classes", "n_prompts",
                                          "max_nodes", "dtype")] + \
                [("cfg_scale", C.c_float), ("rms_eps", C.c_float), ("rope_base", C.c_float),
-                ("relax_k", C.c_int32), ("relax_delta", C.c_float)]
+                ("relax_k", C.c_int32), ("relax_delta", C.c_float),
+                ("feature_slots", C.c_int32), ("feature_pre_norm", C.c_int32)]
 
 
 class VvsError(RuntimeError):
@@ -53,6 +54,8 @@ def _load():
         "vvs_check_tree": (i32, [i32, vp, vp, vp, vp]),
         "vvs_prefill": (i32, [vp, vp, vp, i32, vp, vp, vp, vp]),
         "vvs_verify": (i32, [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]),
+        "vvs_verify_post": (i32, [vp, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]),
+        "vvs_read_features": (i32, [vp, vp, vp, vp]),
         "vvs_accept_from_logits": (i32, [vp, i32, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]),
         "vvs_kv_commit": (i32, [vp, vp]),
         "vvs_read_state": (i32, [vp, vp, vp]),
@@ -74,12 +77,13 @@ def _load():
 lib, EXPORTS = _load()
 
 
-def make_config(shape, max_nodes: Optional[int] = None) -> VvsConfig:
+def make_config(shape, max_nodes: Optional[int] = None, feature_slots: int = 5, feature_pre_norm: int = 0) -> VvsConfig:
     """vvs_config from a synth.Shape-like object."""
     return VvsConfig(shape.n_layers, shape.d_model, shape.n_heads, shape.d_ff, shape.vocab, shape.logit_lo,
                      shape.logit_hi, shape.grid_h, shape.grid_w, shape.prefix_len, shape.prefix_kind,
                      shape.n_classes, shape.n_prompts, shape.n_nodes if max_nodes is None else max_nodes,
-                     shape.dtype, shape.cfg_scale, shape.rms_eps, shape.rope_base, shape.relax_k, shape.relax_delta)
+                     shape.dtype, shape.cfg_scale, shape.rms_eps, shape.rope_base, shape.relax_k, shape.relax_delta,
+                     feature_slots, feature_pre_norm)
 
 
 def vvs_query_sizes(cfg: VvsConfig):
@@ -197,6 +201,23 @@ class Context:
                                    None if m is None else m.ctypes.data, _ptr(draft_tokens), _ptr(draft_probs),
                                    _ptr(uniforms), mode, _ptr(accept_len), _ptr(path), _ptr(next_token), _stream()))
         self.last_T = n_nodes + 1
+
+    def vvs_verify_post(self, n_nodes: int, n_post: int, parent: Optional[np.ndarray], tree_mask: Optional[np.ndarray],
+                        draft_tokens: Optional[torch.Tensor], draft_probs: Optional[torch.Tensor], uniforms: torch.Tensor,
+                        mode: int, accept_len: torch.Tensor, path: torch.Tensor, next_token: torch.Tensor):
+        p = None if parent is None else np.ascontiguousarray(parent, dtype=np.int32)
+        m = None if tree_mask is None else np.ascontiguousarray(tree_mask, dtype=np.uint8)
+        self._check(lib.vvs_verify_post(self.h, n_nodes, n_post, None if p is None else p.ctypes.data,
+                                        None if m is None else m.ctypes.data, _ptr(draft_tokens), _ptr(draft_probs),
+                                        _ptr(uniforms), mode, _ptr(accept_len), _ptr(path), _ptr(next_token), _stream()))
+        self.last_T = n_nodes + 1
+
+    def vvs_read_features(self):
+        """(features float32 [R, feature_slots, d] oldest first, count int32 [B])."""
+        feats = torch.empty((self.R, self.cfg.feature_slots, self.cfg.d_model), dtype=torch.float32, device=self.device)
+        count = torch.empty((self.B,), dtype=torch.int32, device=self.device)
+        self._check(lib.vvs_read_features(self.h, _ptr(feats), _ptr(count), _stream()))
+        return feats.cpu().numpy(), count.cpu().numpy()
 
     def vvs_accept_from_logits(self, n_nodes: int, parent, tree_mask, raw_logits: torch.Tensor, draft_tokens, draft_probs,
                                uniforms, mode, accept_len, path, next_token):

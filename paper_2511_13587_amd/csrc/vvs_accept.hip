@@ -159,7 +159,9 @@ __global__ __launch_bounds__(1024) void k_accept_node(AcceptArgs a, TreeDesc tre
   }
 
   int accepted = 0;
-  if (tree.first_child[j] >= 0 && tree.depth[j] < cap) {
+  if (tree.first_child[j] >= 0 && tree.depth[j] < cap && tree.first_child[j] <= tree.n_forced) {
+    accepted = tree.first_child[j];          // post verification: accepted without a test, nothing is read or changed
+  } else if (tree.first_child[j] >= 0 && tree.depth[j] < cap) {
     const float* qrow = a.q + (size_t)(b * T + j) * V;
     for (int v0 = tid; v0 < V; v0 += 8 * nt) {               // 8 independent requests per thread and pass
       float qv[8];

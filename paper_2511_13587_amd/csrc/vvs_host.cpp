@@ -64,6 +64,9 @@ vvs_status plan_sizes(const vvs_config* cfg, Ctx* c, std::string* err) {
   if (g.relax_k < 0 || g.relax_k > 64) return fail(err, VVS_ESIZE, "config: relax_k must be in [0, 64]");
   if (!(g.relax_delta >= 0.f)) return fail(err, VVS_EINVAL, "config: relax_delta < 0");
   if (!(g.rms_eps > 0.f) || !(g.rope_base > 1.f)) return fail(err, VVS_EINVAL, "config: rms_eps / rope_base");
+  if (g.feature_slots < 0 || g.feature_slots > VVS_MAX_FEATURE_SLOTS)
+    return fail(err, VVS_ESIZE, "config: feature_slots must be in [0, VVS_MAX_FEATURE_SLOTS]");
+  if (g.feature_pre_norm != 0 && g.feature_pre_norm != 1) return fail(err, VVS_EINVAL, "config: feature_pre_norm must be 0 or 1");
   int dh = g.d_model / g.n_heads;
   if (dh % 4) return fail(err, VVS_ESIZE, "config: head size must be a multiple of 4 (2D rotary pairs)");
   if (g.d_model % 8 || g.d_ff % 8) return fail(err, VVS_ESIZE, "config: d_model and d_ff must be multiples of 8");
@@ -106,6 +109,7 @@ vvs_status plan_sizes(const vvs_config* cfg, Ctx* c, std::string* err) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   w.state = take(sizeof(int32_t) * 3 * c->B);
+  w.ring_state = take(sizeof(int32_t) * 2 * c->R);        // per row: features held, slot of the oldest (zeroed with the state)
   w.outcome = take(sizeof(int32_t) * c->B * (2 + VVS_MAX_T));
   w.node_result = take(sizeof(int32_t) * c->B * VVS_MAX_T * 2);
   w.tokens = take(sizeof(int32_t) * c->B * VVS_MAX_T);
@@ -122,6 +126,7 @@ vvs_status plan_sizes(const vvs_config* cfg, Ctx* c, std::string* err) {
   w.pq_work = take(sizeof(float) * (size_t)c->B * c->Tmax * 2 * veff);
   w.ss = take(sizeof(float) * (size_t)c->Mmax * (((d + 63) / 64 + 3) & ~3));     // per-row, per-64-column sums of squares of the residual
   w.ss2 = take(sizeof(float) * (size_t)c->Mlog * (((d + 63) / 64 + 3) & ~3));
+  w.ring = take(c->esz * (size_t)c->R * std::max(g.feature_slots, 1) * d);
   w.total = off;
   // packed weights
   PackedLayout& p = c->p;
@@ -384,6 +389,7 @@ vvs_status vvs_prefill(vvs_ctx* ctx, const void* d_prefix_cond, const void* d_pr
       launch_accept(c, one, 1, (const float*)(c->ws + c->w.logits), nullptr, nullptr, d_uniform, 1, 0, 0, 0, VVS_STRICT,
                     false, nullptr, nullptr, nullptr, false, st);
       launch_prefill_finish(c, n_forced, d_first_token, st);
+      launch_push_prefill_feature(c, T, st);
     }
   }
   vvs_status rc = check_launch(c, "prefill");
@@ -408,9 +414,9 @@ static vvs_status check_verify_args(Ctx* c, const char* who, int32_t n_nodes, co
   return VVS_OK;
 }
 
-vvs_status vvs_verify(vvs_ctx* ctx, int32_t n_nodes, const int32_t* h_parent, const uint8_t* h_tree_mask,
-                      const int32_t* d_draft_tokens, const float* d_draft_probs, const float* d_uniforms, int32_t mode,
-                      int32_t* d_accept_len, int32_t* d_path, int32_t* d_next_token, vvs_stream s) {
+vvs_status vvs_verify_post(vvs_ctx* ctx, int32_t n_nodes, int32_t n_post, const int32_t* h_parent, const uint8_t* h_tree_mask,
+                           const int32_t* d_draft_tokens, const float* d_draft_probs, const float* d_uniforms, int32_t mode,
+                           int32_t* d_accept_len, int32_t* d_path, int32_t* d_next_token, vvs_stream s) {
   Ctx* c = reinterpret_cast<Ctx*>(ctx);
   if (!c) return VVS_EINVAL;
   if (!c->prefilled) return fail(&c->err, VVS_ESTATE, "verify: call vvs_prefill first");
@@ -418,9 +424,17 @@ vvs_status vvs_verify(vvs_ctx* ctx, int32_t n_nodes, const int32_t* h_parent, co
   vvs_status rc = check_verify_args(c, "verify", n_nodes, d_draft_tokens, d_draft_probs, d_uniforms, mode, d_accept_len,
                                     d_path, d_next_token);
   if (rc != VVS_OK) return rc;
+  if (n_post < 0 || n_post > n_nodes) return fail(&c->err, VVS_EINVAL, "verify: n_post must be in [0, n_nodes]");
   TreeDesc tree;
   rc = build_tree(n_nodes, h_parent, h_tree_mask, &tree, &c->err);
   if (rc != VVS_OK) return rc;
+  for (int j = 1; j <= n_nodes; ++j) {
+    if (j <= n_post && tree.parent[j] != j - 1)
+      return fail(&c->err, VVS_EINVAL, "verify: the post-verified tokens must form a chain below the root");
+    if (j > n_post && tree.parent[j] < n_post)
+      return fail(&c->err, VVS_EINVAL, "verify: every candidate must descend from the last post-verified token");
+  }
+  tree.n_forced = n_post;
   hipStream_t st = (hipStream_t)s;
   const int T = n_nodes + 1;
   const int32_t* state = (const int32_t*)(c->ws + c->w.state);
@@ -434,6 +448,13 @@ vvs_status vvs_verify(vvs_ctx* ctx, int32_t n_nodes, const int32_t* h_parent, co
   c->verify_pending = true;
   c->last_T = T;
   return VVS_OK;
+}
+
+vvs_status vvs_verify(vvs_ctx* ctx, int32_t n_nodes, const int32_t* h_parent, const uint8_t* h_tree_mask,
+                      const int32_t* d_draft_tokens, const float* d_draft_probs, const float* d_uniforms, int32_t mode,
+                      int32_t* d_accept_len, int32_t* d_path, int32_t* d_next_token, vvs_stream s) {
+  return vvs_verify_post(ctx, n_nodes, 0, h_parent, h_tree_mask, d_draft_tokens, d_draft_probs, d_uniforms, mode, d_accept_len,
+                         d_path, d_next_token, s);
 }
 
 vvs_status vvs_accept_from_logits(vvs_ctx* ctx, int32_t n_nodes, const int32_t* h_parent, const uint8_t* h_tree_mask,
@@ -463,6 +484,16 @@ vvs_status vvs_kv_commit(vvs_ctx* ctx, vvs_stream s) {
   if (rc != VVS_OK) return rc;
   c->verify_pending = false;
   return VVS_OK;
+}
+
+vvs_status vvs_read_features(vvs_ctx* ctx, float* d_features, int32_t* d_count, vvs_stream s) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return VVS_EINVAL;
+  if (!d_features || !d_count) return fail(&c->err, VVS_EINVAL, "read_features: NULL");
+  if (c->cfg.feature_slots < 1) return fail(&c->err, VVS_ESTATE, "read_features: the context was created with feature_slots = 0");
+  if (!c->prefilled) return fail(&c->err, VVS_ESTATE, "read_features: call vvs_prefill first");
+  launch_read_features(c, d_features, d_count, (hipStream_t)s);
+  return check_launch(c, "read_features");
 }
 
 vvs_status vvs_read_state(vvs_ctx* ctx, int32_t* d_state, vvs_stream s) {

@@ -15,6 +15,7 @@ typedef uint16_t bf16_t;   // raw bf16 bits
 struct TreeDesc {
   int32_t T;                       // query tokens per row (root + N)
   int32_t causal;                  // 1: chain / prefill chunk (token i sees tokens 0..i of the block)
+  int32_t n_forced;                // nodes 1..n_forced are accepted without a test (post verification)
   int8_t parent[VVS_MAX_T];        // parent[0] = -1
   int8_t depth[VVS_MAX_T];
   int8_t first_child[VVS_MAX_T];   // -1 = leaf
@@ -36,7 +37,7 @@ struct GemmPlan { int bm, bn, splits; };
 // Byte offsets into the caller's workspace.
 struct Workspace {
   size_t state, outcome, node_result, tokens, rope_tab, x, h, gemm_out, q, attn, act, hf, logits, probs,
-      pq_work, ss, ss2, total;
+      pq_work, ss, ss2, ring, ring_state, total;
 };
 
 struct PackedLayout {
@@ -103,6 +104,8 @@ void launch_accept(Ctx* c, const TreeDesc& tree, int T, const float* d_logits, c
                    bool keep_outcome, hipStream_t s);
 void launch_prefill_finish(Ctx* c, int n_forced, int32_t* d_first, hipStream_t s);
 void launch_commit(Ctx* c, hipStream_t s);
+void launch_push_prefill_feature(Ctx* c, int T_last_chunk, hipStream_t s);
+void launch_read_features(Ctx* c, float* d_features, int32_t* d_count, hipStream_t s);
 void launch_read_state(Ctx* c, int32_t* d_state, hipStream_t s);
 void launch_set_state(Ctx* c, const int32_t* d_state, hipStream_t s);
 void launch_debug_logits(Ctx* c, float* raw, float* mixed, float* probs, hipStream_t s);

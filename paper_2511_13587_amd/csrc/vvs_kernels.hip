@@ -681,6 +681,8 @@ __global__ void k_commit_state(int32_t* __restrict__ state, const int32_t* __res
   state[2 * B + b] = next_token[b];        // pending token
 }
 
+static void launch_push_features(Ctx* c, const int32_t* path, int Tq, int fixed_node, hipStream_t s);
+
 void launch_commit(Ctx* c, hipStream_t s) {
   Timed timed(c, VVS_K_COMMIT, s);
   int32_t* state = (int32_t*)(c->ws + c->w.state);
@@ -702,7 +704,91 @@ void launch_commit(Ctx* c, hipStream_t s) {
   else
     hipLaunchKernelGGL((k_commit_kv<float, float>), grid, dim3(256), 0, s, (float*)c->kv, (float*)c->kv + c->kv_v_off, state, accept_len,
                        next_token, path, c->H, c->dh, c->kv_layer_stride, c->kv_row_stride, c->kv_head_stride, c->S_cap);
+  launch_push_features(c, path, c->last_T, -1, s);
   hipLaunchKernelGGL(k_commit_state, dim3((c->B + 63) / 64), dim3(64), 0, s, state, accept_len, next_token, c->B);
+}
+
+// ------------------------------------------------------------------------------------------------ token-level feature cache
+// Section 4.3 / Algorithm 2 "UpdateCache".  One workgroup per row appends the features of n tokens of the
+// last forward (rows r * Tq + node of the residual stream x) to the row's ring: a feature is
+// rmsnorm(x) * gf - the input of the output head - or x itself (pre_norm), stored like an activation
+// of the model.  Ring state per row: (entries held, slot of the oldest); the token appended as the
+// k-th since the oldest goes to slot (oldest + held + k) % slots.
+//   path != nullptr: commit - the tokens are path[b][0 .. accept_len[b]] (skipped for finished prompts);
+//   path == nullptr: prefill - the single token fixed_node, into an emptied ring.
+template <typename T>
+__global__ __launch_bounds__(256) void k_push_features(const float* __restrict__ x, const float* __restrict__ gf, T* __restrict__ ring,
+                                                       int32_t* __restrict__ ring_state, const int32_t* __restrict__ accept_len,
+                                                       const int32_t* __restrict__ next_token, const int32_t* __restrict__ path, int Tq,
+                                                       int fixed_node, int R, int d, int slots, int pre_norm, float eps) {
+  __shared__ float red[16];
+  const int r = blockIdx.x, b = r >> 1;
+  int n = 1, held = 0, oldest = 0;
+  if (path) {
+    if (next_token[b] < 0) return;
+    n = accept_len[b] + 1;
+    held = ring_state[r];
+    oldest = ring_state[R + r];
+  }
+  for (int i = max(0, n - slots); i < n; ++i) {            // older ones would be overwritten by this very push
+    const int node = path ? path[b * VVS_MAX_T + i] : fixed_node;
+    const float* xr = x + ((size_t)r * Tq + node) * d;
+    float scale = 1.f;
+    if (!pre_norm) {
+      float ss = 0.f;
+      for (int k = threadIdx.x; k < d; k += blockDim.x) ss += xr[k] * xr[k];
+      ss = block_sum(ss, red);
+      scale = 1.0f / sqrtf(ss / (float)d + eps);
+    }
+    T* dst = ring + ((size_t)r * slots + (oldest + held + i) % slots) * d;
+    for (int k = threadIdx.x; k < d; k += blockDim.x) st(dst + k, pre_norm ? xr[k] : xr[k] * scale * gf[k]);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int now = min(held + n, slots);
+    ring_state[r] = now;
+    ring_state[R + r] = (oldest + held + n - now) % slots;
+  }
+}
+
+static void launch_push_features(Ctx* c, const int32_t* path, int Tq, int fixed_node, hipStream_t s) {
+  if (c->cfg.feature_slots < 1) return;
+  const int32_t* oc = (const int32_t*)(c->ws + c->w.outcome);
+  const float* x = (const float*)(c->ws + c->w.x);
+  const float* gf = (const float*)(c->pw + c->p.gf);
+  int32_t* rstate = (int32_t*)(c->ws + c->w.ring_state);
+  if (c->cfg.dtype == VVS_BF16)
+    hipLaunchKernelGGL(k_push_features<bf16_t>, dim3(c->R), dim3(256), 0, s, x, gf, (bf16_t*)(c->ws + c->w.ring), rstate, oc, oc + c->B, path,
+                       Tq, fixed_node, c->R, c->d, c->cfg.feature_slots, c->cfg.feature_pre_norm, c->cfg.rms_eps);
+  else
+    hipLaunchKernelGGL(k_push_features<float>, dim3(c->R), dim3(256), 0, s, x, gf, (float*)(c->ws + c->w.ring), rstate, oc, oc + c->B, path,
+                       Tq, fixed_node, c->R, c->d, c->cfg.feature_slots, c->cfg.feature_pre_norm, c->cfg.rms_eps);
+}
+
+void launch_push_prefill_feature(Ctx* c, int T_last_chunk, hipStream_t s) {
+  launch_push_features(c, nullptr, T_last_chunk, T_last_chunk - 1, s);
+}
+
+template <typename T>
+__global__ void k_read_features(const T* __restrict__ ring, const int32_t* __restrict__ ring_state, float* __restrict__ out,
+                                int32_t* __restrict__ count, int R, int d, int slots) {
+  const int r = blockIdx.x, j = blockIdx.y;                // j-th oldest entry of row r
+  const int held = ring_state[r], oldest = ring_state[R + r];
+  if (j == 0 && threadIdx.x == 0 && (r & 1) == 0) count[r >> 1] = held;
+  const T* src = ring + ((size_t)r * slots + (oldest + j) % slots) * d;
+  float* dst = out + ((size_t)r * slots + j) * d;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) dst[k] = j < held ? ld(src + k) : 0.f;
+}
+
+void launch_read_features(Ctx* c, float* d_features, int32_t* d_count, hipStream_t s) {
+  const int32_t* rstate = (const int32_t*)(c->ws + c->w.ring_state);
+  dim3 grid(c->R, c->cfg.feature_slots);
+  if (c->cfg.dtype == VVS_BF16)
+    hipLaunchKernelGGL(k_read_features<bf16_t>, grid, dim3(256), 0, s, (const bf16_t*)(c->ws + c->w.ring), rstate, d_features, d_count, c->R,
+                       c->d, c->cfg.feature_slots);
+  else
+    hipLaunchKernelGGL(k_read_features<float>, grid, dim3(256), 0, s, (const float*)(c->ws + c->w.ring), rstate, d_features, d_count, c->R,
+                       c->d, c->cfg.feature_slots);
 }
 
 __global__ void k_read_state(const int32_t* __restrict__ state, int32_t* __restrict__ out, int n) {

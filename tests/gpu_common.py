@@ -51,15 +51,16 @@ def perturbed_rounding(oracle, eps=1e-7, seed=1):
 class Pair:
     """The HIP context and the checker, fed with identical inputs."""
 
-    def __init__(self, shape, weights=None, gain_jitter=0.0, std=0.02, with_oracle=True, shadow=False):
+    def __init__(self, shape, weights=None, gain_jitter=0.0, std=0.02, with_oracle=True, shadow=False, feature_pre_norm=0):
         self.shape = shape
         self.w = weights if weights is not None else synth.make_weights(shape, std=std, gain_jitter=gain_jitter)
-        self.cfg = vb.make_config(shape)
+        self.cfg = vb.make_config(shape, feature_pre_norm=feature_pre_norm)
+        ocfg = dict(dataclasses.asdict(shape), feature_slots=self.cfg.feature_slots, feature_pre_norm=feature_pre_norm)
         self.ctx = vb.Context(self.cfg)
         self.ctx.load_weights_from_host(self.w, synth.weight_names(shape))
-        self.oracle = vo.Oracle(dataclasses.asdict(shape), self.w) if with_oracle else None
+        self.oracle = vo.Oracle(ocfg, self.w) if with_oracle else None
         # a second checker with perturbed rounding measures the noise floor of this shape on these inputs
-        self.shadow = perturbed_rounding(vo.Oracle(dataclasses.asdict(shape), self.w)) if shadow else None
+        self.shadow = perturbed_rounding(vo.Oracle(ocfg, self.w)) if shadow else None
         self.floor = 0.0
         self.dev = self.ctx.device
         B = shape.n_prompts
@@ -110,12 +111,15 @@ class Pair:
                 self.floor = max(self.floor, float(np.abs(self.shadow.prefill_logits - self.oracle.prefill_logits).max()))
         return first.cpu().numpy(), ofirst, u
 
-    def verify(self, parent, tokens, q, u, mode=0, run_oracle=True, mask=None):
+    def verify(self, parent, tokens, q, u, mode=0, run_oracle=True, mask=None, n_post=0):
         N = 0 if tokens is None else tokens.shape[1]
         dtok = None if N == 0 else torch.from_numpy(np.ascontiguousarray(tokens, dtype=np.int32)).to(self.dev)
         dq = None if N == 0 else torch.from_numpy(np.ascontiguousarray(q, dtype=np.float32)).to(self.dev)
         du = torch.from_numpy(np.ascontiguousarray(u, dtype=np.float32)).to(self.dev)
-        self.ctx.vvs_verify(N, parent, mask, dtok, dq, du, mode, self.accept_len, self.path, self.next_token)
+        if n_post:
+            self.ctx.vvs_verify_post(N, n_post, parent, mask, dtok, dq, du, mode, self.accept_len, self.path, self.next_token)
+        else:
+            self.ctx.vvs_verify(N, parent, mask, dtok, dq, du, mode, self.accept_len, self.path, self.next_token)
         torch.cuda.synchronize()
         out = (self.accept_len.cpu().numpy().copy(), self.path.cpu().numpy().copy(), self.next_token.cpu().numpy().copy())
         oout = None
@@ -127,9 +131,9 @@ class Pair:
                 self.shadow.kv_len(b) == self.oracle.kv_len(b) for b in range(self.shape.n_prompts))
             if same_state:
                 self.shadow.pending[:] = self.oracle.pending
-            oout = self.oracle.verify(oparent, otok, oq, u, mode)
+            oout = self.oracle.verify(oparent, otok, oq, u, mode, n_post=n_post)
             if same_state:
-                self.shadow.verify(oparent, otok, oq, u, mode)
+                self.shadow.verify(oparent, otok, oq, u, mode, n_post=n_post)
                 self.floor = max(self.floor, float(np.abs(self.shadow.raw_logits - self.oracle.raw_logits).max()))
         return out, oout
 
