@@ -294,6 +294,18 @@ def main():
         "kernel_classes": classes,
         "roofline": roof,
     }
+    # the dynamic schedule's decision kernel (Eq. 2 on the same draft tree), timed on its own: it is not part of a verify step
+    emb = torch.from_numpy(synth.make_codebook_embeddings(shape.vocab)).to(dev)
+    ctx.vvs_set_codebook(emb)
+    for _ in range(5):
+        ctx.vvs_path_similarity(N, parent, None, dtoks, 0.8, 2)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(200):
+        sim = ctx.vvs_path_similarity(N, parent, None, dtoks, 0.8, 2)
+    torch.cuda.synchronize()
+    out["scheduler"] = {"path_similarity_us_per_call": (time.perf_counter() - t0) / 200 * 1e6, "alpha": 0.8, "stride": 2,
+                        "mean_similarity": float(sim.mean().item())}
     ctx.close()
     del ctx
     if not args.no_cpu_baseline:

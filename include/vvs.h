@@ -187,6 +187,42 @@ vvs_status vvs_kv_commit(vvs_ctx* ctx, vvs_stream s);
  * vvs_set_state does not touch the cache. */
 vvs_status vvs_read_features(vvs_ctx* ctx, float* d_features, int32_t* d_count, vvs_stream s);
 
+/* ---- The verification-free step (Sections 4.2 and 4.4).  Host-only helpers need no context. ----
+ *
+ * Candidate paths of a draft tree = its root-to-leaf node sequences (root excluded), ordered by the
+ * node id of their leaf.
+ *
+ * vvs_select_unverified (Section 4.2, Eq. 1): draws one candidate path uniformly with the uniform
+ * u in [0, 1) (path floor(u * |P|)) and keeps its first gamma = min(L_s, floor(mean path length))
+ * nodes.  Topology arguments as in vvs_check_tree.  h_nodes: host int32 [VVS_MAX_T] out, the kept node
+ * ids in path order (these are the tokens to hand to the next vvs_verify_post as its unverified
+ * tokens); n_kept: their number (0 for an empty tree). */
+vvs_status vvs_select_unverified(int32_t n_nodes, const int32_t* h_parent, const uint8_t* h_tree_mask, float u,
+                                 int32_t* h_nodes, int32_t* n_kept);
+
+/* Uniform-interval policy (Section 4.4): 1 iff step step_index (counted from 0) is verification-free for
+ * interval i, i.e. (step_index + 1) % i == 0 with i >= 2; never two in a row. */
+int32_t vvs_skip_uniform(int32_t step_index, int32_t interval);
+
+/* Dynamic policy (Algorithm 1): 1 iff the last step was verified and similarity >= threshold. */
+int32_t vvs_skip_dynamic(float similarity, float threshold, int32_t last_step_verified);
+
+/* Latent codebook for vvs_path_similarity: float [vocab, dim] on the device, dim in [1, 64]; kept by
+ * reference. */
+vvs_status vvs_set_codebook(vvs_ctx* ctx, const float* d_embed, int32_t dim);
+
+/* Weighted average similarity of the candidate paths (Eq. 2; Algorithm 1 "CompSim" after
+ * "Downsample"): per prompt, S = sum_l w_l S_l with w_l proportional to alpha^l, where S_l is the mean
+ * cosine similarity of the codebook embeddings of the tokens at position l over all unordered pairs of
+ * the kept paths that reach position l.  Every stride-th path is kept, starting with the first.
+ * Positions reached by fewer than two kept paths are left out (weights renormalised); with no such
+ * position S = 1; an all-zero embedding has cosine 0.
+ *   d_draft_tokens int32 [B, N] full-vocabulary ids (as for vvs_verify); d_similarity float [B] out.
+ * Does not touch the model state; may run on another stream than a verify in flight. */
+vvs_status vvs_path_similarity(vvs_ctx* ctx, int32_t n_nodes, const int32_t* h_parent, const uint8_t* h_tree_mask,
+                               const int32_t* d_draft_tokens, float alpha, int32_t stride, float* d_similarity,
+                               vvs_stream s);
+
 /* Per-prompt state: int32 [3, B] out = cached length S_b, emitted image tokens, pending token. */
 vvs_status vvs_read_state(vvs_ctx* ctx, int32_t* d_state, vvs_stream s);
 

@@ -56,6 +56,11 @@ def _load():
         "vvs_verify": (i32, [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]),
         "vvs_verify_post": (i32, [vp, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]),
         "vvs_read_features": (i32, [vp, vp, vp, vp]),
+        "vvs_select_unverified": (i32, [i32, vp, vp, C.c_float, vp, C.POINTER(i32)]),
+        "vvs_skip_uniform": (i32, [i32, i32]),
+        "vvs_skip_dynamic": (i32, [C.c_float, C.c_float, i32]),
+        "vvs_set_codebook": (i32, [vp, vp, i32]),
+        "vvs_path_similarity": (i32, [vp, i32, vp, vp, vp, C.c_float, i32, vp, vp]),
         "vvs_accept_from_logits": (i32, [vp, i32, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]),
         "vvs_kv_commit": (i32, [vp, vp]),
         "vvs_read_state": (i32, [vp, vp, vp]),
@@ -103,6 +108,25 @@ def vvs_check_tree(n_nodes: int, parent: Optional[np.ndarray], mask: Optional[np
     st = lib.vvs_check_tree(n_nodes, None if p is None else p.ctypes.data, None if m is None else m.ctypes.data,
                             depth.ctypes.data, pout.ctypes.data)
     return st, depth, pout[:max(n_nodes, 0)]
+
+
+def vvs_select_unverified(n_nodes: int, parent: Optional[np.ndarray], mask: Optional[np.ndarray], u: float):
+    """Host-only: (status, kept node ids) of the uniformly drawn, truncated candidate path."""
+    nodes = np.zeros(VVS_MAX_T, dtype=np.int32)
+    kept = C.c_int32()
+    p = None if parent is None else np.ascontiguousarray(parent, dtype=np.int32)
+    m = None if mask is None else np.ascontiguousarray(mask, dtype=np.uint8)
+    st = lib.vvs_select_unverified(n_nodes, None if p is None else p.ctypes.data, None if m is None else m.ctypes.data,
+                                   float(u), nodes.ctypes.data, C.byref(kept))
+    return st, nodes[:max(kept.value, 0)].copy()
+
+
+def vvs_skip_uniform(step_index: int, interval: int) -> bool:
+    return bool(lib.vvs_skip_uniform(step_index, interval))
+
+
+def vvs_skip_dynamic(similarity: float, threshold: float, last_step_verified: bool) -> bool:
+    return bool(lib.vvs_skip_dynamic(float(similarity), float(threshold), 1 if last_step_verified else 0))
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -211,6 +235,20 @@ class Context:
                                         None if m is None else m.ctypes.data, _ptr(draft_tokens), _ptr(draft_probs),
                                         _ptr(uniforms), mode, _ptr(accept_len), _ptr(path), _ptr(next_token), _stream()))
         self.last_T = n_nodes + 1
+
+    def vvs_set_codebook(self, embed: torch.Tensor):
+        assert embed.dtype == torch.float32 and embed.dim() == 2
+        self._codebook = embed                      # kept by reference in the library
+        self._check(lib.vvs_set_codebook(self.h, _ptr(embed), int(embed.shape[1])))
+
+    def vvs_path_similarity(self, n_nodes: int, parent, tree_mask, draft_tokens: Optional[torch.Tensor], alpha: float, stride: int = 2):
+        p = None if parent is None else np.ascontiguousarray(parent, dtype=np.int32)
+        m = None if tree_mask is None else np.ascontiguousarray(tree_mask, dtype=np.uint8)
+        out = torch.empty((self.B,), dtype=torch.float32, device=self.device)
+        self._check(lib.vvs_path_similarity(self.h, n_nodes, None if p is None else p.ctypes.data,
+                                            None if m is None else m.ctypes.data, _ptr(draft_tokens), float(alpha), int(stride),
+                                            _ptr(out), _stream()))
+        return out
 
     def vvs_read_features(self):
         """(features float32 [R, feature_slots, d] oldest first, count int32 [B])."""

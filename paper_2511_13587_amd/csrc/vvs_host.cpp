@@ -7,6 +7,7 @@
 #include <stdlib.h>
 #include <string.h>
 #include <algorithm>
+#include <cmath>
 #include <vector>
 
 namespace vvs {
@@ -268,6 +269,8 @@ vvs_status vvs_create(const vvs_config* cfg, void* d_kv, void* d_workspace, void
   }
   c->kv = (char*)d_kv; c->ws = (char*)d_workspace; c->pw = (char*)d_packed_weights;
   c->nbr = nullptr;
+  c->codebook = nullptr;
+  c->code_dim = 0;
   // zero the KV cache (padded slots are read, multiplied by zero weights) and the state block
   launch_fill_zero(c->kv, 2 * c->kv_v_off * c->esz, nullptr);
   launch_fill_zero(c->ws, c->w.x, nullptr);
@@ -484,6 +487,67 @@ vvs_status vvs_kv_commit(vvs_ctx* ctx, vvs_stream s) {
   if (rc != VVS_OK) return rc;
   c->verify_pending = false;
   return VVS_OK;
+}
+
+vvs_status vvs_select_unverified(int32_t n_nodes, const int32_t* h_parent, const uint8_t* h_tree_mask, float u, int32_t* h_nodes,
+                                 int32_t* n_kept) {
+  if (!h_nodes || !n_kept) return VVS_EINVAL;
+  if (!(u >= 0.f && u < 1.f)) return VVS_EINVAL;
+  TreeDesc t;
+  vvs_status st = build_tree(n_nodes, h_parent, h_tree_mask, &t, nullptr);
+  if (st != VVS_OK) return st;
+  *n_kept = 0;
+  // candidate paths = one per leaf, in leaf order; their lengths are the leaves' depths
+  std::vector<int> leaves;
+  long total = 0;
+  for (int j = 1; j <= n_nodes; ++j)
+    if (t.first_child[j] < 0) { leaves.push_back(j); total += t.depth[j]; }
+  if (leaves.empty()) return VVS_OK;
+  const int n_paths = (int)leaves.size();
+  const int sel = std::min((int)std::floor((double)u * n_paths), n_paths - 1);
+  const int mean_floor = (int)(total / n_paths);                     // floor of the mean path length (Eq. 1)
+  const int len = t.depth[leaves[sel]], keep = std::min(len, mean_floor);
+  int node = leaves[sel];
+  for (int k = len - 1; k >= 0; --k) {                               // walk up; position k of the path is the ancestor at depth k + 1
+    if (k < keep) h_nodes[k] = node;
+    node = t.parent[node];
+  }
+  *n_kept = keep;
+  return VVS_OK;
+}
+
+int32_t vvs_skip_uniform(int32_t step_index, int32_t interval) {
+  return interval >= 2 && step_index >= 0 && (step_index + 1) % interval == 0;
+}
+
+int32_t vvs_skip_dynamic(float similarity, float threshold, int32_t last_step_verified) {
+  return last_step_verified != 0 && similarity >= threshold;
+}
+
+vvs_status vvs_set_codebook(vvs_ctx* ctx, const float* d_embed, int32_t dim) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return VVS_EINVAL;
+  if (!d_embed) return fail(&c->err, VVS_EINVAL, "set_codebook: table is NULL");
+  if (dim < 1 || dim > 64) return fail(&c->err, VVS_ESIZE, "set_codebook: dim must be in [1, 64]");
+  c->codebook = d_embed;
+  c->code_dim = dim;
+  return VVS_OK;
+}
+
+vvs_status vvs_path_similarity(vvs_ctx* ctx, int32_t n_nodes, const int32_t* h_parent, const uint8_t* h_tree_mask,
+                               const int32_t* d_draft_tokens, float alpha, int32_t stride, float* d_similarity, vvs_stream s) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return VVS_EINVAL;
+  if (!c->codebook) return fail(&c->err, VVS_ESTATE, "path_similarity: call vvs_set_codebook first");
+  if (!d_similarity || (n_nodes > 0 && !d_draft_tokens)) return fail(&c->err, VVS_EINVAL, "path_similarity: NULL argument");
+  if (stride < 1) return fail(&c->err, VVS_EINVAL, "path_similarity: stride < 1");
+  if (!(alpha > 0.f)) return fail(&c->err, VVS_EINVAL, "path_similarity: alpha must be positive");
+  if (n_nodes > c->cfg.max_nodes) return fail(&c->err, VVS_ESIZE, "path_similarity: n_nodes exceeds max_nodes of the context");
+  TreeDesc tree;
+  vvs_status rc = build_tree(n_nodes, h_parent, h_tree_mask, &tree, &c->err);
+  if (rc != VVS_OK) return rc;
+  launch_path_similarity(c, tree, n_nodes, d_draft_tokens, alpha, stride, d_similarity, (hipStream_t)s);
+  return check_launch(c, "path_similarity");
 }
 
 vvs_status vvs_read_features(vvs_ctx* ctx, float* d_features, int32_t* d_count, vvs_stream s) {

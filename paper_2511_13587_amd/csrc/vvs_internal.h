@@ -59,6 +59,7 @@ struct Ctx {
   PackedLayout p;
   size_t gemm_out_elems;
   const int32_t* nbr;
+  const float* codebook; int code_dim;   // latent codebook of the path-similarity kernel (by reference)
   bool weights_loaded, prefilled, verify_pending;
   int last_T;                            // T of the last verify / prefill (for debug export)
   std::string err;
@@ -106,6 +107,8 @@ void launch_prefill_finish(Ctx* c, int n_forced, int32_t* d_first, hipStream_t s
 void launch_commit(Ctx* c, hipStream_t s);
 void launch_push_prefill_feature(Ctx* c, int T_last_chunk, hipStream_t s);
 void launch_read_features(Ctx* c, float* d_features, int32_t* d_count, hipStream_t s);
+void launch_path_similarity(Ctx* c, const TreeDesc& tree, int n_nodes, const int32_t* d_draft_tokens, float alpha, int stride,
+                            float* d_similarity, hipStream_t s);
 void launch_read_state(Ctx* c, int32_t* d_state, hipStream_t s);
 void launch_set_state(Ctx* c, const int32_t* d_state, hipStream_t s);
 void launch_debug_logits(Ctx* c, float* raw, float* mixed, float* probs, hipStream_t s);

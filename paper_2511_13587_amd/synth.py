@@ -268,6 +268,15 @@ def make_forced_tokens(shape: Shape, n_forced: int) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------- codebook neighbours
+def make_codebook_embeddings(vocab: int, dim: int = 8, seed: int = 4242) -> np.ndarray:
+    """float32 [vocab, dim]: the random unit-norm latent embeddings behind make_codebook_neighbours
+    (same seed, same vectors), standing in for the VQ codebook of the image tokenizer."""
+    rng = np.random.default_rng(seed)
+    e = rng.standard_normal((vocab, dim))
+    e /= np.linalg.norm(e, axis=1, keepdims=True)
+    return e.astype(np.float32)
+
+
 def make_codebook_neighbours(vocab: int, k: int, dim: int = 8, seed: int = 4242) -> np.ndarray:
     """int32 [vocab, k]: for every code, its k nearest other codes by cosine distance on random
     unit-norm `dim`-d embeddings, ascending distance, ties broken by the lower id."""

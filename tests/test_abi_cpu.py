@@ -107,3 +107,33 @@ def test_check_tree_rejects_malformed_input(binding):
     bad = mask.copy(); bad[1, 3] = 1                                            # looks ahead
     assert binding.vvs_check_tree(3, parent, bad)[0] == -1
     assert binding.vvs_check_tree(3, np.array([0, 1, 2]), mask)[0] == -1        # mask of another tree
+
+
+def test_select_unverified_and_skip_rules_match_the_checker(binding):
+    """Host-only logic of the verification-free step (Section 4.2, Eq. 1; Section 4.4; Algorithm 1):
+    the library's answers equal the CPU checker's on random trees and uniforms."""
+    from oracle import vvs_schedule as vs
+    rng = np.random.default_rng(5)
+    for trial in range(200):
+        n = int(rng.integers(0, 40))
+        parent = np.array([int(rng.integers(0, j)) for j in range(1, n + 1)], dtype=np.int32)
+        u = np.float32(rng.random())
+        if u >= 1.0:
+            u = np.float32(0.5)
+        st, kept = binding.vvs_select_unverified(n, parent if n else None, None, float(u))
+        assert st == binding.VVS_OK
+        assert list(kept) == vs.select_unverified(parent, float(u)), (parent, u)
+    # the synthetic benchmark trees, from the ancestor mask alone
+    for widths, n in (((4, 6, 6, 4, 3, 3), 26), ((8, 12, 12, 10, 8, 6, 4), 60)):
+        parent = synth.tree_parents(widths, n)
+        st, kept = binding.vvs_select_unverified(n, None, synth.ancestor_mask(parent), 0.37)
+        assert st == binding.VVS_OK and list(kept) == vs.select_unverified(parent, np.float32(0.37))
+    st, _ = binding.vvs_select_unverified(3, np.array([0, 0, 1], dtype=np.int32), None, 1.0)
+    assert st == binding.VVS_EINVAL
+    st, _ = binding.vvs_select_unverified(3, np.array([0, 2, 1], dtype=np.int32), None, 0.5)       # parent after child
+    assert st == binding.VVS_EINVAL
+    for i in range(0, 6):
+        for t in range(20):
+            assert binding.vvs_skip_uniform(t, i) == vs.skip_uniform(t, i)
+    for s, thr, last in ((0.81, 0.8, True), (0.8, 0.8, True), (0.79, 0.8, True), (0.99, 0.8, False)):
+        assert binding.vvs_skip_dynamic(s, thr, last) == vs.skip_dynamic(np.float32(s), np.float32(thr), last)
