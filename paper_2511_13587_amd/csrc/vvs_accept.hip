@@ -9,6 +9,11 @@
 
 #include <limits.h>
 
+// Phase marks: a profiling build may define VVS_PHASE_MARK(i) to record a time stamp; normally nothing.
+#ifndef VVS_PHASE_MARK
+#define VVS_PHASE_MARK(i)
+#endif
+
 namespace vvs {
 
 struct AcceptArgs {
@@ -35,8 +40,28 @@ __device__ int inverse_cdf(const float* __restrict__ P, int n, float u, float* r
   const int nt = blockDim.x, tid = threadIdx.x;
   const int per = (n + nt - 1) / nt;
   const int beg = min(tid * per, n), end = min(beg + per, n);
+  // chunks of up to 16 ids are read once into registers (16-byte reads when the chunk is aligned)
+  constexpr int CK = 16;
+  float c[CK];
+  const bool in_regs = per <= CK;
   float local = 0.f;
-  for (int v = beg; v < end; ++v) local += P[v];
+  if (in_regs) {
+    if ((per & 3) == 0 && (n & 3) == 0) {
+#pragma unroll
+      for (int i = 0; i < CK; i += 4) {
+        float4 v4 = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (i < per && beg + i < end) v4 = *(const float4*)(P + beg + i);
+        c[i] = v4.x; c[i + 1] = v4.y; c[i + 2] = v4.z; c[i + 3] = v4.w;
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < CK; ++i) c[i] = (beg + i < end) ? P[beg + i] : 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < CK; ++i) local += c[i];               // ids past the chunk hold 0
+  } else {
+    for (int v = beg; v < end; ++v) local += P[v];
+  }
   // exclusive scan of the per-thread sums: inclusive inside a wave, then wave offsets in order
   float inc = local;
 #pragma unroll
@@ -56,11 +81,23 @@ __device__ int inverse_cdf(const float* __restrict__ P, int n, float u, float* r
   const float target = u * total;
   float run = woff + inc - local;
   int cand = INT_MAX, last_pos = -1;
-  for (int v = beg; v < end; ++v) {
-    const float pv = P[v];
-    run += pv;
-    if (pv > 0.f) last_pos = v;
-    if (cand == INT_MAX && run > target) cand = v;
+  if (in_regs) {
+#pragma unroll
+    for (int i = 0; i < CK; ++i) {
+      const float pv = c[i];
+      run += pv;
+      if (beg + i < end) {
+        if (pv > 0.f) last_pos = beg + i;
+        if (cand == INT_MAX && run > target) cand = beg + i;
+      }
+    }
+  } else {
+    for (int v = beg; v < end; ++v) {
+      const float pv = P[v];
+      run += pv;
+      if (pv > 0.f) last_pos = v;
+      if (cand == INT_MAX && run > target) cand = v;
+    }
   }
   int win = block_min_int(cand, ired);
   if (win == INT_MAX) win = block_max_int(last_pos, ired);
@@ -73,13 +110,17 @@ __device__ int inverse_cdf(const float* __restrict__ P, int n, float u, float* r
 template <bool LDS_PQ>
 __global__ __launch_bounds__(1024) void k_accept_node(AcceptArgs a, TreeDesc tree) {
   extern __shared__ float pq_lds[];
-  __shared__ float red[16];
+  __shared__ float red[32];
   __shared__ int ired[16];
   __shared__ float scan[16];
   __shared__ float nb_mass[64];
   __shared__ int nb_id[64];
-  __shared__ float sh_num;
+  __shared__ float sh_num, sh_px, sh_qx;
   __shared__ int sh_m;
+  __shared__ int sh_cx[VVS_MAX_T];         // drafted ids (inside the slice) and accept uniforms of this node's children, in order
+  __shared__ float sh_cu[VVS_MAX_T];
+  __shared__ int sh_cn[VVS_MAX_T], sh_nc;  // their node ids; how many
+  VVS_PHASE_MARK(0);
   const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, nt = blockDim.x;
   const int T = a.T, V = a.veff;
   const float* lc = a.logits + ((size_t)(2 * b) * T + j) * V;
@@ -88,12 +129,17 @@ __global__ __launch_bounds__(1024) void k_accept_node(AcceptArgs a, TreeDesc tre
   float* Q = P + V;
   float* prow = a.probs + (size_t)(b * T + j) * V;
 
-  // CFG mix + softmax (temperature 1) over the allowed slice.  Up to 16 ids per thread (the usual
-  // codebook sizes) stay in registers: all logits are requested at once instead of one dependent
-  // memory round trip per pass of a loop; larger slices take the generic loops.
+  // CFG mix + softmax (temperature 1) over the allowed slice.  Up to RK ids per thread (the usual
+  // codebook sizes): thread tid owns ids tid + k * nt and keeps its part of the running target (and
+  // later of the draft distribution) in registers for the whole kernel; the LDS / global copy P is
+  // only brought up to date where ids are addressed at random (relaxed neighbourhoods, the final
+  // inverse-CDF draw).  Larger slices take the generic loops over P and Q.
   constexpr int RK = 16;
-  if (V <= RK * nt) {
-    float m[RK];
+  const bool regs = V <= RK * nt;
+  float p[RK], q[RK];
+#pragma unroll
+  for (int k = 0; k < RK; ++k) p[k] = q[k] = 0.f;
+  if (regs) {
     float lcv[RK], luv[RK];
 #pragma unroll
     for (int k = 0; k < RK; ++k) {
@@ -104,24 +150,25 @@ __global__ __launch_bounds__(1024) void k_accept_node(AcceptArgs a, TreeDesc tre
     float mx = -INFINITY;
 #pragma unroll
     for (int k = 0; k < RK; ++k) {
-      m[k] = tid + k * nt < V ? luv[k] + a.scale * (lcv[k] - luv[k]) : -INFINITY;
-      mx = fmaxf(mx, m[k]);
+      p[k] = tid + k * nt < V ? luv[k] + a.scale * (lcv[k] - luv[k]) : -INFINITY;
+      mx = fmaxf(mx, p[k]);
     }
     mx = block_max(mx, red);
     float sum = 0.f;
 #pragma unroll
     for (int k = 0; k < RK; ++k) {
-      m[k] = tid + k * nt < V ? expf(m[k] - mx) : 0.f;
-      sum += m[k];
+      p[k] = tid + k * nt < V ? expf(p[k] - mx) : 0.f;
+      sum += p[k];
     }
     sum = block_sum(sum, red);
+    const float inv_sum = 1.0f / sum;
 #pragma unroll
     for (int k = 0; k < RK; ++k) {
       const int v = tid + k * nt;
+      p[k] = p[k] * inv_sum;
       if (v < V) {
-        const float pv = m[k] / sum;
-        P[v] = pv;
-        prow[v] = pv;
+        P[v] = p[k];
+        prow[v] = p[k];
       }
     }
   } else {
@@ -140,13 +187,14 @@ __global__ __launch_bounds__(1024) void k_accept_node(AcceptArgs a, TreeDesc tre
     }
     sum = block_sum(sum, red);
     for (int v = tid; v < V; v += nt) {
-      const float p = P[v] / sum;
-      P[v] = p;
-      prow[v] = p;
+      const float pv = P[v] / sum;
+      P[v] = pv;
+      prow[v] = pv;
     }
   }
   __syncthreads();
 
+  VVS_PHASE_MARK(1);
   int32_t* res = a.node_result + ((size_t)b * VVS_MAX_T + j) * 2;
   int cap = INT_MAX;
   if (a.n_emitted) {
@@ -159,24 +207,54 @@ __global__ __launch_bounds__(1024) void k_accept_node(AcceptArgs a, TreeDesc tre
   }
 
   int accepted = 0;
+  bool p_in_memory = true;                   // P holds the current target (false: only the registers do)
   if (tree.first_child[j] >= 0 && tree.depth[j] < cap && tree.first_child[j] <= tree.n_forced) {
     accepted = tree.first_child[j];          // post verification: accepted without a test, nothing is read or changed
   } else if (tree.first_child[j] >= 0 && tree.depth[j] < cap) {
     const float* qrow = a.q + (size_t)(b * T + j) * V;
-    for (int v0 = tid; v0 < V; v0 += 8 * nt) {               // 8 independent requests per thread and pass
-      float qv[8];
+    const int N = T - 1;
+    // the children (ascending node id = the order in which they are tried), their drafted ids and
+    // uniforms: found by the first wave in parallel, one memory round trip for all of them
+    if (tid < VVS_MAX_T) {
+      const bool child = tid > 0 && tid < T && tree.parent[tid] == j;
+      const unsigned long long m = __ballot(child);
+      if (child) {
+        const int rank = __popcll(m & ((1ull << tid) - 1ull));
+        sh_cn[rank] = tid;
+        sh_cx[rank] = min(max(a.draft[b * N + tid - 1] - a.lo, 0), V - 1);
+        sh_cu[rank] = a.u[(size_t)b * a.usb + (size_t)tid * a.usj + a.uoa];
+      }
+      if (tid == 0) sh_nc = __popcll(m);
+    }
+    if (regs) {
 #pragma unroll
-      for (int k = 0; k < 8; ++k) qv[k] = qrow[min(v0 + k * nt, V - 1)];
+      for (int k = 0; k < RK; ++k) q[k] = tid + k * nt < V ? qrow[tid + k * nt] : 0.f;
+    } else {
+      for (int v0 = tid; v0 < V; v0 += 8 * nt) {             // 8 independent requests per thread and pass
+        float qv[8];
 #pragma unroll
-      for (int k = 0; k < 8; ++k)
-        if (v0 + k * nt < V) Q[v0 + k * nt] = qv[k];
+        for (int k = 0; k < 8; ++k) qv[k] = qrow[min(v0 + k * nt, V - 1)];
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+          if (v0 + k * nt < V) Q[v0 + k * nt] = qv[k];
+      }
     }
     __syncthreads();
-    const int N = T - 1;
-    for (int c = tree.first_child[j]; c >= 0; c = tree.next_sibling[c]) {
-      const int x = min(max(a.draft[b * N + c - 1] - a.lo, 0), V - 1);
+    const int n_children = sh_nc;
+    for (int ci = 0; ci < n_children; ++ci) {
+      const int c = sh_cn[ci];
+      const int x = sh_cx[ci];
+      const float ua = sh_cu[ci];
+      const int xo = x % nt, xk = x / nt;                    // owner thread and register of id x
       if (a.mode == VVS_RELAXED && a.relax_k > 0) {
         // absorb neighbour mass in ascending distance while the absorbed total stays <= delta
+        if (regs && !p_in_memory) {
+#pragma unroll
+          for (int k = 0; k < RK; ++k)
+            if (tid + k * nt < V) P[tid + k * nt] = p[k];
+          __syncthreads();
+          p_in_memory = true;
+        }
         if (tid < 64) {
           float pm = 0.f;
           int id = -1;
@@ -204,33 +282,85 @@ __global__ __launch_bounds__(1024) void k_accept_node(AcceptArgs a, TreeDesc tre
         __syncthreads();
         if (tid == 0) P[x] = sh_num;
         __syncthreads();
+        if (regs) {
+#pragma unroll
+          for (int k = 0; k < RK; ++k)
+            if (tid + k * nt < V) p[k] = P[tid + k * nt];
+        }
       }
-      const float num = P[x], qx = Q[x];
-      const float ua = a.u[(size_t)b * a.usb + (size_t)c * a.usj + a.uoa];
+      float num, qx;
+      if (regs) {                                            // the owner of id x publishes its target and draft mass
+        if (tid == xo) {
+          float pv = 0.f, qv = 0.f;
+#pragma unroll
+          for (int k = 0; k < RK; ++k)
+            if (k == xk) { pv = p[k]; qv = q[k]; }
+          sh_px = pv;
+          sh_qx = qv;
+        }
+        __syncthreads();
+        num = sh_px;
+        qx = sh_qx;
+      } else {
+        num = P[x];
+        qx = Q[x];
+      }
       if (ua * qx < num) { accepted = c; break; }
       // rejected: target <- normalised positive part of (target - draft); drop x from the draft
-      float z = 0.f;
-      for (int v = tid; v < V; v += nt) z += fmaxf(0.f, P[v] - Q[v]);
-      z = block_sum(z, red);
-      if (z > 0.f)
-        for (int v = tid; v < V; v += nt) P[v] = fmaxf(0.f, P[v] - Q[v]) / z;
-      __syncthreads();
-      if (tid == 0) Q[x] = 0.f;
-      __syncthreads();
-      float zq = 0.f;
-      for (int v = tid; v < V; v += nt) zq += Q[v];
-      zq = block_sum(zq, red);
-      if (!(zq > 0.f)) break;
-      for (int v = tid; v < V; v += nt) Q[v] = Q[v] / zq;
-      __syncthreads();
+      if (regs) {
+        float r[RK];
+        float z = 0.f, zq = 0.f;
+#pragma unroll
+        for (int k = 0; k < RK; ++k) {
+          r[k] = fmaxf(0.f, p[k] - q[k]);
+          if (tid == xo && k == xk) q[k] = 0.f;              // x leaves the draft distribution
+          z += r[k];
+          zq += q[k];
+        }
+        const float2 zz = block_sum2(z, zq, red);
+        if (zz.x > 0.f) {                                    // a residual without mass leaves the target as it is
+          const float inv = 1.0f / zz.x;                       // one division per row instead of one per id: 16 waves share 4 SIMDs
+#pragma unroll
+          for (int k = 0; k < RK; ++k) p[k] = r[k] * inv;
+          p_in_memory = false;
+        }
+        if (!(zz.y > 0.f)) break;
+        const float invq = 1.0f / zz.y;
+#pragma unroll
+        for (int k = 0; k < RK; ++k) q[k] = q[k] * invq;
+      } else {
+        float z = 0.f;
+        for (int v = tid; v < V; v += nt) z += fmaxf(0.f, P[v] - Q[v]);
+        z = block_sum(z, red);
+        if (z > 0.f)
+          for (int v = tid; v < V; v += nt) P[v] = fmaxf(0.f, P[v] - Q[v]) / z;
+        __syncthreads();
+        if (tid == 0) Q[x] = 0.f;
+        __syncthreads();
+        float zq = 0.f;
+        for (int v = tid; v < V; v += nt) zq += Q[v];
+        zq = block_sum(zq, red);
+        if (!(zq > 0.f)) break;
+        for (int v = tid; v < V; v += nt) Q[v] = Q[v] / zq;
+        __syncthreads();
+      }
     }
   }
+  VVS_PHASE_MARK(2);
   if (accepted) {
     if (tid == 0) { res[0] = accepted; res[1] = -1; }
     return;
   }
+  if (regs && !p_in_memory) {                                // the draw addresses ids in ascending order: bring P up to date
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < RK; ++k)
+      if (tid + k * nt < V) P[tid + k * nt] = p[k];
+  }
+  __syncthreads();
   const float ut = a.u[(size_t)b * a.usb + (size_t)j * a.usj + a.uot];
   const int tok = inverse_cdf(P, V, ut, red, ired, scan);
+  VVS_PHASE_MARK(3);
   if (tid == 0) { res[0] = 0; res[1] = a.lo + tok; }
 }
 

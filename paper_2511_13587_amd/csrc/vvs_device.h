@@ -83,6 +83,22 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   for (int i = 0; i < nw; ++i) t += red[i];
   return t;
 }
+// two sums at once (one pair of barriers); red = 32 floats of LDS
+__device__ __forceinline__ float2 block_sum2(float a, float b, float* red) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {       // the two butterfly chains interleaved: their latencies overlap
+    const float ta = __shfl_xor(a, o, 64), tb = __shfl_xor(b, o, 64);
+    a += ta;
+    b += tb;
+  }
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) { red[w] = a; red[16 + w] = b; }
+  __syncthreads();
+  float ta = 0.f, tb = 0.f;
+  for (int i = 0; i < nw; ++i) { ta += red[i]; tb += red[16 + i]; }
+  return make_float2(ta, tb);
+}
 __device__ __forceinline__ float block_max(float v, float* red) {
   v = wave_max(v);
   const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;

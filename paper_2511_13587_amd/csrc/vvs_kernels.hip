@@ -635,7 +635,7 @@ __global__ __launch_bounds__(256) void k_commit_kv(T* __restrict__ kcache, T* __
   T* kb = kcache + l * layer_stride + r * row_stride;
   T* vb = vcache + l * layer_stride + r * row_stride;
   const int n_k = H * dh / CH, n_v = H * dh;
-  for (int item = threadIdx.x; item < n_k + n_v; item += blockDim.x) {
+  for (int item = blockIdx.z * blockDim.x + threadIdx.x; item < n_k + n_v; item += gridDim.z * blockDim.x) {   // one item per thread
     if (item < n_k) {
       const int col = item * CH, hd = col / dh, e = col % dh;
       T* kh = kb + hd * head_stride;
@@ -672,13 +672,22 @@ __global__ __launch_bounds__(256) void k_commit_kv(T* __restrict__ kcache, T* __
   }
 }
 
-__global__ void k_commit_state(int32_t* __restrict__ state, const int32_t* __restrict__ accept_len,
-                               const int32_t* __restrict__ next_token, int B) {
+__global__ void k_commit_state(int32_t* __restrict__ state, int32_t* __restrict__ ring_state, int slots,
+                               const int32_t* __restrict__ accept_len, const int32_t* __restrict__ next_token, int B) {
   int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= B || next_token[b] < 0) return;
-  state[b] += accept_len[b] + 1;           // cached length
-  state[B + b] += accept_len[b] + 1;       // emitted image tokens
+  const int n = accept_len[b] + 1;
+  state[b] += n;                           // cached length
+  state[B + b] += n;                       // emitted image tokens
   state[2 * B + b] = next_token[b];        // pending token
+  if (slots > 0) {                         // the feature rings of both rows took n more entries
+    const int R = 2 * B;
+    for (int r = 2 * b; r < 2 * b + 2; ++r) {
+      const int held = ring_state[r], oldest = ring_state[R + r], now = min(held + n, slots);
+      ring_state[r] = now;
+      ring_state[R + r] = (oldest + held + n - now) % slots;
+    }
+  }
 }
 
 static void launch_push_features(Ctx* c, const int32_t* path, int Tq, int fixed_node, hipStream_t s);
@@ -690,8 +699,9 @@ void launch_commit(Ctx* c, hipStream_t s) {
   const int32_t* accept_len = oc;
   const int32_t* next_token = oc + c->B;
   const int32_t* path = oc + 2 * c->B;
-  dim3 grid(c->R, c->L);
   const bool vec = (c->dh * c->esz) % 16 == 0;
+  const int items = c->H * c->dh / (vec ? 16 / (int)c->esz : 1) + c->H * c->dh;   // K chunks + V elements per (row, layer)
+  dim3 grid(c->R, c->L, (items + 255) / 256);
   if (c->cfg.dtype == VVS_BF16 && vec)
     hipLaunchKernelGGL((k_commit_kv<bf16_t, uint4>), grid, dim3(256), 0, s, (bf16_t*)c->kv, (bf16_t*)c->kv + c->kv_v_off, state, accept_len,
                        next_token, path, c->H, c->dh, c->kv_layer_stride, c->kv_row_stride, c->kv_head_stride, c->S_cap);
@@ -705,17 +715,20 @@ void launch_commit(Ctx* c, hipStream_t s) {
     hipLaunchKernelGGL((k_commit_kv<float, float>), grid, dim3(256), 0, s, (float*)c->kv, (float*)c->kv + c->kv_v_off, state, accept_len,
                        next_token, path, c->H, c->dh, c->kv_layer_stride, c->kv_row_stride, c->kv_head_stride, c->S_cap);
   launch_push_features(c, path, c->last_T, -1, s);
-  hipLaunchKernelGGL(k_commit_state, dim3((c->B + 63) / 64), dim3(64), 0, s, state, accept_len, next_token, c->B);
+  hipLaunchKernelGGL(k_commit_state, dim3((c->B + 63) / 64), dim3(64), 0, s, state, (int32_t*)(c->ws + c->w.ring_state),
+                     c->cfg.feature_slots, accept_len, next_token, c->B);
 }
 
 // ------------------------------------------------------------------------------------------------ token-level feature cache
-// Section 4.3 / Algorithm 2 "UpdateCache".  One workgroup per row appends the features of n tokens of the
-// last forward (rows r * Tq + node of the residual stream x) to the row's ring: a feature is
+// Section 4.3 / Algorithm 2 "UpdateCache".  The features of n tokens of the last forward (rows
+// r * Tq + node of the residual stream x) are appended to the ring of row r: a feature is
 // rmsnorm(x) * gf - the input of the output head - or x itself (pre_norm), stored like an activation
 // of the model.  Ring state per row: (entries held, slot of the oldest); the token appended as the
-// k-th since the oldest goes to slot (oldest + held + k) % slots.
+// k-th since the oldest goes to slot (oldest + held + k) % slots.  One workgroup per (row, appended
+// token); only the last `slots` tokens of a push are written (older ones would be overwritten by it).
 //   path != nullptr: commit - the tokens are path[b][0 .. accept_len[b]] (skipped for finished prompts);
-//   path == nullptr: prefill - the single token fixed_node, into an emptied ring.
+//                    the ring state is advanced afterwards by k_commit_state;
+//   path == nullptr: prefill - the single token fixed_node into an emptied ring (state written here).
 template <typename T>
 __global__ __launch_bounds__(256) void k_push_features(const float* __restrict__ x, const float* __restrict__ gf, T* __restrict__ ring,
                                                        int32_t* __restrict__ ring_state, const int32_t* __restrict__ accept_len,
@@ -730,24 +743,22 @@ __global__ __launch_bounds__(256) void k_push_features(const float* __restrict__
     held = ring_state[r];
     oldest = ring_state[R + r];
   }
-  for (int i = max(0, n - slots); i < n; ++i) {            // older ones would be overwritten by this very push
-    const int node = path ? path[b * VVS_MAX_T + i] : fixed_node;
-    const float* xr = x + ((size_t)r * Tq + node) * d;
-    float scale = 1.f;
-    if (!pre_norm) {
-      float ss = 0.f;
-      for (int k = threadIdx.x; k < d; k += blockDim.x) ss += xr[k] * xr[k];
-      ss = block_sum(ss, red);
-      scale = 1.0f / sqrtf(ss / (float)d + eps);
-    }
-    T* dst = ring + ((size_t)r * slots + (oldest + held + i) % slots) * d;
-    for (int k = threadIdx.x; k < d; k += blockDim.x) st(dst + k, pre_norm ? xr[k] : xr[k] * scale * gf[k]);
+  const int i = max(0, n - slots) + blockIdx.y;
+  if (i >= n) return;
+  const int node = path ? path[b * VVS_MAX_T + i] : fixed_node;
+  const float* xr = x + ((size_t)r * Tq + node) * d;
+  float scale = 1.f;
+  if (!pre_norm) {
+    float ss = 0.f;
+    for (int k = threadIdx.x; k < d; k += blockDim.x) ss += xr[k] * xr[k];
+    ss = block_sum(ss, red);
+    scale = 1.0f / sqrtf(ss / (float)d + eps);
   }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    const int now = min(held + n, slots);
-    ring_state[r] = now;
-    ring_state[R + r] = (oldest + held + n - now) % slots;
+  T* dst = ring + ((size_t)r * slots + (oldest + held + i) % slots) * d;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) st(dst + k, pre_norm ? xr[k] : xr[k] * scale * gf[k]);
+  if (!path && threadIdx.x == 0) {
+    ring_state[r] = 1;
+    ring_state[R + r] = 0;
   }
 }
 
@@ -757,11 +768,12 @@ static void launch_push_features(Ctx* c, const int32_t* path, int Tq, int fixed_
   const float* x = (const float*)(c->ws + c->w.x);
   const float* gf = (const float*)(c->pw + c->p.gf);
   int32_t* rstate = (int32_t*)(c->ws + c->w.ring_state);
+  dim3 grid(c->R, path ? c->cfg.feature_slots : 1);
   if (c->cfg.dtype == VVS_BF16)
-    hipLaunchKernelGGL(k_push_features<bf16_t>, dim3(c->R), dim3(256), 0, s, x, gf, (bf16_t*)(c->ws + c->w.ring), rstate, oc, oc + c->B, path,
+    hipLaunchKernelGGL(k_push_features<bf16_t>, grid, dim3(256), 0, s, x, gf, (bf16_t*)(c->ws + c->w.ring), rstate, oc, oc + c->B, path,
                        Tq, fixed_node, c->R, c->d, c->cfg.feature_slots, c->cfg.feature_pre_norm, c->cfg.rms_eps);
   else
-    hipLaunchKernelGGL(k_push_features<float>, dim3(c->R), dim3(256), 0, s, x, gf, (float*)(c->ws + c->w.ring), rstate, oc, oc + c->B, path,
+    hipLaunchKernelGGL(k_push_features<float>, grid, dim3(256), 0, s, x, gf, (float*)(c->ws + c->w.ring), rstate, oc, oc + c->B, path,
                        Tq, fixed_node, c->R, c->d, c->cfg.feature_slots, c->cfg.feature_pre_norm, c->cfg.rms_eps);
 }
 
