@@ -31,7 +31,7 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_correlated_draft(ctx, vb, synth, shape, parent, torch, noise_std, bufs, n_post=0):
+def build_correlated_draft(ctx, vb, synth, shape, parent, torch, noise_std, bufs, n_post=0, draft_index=0):
     """Synthetic drafter of tunable quality.  Level by level: run a verify pass, read the target's
     mixed logits at the nodes of depth k, let the draft distribution of those nodes be the normalised
     exponential of (target logits + Gaussian noise), and draw their children from it without
@@ -41,10 +41,10 @@ def build_correlated_draft(ctx, vb, synth, shape, parent, torch, noise_std, bufs
     B, N, V = shape.n_prompts, shape.n_nodes, shape.v_eff
     T = N + 1
     depth = synth.node_depths(parent)
-    rng = np.random.default_rng(shape.seed + 99)
+    rng = np.random.default_rng(shape.seed + 99 + 7919 * draft_index)
     q = np.full((B, T, V), 1.0 / V, dtype=np.float32)
     toks = rng.integers(shape.logit_lo, shape.logit_hi, size=(B, N)).astype(np.int32)
-    u = synth.make_uniforms(shape, N, 0)
+    u = synth.make_uniforms(shape, N, draft_index)
     state = bufs["state"]
     children = {}
     for j in range(1, T):
@@ -138,6 +138,9 @@ def main():
                     help="also launch a plain 256 MiB copy kernel (k_copy_bytes) three times, for scaling hardware traffic counters")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (set_state, verify, commit) in a HIP graph and time its replays instead of eager launches")
+    ap.add_argument("--drafts", type=int, default=6,
+                    help="independent synthetic draft sets (tokens, draft distributions, uniforms) cycled through by the steps, so "
+                         "that the accept length behind `value` is a mean over drafts x prompts draws and not one draw")
     ap.add_argument("--post", type=int, default=0,
                     help="post verification: this many unverified tokens of a previous verification-free step ride in front of the "
                          "draft tree (vvs_verify_post); 0 = the plain verify pass of the headline workload")
@@ -195,13 +198,21 @@ def main():
     if args.post:                                   # the draft tree hangs below a chain of unverified tokens
         parent = np.array(list(range(args.post)) + [int(p) + args.post for p in parent], dtype=np.int32)
     mask = synth.ancestor_mask(parent)
-    q, toks, u = build_correlated_draft(ctx, vb, synth, shape, parent, torch, args.draft_noise, bufs, args.post)
-    dq, dtoks, du = torch.from_numpy(q).to(dev), torch.from_numpy(toks).to(dev), torch.from_numpy(u).to(dev)
     N = shape.n_nodes
+    drafts = []
+    for di in range(max(1, args.drafts)):
+        q_i, toks_i, u_i = build_correlated_draft(ctx, vb, synth, shape, parent, torch, args.draft_noise, bufs, args.post, di)
+        drafts.append((torch.from_numpy(q_i).to(dev), torch.from_numpy(toks_i).to(dev), torch.from_numpy(u_i).to(dev)))
+        if di == 0:
+            q, toks, u = q_i, toks_i, u_i                # the CPU baseline replays draft set 0
+    dq, dtoks, du = drafts[0]
+    counter = [0]
 
     def step():
+        dq_, dtoks_, du_ = drafts[counter[0] % len(drafts)]
+        counter[0] += 1
         ctx.vvs_set_state(state)
-        ctx.vvs_verify_post(N, args.post, parent, mask, dtoks, dq, du, mode, bufs["a"], bufs["path"], bufs["next"])
+        ctx.vvs_verify_post(N, args.post, parent, mask, dtoks_, dq_, du_, mode, bufs["a"], bufs["path"], bufs["next"])
         ctx.vvs_kv_commit()
 
     if args.calibrate_copy:
@@ -230,8 +241,15 @@ def main():
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
-    accept = bufs["a"].cpu().numpy()
-    emitted = float(accept.sum() + B)
+    # accept lengths: every draft set replayed once more (the kernels are deterministic), outside the timed region
+    n_sets = 1 if args.graph else len(drafts)               # a captured graph replays draft set 0 only
+    counter[0] = 0
+    accepts = []
+    for _ in range(n_sets):
+        step()
+        accepts.append(bufs["a"].cpu().numpy().copy())
+    accept = np.concatenate(accepts)
+    emitted = float(accept.sum() + len(accept)) / n_sets    # mean emitted tokens per step
     value = emitted / (ms_per_step * 1e-3)
 
     # per-kernel-class durations from HIP events recorded by the library on this stream
@@ -285,7 +303,8 @@ def main():
         "config": {"workload": shape.name, "layers": shape.n_layers, "d_model": shape.d_model, "prompts": B,
                    "rows": shape.n_rows, "draft_nodes": N, "tree_depth": int(synth.node_depths(parent).max()),
                    "cache_len_mean": S_mean, "mode": args.mode, "draft_noise_std": args.draft_noise,
-                   "launch": "hip graph replay" if args.graph else "eager", "post_verified_tokens": args.post},
+                   "launch": "hip graph replay" if args.graph else "eager", "post_verified_tokens": args.post,
+                   "draft_sets": n_sets},
         "verify_latency_ms": ms_per_step, "mean_accept_len": float(accept.mean()),
         "emitted_tokens_per_step": emitted, "scored_draft_tokens_per_s": B * N / (ms_per_step * 1e-3),
         "whole_pass": {"algorithmic_GB": total_bytes / 1e9, "algorithmic_TFLOP": (cnt["gemm_flops"] + cnt["attn_flops"]) / 1e12,

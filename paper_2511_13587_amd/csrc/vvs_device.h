@@ -5,11 +5,13 @@
 namespace vvs {
 
 __device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
-// round to nearest, ties to even (inputs here are finite)
-__device__ __forceinline__ bf16_t f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
+// round to nearest, ties to even: the hardware conversion of gfx950 (v_cvt_pk_bf16_f32)
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float floatx2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ bf16_t f2bf(float f) { return __builtin_bit_cast(bf16_t, (__bf16)f); }
+// two values in one instruction: lo in bits 0..15, hi in bits 16..31
+__device__ __forceinline__ uint32_t pack2bf(float lo, float hi) {
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(floatx2_t{lo, hi}, bf16x2_t));
 }
 __device__ __forceinline__ float ld(const float* p) { return *p; }
 __device__ __forceinline__ float ld(const bf16_t* p) { return bf2f(*p); }
@@ -52,10 +54,10 @@ __device__ __forceinline__ void store8(float* base, int row, int k0, int K, cons
 }
 __device__ __forceinline__ void store8(bf16_t* base, int row, int k0, int K, const float* v) {
   uint4 o;
-  o.x = (uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16);
-  o.y = (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16);
-  o.z = (uint32_t)f2bf(v[4]) | ((uint32_t)f2bf(v[5]) << 16);
-  o.w = (uint32_t)f2bf(v[6]) | ((uint32_t)f2bf(v[7]) << 16);
+  o.x = pack2bf(v[0], v[1]);
+  o.y = pack2bf(v[2], v[3]);
+  o.z = pack2bf(v[4], v[5]);
+  o.w = pack2bf(v[6], v[7]);
   *(uint4*)(base + pack_index(row, k0, K)) = o;
 }
 

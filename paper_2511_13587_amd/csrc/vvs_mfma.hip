@@ -226,7 +226,8 @@ __device__ __forceinline__ void tile_epilogue(const float* red, const float* rs,
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const float g = gs[i] * rs[row], up = us[i] * rs[row];
-        v[i] = g / (1.0f + expf(-g)) * up;
+        // silu(g) * up with the hardware exp2 and reciprocal (1 ulp each): the epilogue is VALU work of a single wave per SIMD
+        v[i] = g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g)) * up;
       }
       store8(ep.act, m0 + row, tile_n * (BN / 2) + fl, ep.F, v);
     }
@@ -255,6 +256,9 @@ __device__ __forceinline__ void tile_epilogue(const float* red, const float* rs,
     }
   } else {
     const int sec = n0 / ep.d;                                     // the tile lies inside the q (0), k (1) or v (2) third
+    // index arithmetic without per-thread integer divisions: the tile's first column inside its third is
+    // uniform, and the head size of this path is a power of two (64 or 128)
+    const int nd = n0 - sec * ep.d, dh_sh = 31 - __clz(ep.dh), dh_mask = ep.dh - 1;
     if (sec == 0) {
       const int half = ep.dh >> 1, np = ep.dh >> 2;
       for (int u = threadIdx.x; u < BM * (BN / 16); u += 256) {    // q: one unit = (row, 16 consecutive columns), row-major output
@@ -266,13 +270,13 @@ __device__ __forceinline__ void tile_epilogue(const float* red, const float* rs,
         float v[16] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w, s2.x, s2.y, s2.z, s2.w, s3.x, s3.y, s3.z, s3.w};
 #pragma unroll
         for (int i = 0; i < 16; ++i) v[i] *= rs[row];
-        const int eg = (n0 + c0) % ep.d, e = eg % ep.dh;
+        const int eg = nd + c0, e = eg & dh_mask;
         const int img = s_pos[2 * row + 1];
         if (img >= 0) {
           float2 cs[8];
           if (np == kRopeNpMax) {
             // 16 columns = 8 pairs inside one half of the head: 8 consecutive pairs of the row's LDS table
-            const float4* t4 = (const float4*)(s_rope + row * 2 * kRopeNpMax + (e / half) * np + ((e % half) >> 1));
+            const float4* t4 = (const float4*)(s_rope + row * 2 * kRopeNpMax + (e >> (dh_sh - 1)) * np + ((e & (half - 1)) >> 1));
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
               const float4 c4 = t4[i];
@@ -283,7 +287,7 @@ __device__ __forceinline__ void tile_epilogue(const float* red, const float* rs,
             const int gr = min(img / ep.pos.grid_w, ep.rope_pos - 1), gc = img % ep.pos.grid_w;
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-              const int ei = e + 2 * i, pv = (ei / half) ? gc : gr, ip = (ei % half) >> 1;
+              const int ei = e + 2 * i, pv = (ei >> (dh_sh - 1)) ? gc : gr, ip = (ei & (half - 1)) >> 1;
               cs[i] = *(const float2*)(ep.rope + ((size_t)pv * np + ip) * 2);
             }
           }
@@ -295,10 +299,10 @@ __device__ __forceinline__ void tile_epilogue(const float* red, const float* rs,
           }
         }
         uint4* dst = (uint4*)(ep.q + (size_t)m * ep.d + eg);
-        dst[0] = make_uint4((uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16), (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16),
-                            (uint32_t)f2bf(v[4]) | ((uint32_t)f2bf(v[5]) << 16), (uint32_t)f2bf(v[6]) | ((uint32_t)f2bf(v[7]) << 16));
-        dst[1] = make_uint4((uint32_t)f2bf(v[8]) | ((uint32_t)f2bf(v[9]) << 16), (uint32_t)f2bf(v[10]) | ((uint32_t)f2bf(v[11]) << 16),
-                            (uint32_t)f2bf(v[12]) | ((uint32_t)f2bf(v[13]) << 16), (uint32_t)f2bf(v[14]) | ((uint32_t)f2bf(v[15]) << 16));
+        dst[0] = make_uint4(pack2bf(v[0], v[1]), pack2bf(v[2], v[3]),
+                            pack2bf(v[4], v[5]), pack2bf(v[6], v[7]));
+        dst[1] = make_uint4(pack2bf(v[8], v[9]), pack2bf(v[10], v[11]),
+                            pack2bf(v[12], v[13]), pack2bf(v[14], v[15]));
       }
     } else if (sec == 1) {
       // k: in the cache's operand order 4 consecutive slots of one 8-dim piece are contiguous, so a lane
@@ -316,18 +320,18 @@ __device__ __forceinline__ void tile_epilogue(const float* red, const float* rs,
         for (int c8 = g4 * 8; c8 < BN; c8 += G * 8) {
           const float4 a = sum4(red + row * LDC + c8), b = sum4(red + row * LDC + c8 + 4);
           float v[8] = {a.x * sc, a.y * sc, a.z * sc, a.w * sc, b.x * sc, b.y * sc, b.z * sc, b.w * sc};
-          const int eg = (n0 + c8) % ep.d, hd = eg / ep.dh, e = eg % ep.dh;
+          const int eg = nd + c8, hd = eg >> dh_sh, e = eg & dh_mask;
           if (img >= 0) {
             float2 cs[4];
             if (np == kRopeNpMax) {
-              const float4* t4 = (const float4*)(s_rope + row * 2 * kRopeNpMax + (e / half) * np + ((e % half) >> 1));
+              const float4* t4 = (const float4*)(s_rope + row * 2 * kRopeNpMax + (e >> (dh_sh - 1)) * np + ((e & (half - 1)) >> 1));
               const float4 c0 = t4[0], c1 = t4[1];
               cs[0] = make_float2(c0.x, c0.y); cs[1] = make_float2(c0.z, c0.w);
               cs[2] = make_float2(c1.x, c1.y); cs[3] = make_float2(c1.z, c1.w);
             } else {
 #pragma unroll
               for (int i = 0; i < 4; ++i) {
-                const int ei = e + 2 * i, pv = (ei / half) ? gc : gr, ip = (ei % half) >> 1;
+                const int ei = e + 2 * i, pv = (ei >> (dh_sh - 1)) ? gc : gr, ip = (ei & (half - 1)) >> 1;
                 cs[i] = *(const float2*)(ep.rope + ((size_t)pv * np + ip) * 2);
               }
             }
@@ -339,8 +343,8 @@ __device__ __forceinline__ void tile_epilogue(const float* red, const float* rs,
             }
           }
           *(uint4*)(krow + (size_t)hd * ep.head_stride + k_index(slot, e, ep.dh)) =
-              make_uint4((uint32_t)f2bf(v[0]) | ((uint32_t)f2bf(v[1]) << 16), (uint32_t)f2bf(v[2]) | ((uint32_t)f2bf(v[3]) << 16),
-                         (uint32_t)f2bf(v[4]) | ((uint32_t)f2bf(v[5]) << 16), (uint32_t)f2bf(v[6]) | ((uint32_t)f2bf(v[7]) << 16));
+              make_uint4(pack2bf(v[0], v[1]), pack2bf(v[2], v[3]),
+                         pack2bf(v[4], v[5]), pack2bf(v[6], v[7]));
         }
       }
     } else {
@@ -356,7 +360,7 @@ __device__ __forceinline__ void tile_epilogue(const float* red, const float* rs,
 #pragma unroll 4
         for (int c4 = g * 4; c4 < BN; c4 += G * 4) {
           const float4 v = sum4(red + row * LDC + c4);
-          const int eg = (n0 + c4) % ep.d, hd = eg / ep.dh, e = eg % ep.dh;   // 4 columns stay inside one head (head size % 4 == 0)
+          const int eg = nd + c4, hd = eg >> dh_sh, e = eg & dh_mask;    // 4 columns stay inside one head
           bf16_t* vh = vrow + (size_t)hd * ep.head_stride;
           vh[v_index(slot, e, ep.dh)] = f2bf(v.x * sc);
           vh[v_index(slot, e + 1, ep.dh)] = f2bf(v.y * sc);
@@ -805,15 +809,15 @@ __global__ __launch_bounds__(NW * 64, (DH * NQB >= 256 ? 1 : 2)) void k_attn_mfm
           mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
           const float m_new = fmaxf(m_run[qb], mx);
           const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-          const float alpha = exp2f((m_run[qb] - m_safe) * c_exp);
+          const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_safe) * c_exp);
           uint32_t pk[4];
           float rs = 0.f;
 #pragma unroll
           for (int i = 0; i < 8; i += 2) {
-            const bf16_t p0 = f2bf(exp2f((sv[i] - m_safe) * c_exp));
-            const bf16_t p1 = f2bf(exp2f((sv[i + 1] - m_safe) * c_exp));
-            rs += bf2f(p0) + bf2f(p1);
-            pk[i >> 1] = (uint32_t)p0 | ((uint32_t)p1 << 16);
+            // hardware exp2 (arguments <= 0; results below the normal range are 0 either way after the bf16 rounding)
+            const uint32_t pp = pack2bf(__builtin_amdgcn_exp2f((sv[i] - m_safe) * c_exp), __builtin_amdgcn_exp2f((sv[i + 1] - m_safe) * c_exp));
+            rs += __uint_as_float(pp << 16) + __uint_as_float(pp & 0xFFFF0000u);
+            pk[i >> 1] = pp;
           }
           rs += __shfl_xor(rs, 16, 64);
           rs += __shfl_xor(rs, 32, 64);
@@ -878,7 +882,7 @@ __global__ __launch_bounds__(NW * 64, (DH * NQB >= 256 ? 1 : 2)) void k_attn_mfm
               v0 += s_o[w][qi][dt * 16 + 4 * g + rr] * aw[w];
               v1 += s_o[w][qi][dt * 16 + 4 * g + rr + 1] * aw[w];
             }
-            pk[rr >> 1] = (uint32_t)f2bf(v0 * inv) | ((uint32_t)f2bf(v1 * inv) << 16);
+            pk[rr >> 1] = pack2bf(v0 * inv, v1 * inv);
           }
           *(uint2*)(out + pack_index(r * T + qi, hd * DH + dt * 16 + 4 * g, d)) = make_uint2(pk[0], pk[1]);   // O-projection operand layout
         }
