@@ -412,14 +412,7 @@ void launch_accept(Ctx* c, const TreeDesc& tree, int T, const float* d_logits, c
   a.scale = c->cfg.cfg_scale; a.delta = c->cfg.relax_delta;
   const size_t pq_bytes = (size_t)2 * c->veff * sizeof(float);
   if (pq_bytes <= kAcceptLdsMax) {
-    // more than 64 KiB of dynamic LDS has to be asked for once per device
-    static bool raised[64] = {};
-    int dev = 0;
-    (void)hipGetDevice(&dev);
-    if (pq_bytes > 64 * 1024 && dev >= 0 && dev < 64 && !raised[dev]) {
-      (void)hipFuncSetAttribute((const void*)k_accept_node<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAcceptLdsMax);
-      raised[dev] = true;
-    }
+    if (pq_bytes > 64 * 1024) allow_dynamic_lds((const void*)k_accept_node<true>, kAcceptLdsMax);
     hipLaunchKernelGGL(k_accept_node<true>, dim3(T, c->B), dim3(1024), pq_bytes, s, a, tree);
   } else {
     hipLaunchKernelGGL(k_accept_node<false>, dim3(T, c->B), dim3(1024), 0, s, a, tree);

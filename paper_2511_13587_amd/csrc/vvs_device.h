@@ -146,6 +146,20 @@ __device__ __forceinline__ void token_pos(const PosDesc& pos, const TreeDesc& tr
   }
 }
 
+// A kernel that uses more than 64 KiB of dynamic LDS has to be allowed to, once per device: remembers per
+// (kernel, device) that it has been done.  Host code; launches of one context come from one thread at a time.
+inline void allow_dynamic_lds(const void* kernel, size_t bytes) {
+  struct Done { const void* fn; int dev; };
+  static std::vector<Done> done;
+  int dev = 0;
+  (void)hipGetDevice(&dev);
+  for (const Done& d : done)
+    if (d.fn == kernel && d.dev == dev) return;
+  // a failure shows up as an invalid-configuration error of the launch that follows
+  (void)hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  done.push_back(Done{kernel, dev});
+}
+
 // MFMA attention / GEMM launchers (vvs_mfma.hip)
 void mfma_gemm(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, GemmPlan p, hipStream_t s);
 void mfma_gemm_scaled(Ctx* c, const bf16_t* A, const bf16_t* W, float* C, const float* ss, int M, int N, int K, GemmPlan p, hipStream_t s);

@@ -615,12 +615,7 @@ static void launch_gemm_shared(const bf16_t* A, const bf16_t* W, float* C, int M
   constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32;
   constexpr size_t lds_tile = (size_t)BM * (BN + 4) * sizeof(float), lds_stage = (size_t)3 * (2 * (BM + BN) / 32) * 1024;
   constexpr size_t lds = lds_tile > lds_stage ? lds_tile : lds_stage;
-  static bool configured = false;
-  if (!configured) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_shared<WM, WN, D, EPI>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)lds);
-    configured = true;
-  }
+  allow_dynamic_lds(reinterpret_cast<const void*>(&k_gemm_shared<WM, WN, D, EPI>), lds);
   dim3 grid((N / BN) * ((M + BM - 1) / BM), 1, 1);
   hipLaunchKernelGGL((k_gemm_shared<WM, WN, D, EPI>), grid, dim3(256), lds, s, (const uint4*)A, (const uint4*)W, C, M, N, K, ep);
 }
@@ -629,12 +624,7 @@ template <int TM, int TN, int D, int EPI>
 static void launch_gemm_direct(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, int splits, const GemmEpi& ep,
                                hipStream_t s) {
   constexpr size_t lds = (size_t)4 * TM * 32 * (TN * 32 + 4) * sizeof(float);
-  static bool configured = false;
-  if (!configured) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_direct<TM, TN, D, EPI>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                              (int)lds);
-    configured = true;
-  }
+  allow_dynamic_lds(reinterpret_cast<const void*>(&k_gemm_direct<TM, TN, D, EPI>), lds);
   const int KB = K / 16;
   const int per = (KB + splits - 1) / splits;
   dim3 grid((N / (TN * 32)) * ((M + TM * 32 - 1) / (TM * 32)), 1, splits);
