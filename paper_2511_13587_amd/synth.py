@@ -148,6 +148,29 @@ def make_weights(shape: Shape, std: float = 0.02, gain_jitter: float = 0.0) -> D
     return out
 
 
+def make_drafter_weights(shape: Shape, target_weights: Dict[str, np.ndarray], std: float = 0.02,
+                         gain_jitter: float = 0.0, seed_offset: int = 104729) -> Dict[str, np.ndarray]:
+    """Random-init weights of a one-block drafter for `shape`: its own block (l0.*), final gain gf and
+    input map fc [2 d, d]; the token embedding table, class table and output head are the target's
+    (the same arrays).  float32, bf16-representable for bf16 shapes."""
+    one = shape.replace(n_layers=1, seed=shape.seed + seed_offset)
+    own = make_weights(one, std=std, gain_jitter=gain_jitter)
+    out = {k: v for k, v in own.items() if k.startswith("l0.") or k == "gf"}
+    for k in ("embed", "prefix_embed", "wout"):
+        out[k] = target_weights[k]
+    rng = np.random.default_rng(one.seed + 17)
+    fc = rng.standard_normal((2 * shape.d_model, shape.d_model), dtype=np.float32) * np.float32(std * 8)
+    if shape.dtype == DTYPE_BF16:
+        fc = bf16_bits_to_f32(f32_to_bf16_bits(fc))
+    out["fc"] = fc
+    return out
+
+
+def drafter_weight_names() -> List[str]:
+    """Canonical tensor order of a drafter context: the one-layer list followed by fc."""
+    return ["embed", "prefix_embed"] + [f"l0.{k}" for k in ("g1", "wq", "wk", "wv", "wo", "g2", "wg", "wu", "wd")] + ["gf", "wout", "fc"]
+
+
 # ----------------------------------------------------------------------------- prefixes
 def make_prefix(shape: Shape, seed_offset: int = 0):
     """Returns (cond, uncond).
