@@ -75,6 +75,10 @@ typedef struct {
                                     0 .. VVS_MAX_FEATURE_SLOTS (0 = none; the paper keeps 5) */
   int32_t feature_pre_norm;      /* 0: a feature is the input of the output head (after the final
                                     norm); 1: the residual stream in front of the final norm */
+  int32_t draft_input;           /* 0: a target model (token embeddings are the inputs);
+                                    1: a drafter context for vvs_draft: the input of a token is
+                                    W_fc [embedding ; feature], and the weight list ends with one
+                                    more tensor fc [2 d, d] */
 } vvs_config;
 #define VVS_MAX_FEATURE_SLOTS 8
 
@@ -90,10 +94,12 @@ vvs_status vvs_create(const vvs_config* cfg, void* d_kv, void* d_workspace, void
 void vvs_destroy(vvs_ctx* ctx);
 const char* vvs_last_error(const vvs_ctx* ctx);   /* ctx may be NULL: error of the last failed create/query */
 
-/* Number of canonical weight tensors (2 + 9 * n_layers + 2) in this order:
+/* Number of canonical weight tensors (2 + 9 * n_layers + 2, one more for a drafter context) in
+ * this order:
  *   embed [vocab, d]; prefix_embed [n_classes + 1, d] (may be NULL for dense prefixes);
  *   per layer: g1 [d], wq [d,d], wk [d,d], wv [d,d], wo [d,d], g2 [d], wg [d,F], wu [d,F], wd [F,d];
- *   gf [d]; wout [d, vocab].
+ *   gf [d]; wout [d, vocab]; drafter contexts only: fc [2d, d] (rows 0..d-1 multiply the token
+ *   embedding, rows d..2d-1 the feature).
  * Matrices are row-major [in, out] (activations multiply from the left); element type = dtype. */
 int32_t vvs_num_weight_tensors(const vvs_config* cfg);
 
@@ -223,6 +229,37 @@ vvs_status vvs_path_similarity(vvs_ctx* ctx, int32_t n_nodes, const int32_t* h_p
                                const int32_t* d_draft_tokens, float alpha, int32_t stride, float* d_similarity,
                                vvs_stream s);
 
+/* One drafting call (Algorithm 2: "f_t <- Retrieve(C, a); C_t <- M_D(f_t, a)"; Section 3, "Stale
+ * Feature Reusability"; Section 4.1): the drafter - a context created with draft_input = 1, one or more
+ * decoder blocks of the target's kind, the same d_model, dtype, B, id slice and grid as the target -
+ * is conditioned on the n_ctx most recent features of the target's token-level feature cache paired,
+ * by recency, with the n_ctx most recent tokens of the sequence, and fills a candidate tree of a fixed
+ * shape level by level: node j >= 1 gets the input W_fc [embedding of its token ; feature the drafter
+ * produced at its parent]; the distribution at a node is the softmax of the drafter's CFG-mixed logits
+ * (the drafter context's cfg_scale); the c-th child of a node (ascending node id) carries the id with
+ * the c-th largest mixed logit there, ties to the lower id.  The drafter keeps no state between calls:
+ * a node attends to the n_ctx pairs, its ancestors and itself.  Pair i sits at image index
+ * first + i with first = max(0, root - (n_ctx - 1)), root = emitted tokens of the target - 1 +
+ * n_unverified; node j at first + n_ctx - 1 + depth(j).
+ *   n_nodes, h_parent, h_tree_mask: the tree shape, as for vvs_verify (n_nodes >= 1)
+ *   n_ctx          : 1 .. feature_slots of the target; every row of the target should hold that many
+ *                    features (a missing feature is read as zeros); n_ctx + (number of nodes that have
+ *                    children, root excluded) <= max_nodes + 1 of the drafter context
+ *   d_recent_tokens: int32 [B, n_ctx] full-vocabulary ids, oldest first; the last one is the root (the
+ *                    target's pending token, or the last token accepted without verification)
+ *   n_unverified   : tokens accepted without verification since the target's last commit, 0 .. 8
+ *                    (they move the root's position; their features do not exist: the cached ones
+ *                    are paired with newer tokens - stale features)
+ *   d_given_tokens : NULL, or int32 [B, N]: the nodes' tokens are taken from here (e.g. sampled by the
+ *                    caller) and only the distributions are computed
+ *   d_draft_tokens : int32 [B, N] out;  d_draft_probs: float [B, T, V_eff] out, row j = distribution of
+ *                    the children of node j (zeros for a leaf): the layouts vvs_verify takes.
+ * The target's state and feature cache are only read.  Same stream rules as every other call. */
+vvs_status vvs_draft(vvs_ctx* drafter, vvs_ctx* target, int32_t n_nodes, const int32_t* h_parent,
+                     const uint8_t* h_tree_mask, int32_t n_ctx, const int32_t* d_recent_tokens,
+                     int32_t n_unverified, const int32_t* d_given_tokens, int32_t* d_draft_tokens,
+                     float* d_draft_probs, vvs_stream s);
+
 /* Per-prompt state: int32 [3, B] out = cached length S_b, emitted image tokens, pending token. */
 vvs_status vvs_read_state(vvs_ctx* ctx, int32_t* d_state, vvs_stream s);
 
@@ -240,7 +277,9 @@ enum { VVS_K_GEMM = 0, VVS_K_ATTENTION = 1, VVS_K_ACCEPT = 2, VVS_K_ELEMENTWISE 
 vvs_status vvs_timing_enable(vvs_ctx* ctx, int32_t on);
 vvs_status vvs_timing_read(vvs_ctx* ctx, int32_t kernel_class, int32_t* n_launches, float* total_ms);
 
-/* Inspection of the last verify (or prefill, with T = 1): any pointer may be NULL.
+/* Inspection of the last verify (or prefill, with T = 1; for a drafter context: the last level of the
+ * last vvs_draft, T = its block tokens: the n_ctx pairs, then the nodes that have children ordered by
+ * depth, then id): any pointer may be NULL.
  *   d_raw_logits float [R, T, V_eff]; d_mixed_logits float [B, T, V_eff]; d_probs float [B, T, V_eff]. */
 vvs_status vvs_debug_logits(vvs_ctx* ctx, float* d_raw_logits, float* d_mixed_logits, float* d_probs,
                             vvs_stream s);

@@ -28,7 +28,7 @@ class VvsConfig(C.Structure):
                                          "max_nodes", "dtype")] + \
                [("cfg_scale", C.c_float), ("rms_eps", C.c_float), ("rope_base", C.c_float),
                 ("relax_k", C.c_int32), ("relax_delta", C.c_float),
-                ("feature_slots", C.c_int32), ("feature_pre_norm", C.c_int32)]
+                ("feature_slots", C.c_int32), ("feature_pre_norm", C.c_int32), ("draft_input", C.c_int32)]
 
 
 class VvsError(RuntimeError):
@@ -61,6 +61,7 @@ def _load():
         "vvs_skip_dynamic": (i32, [C.c_float, C.c_float, i32]),
         "vvs_set_codebook": (i32, [vp, vp, i32]),
         "vvs_path_similarity": (i32, [vp, i32, vp, vp, vp, C.c_float, i32, vp, vp]),
+        "vvs_draft": (i32, [vp, vp, i32, vp, vp, i32, vp, i32, vp, vp, vp, vp]),
         "vvs_accept_from_logits": (i32, [vp, i32, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]),
         "vvs_kv_commit": (i32, [vp, vp]),
         "vvs_read_state": (i32, [vp, vp, vp]),
@@ -82,13 +83,14 @@ def _load():
 lib, EXPORTS = _load()
 
 
-def make_config(shape, max_nodes: Optional[int] = None, feature_slots: int = 5, feature_pre_norm: int = 0) -> VvsConfig:
+def make_config(shape, max_nodes: Optional[int] = None, feature_slots: int = 5, feature_pre_norm: int = 0,
+                draft_input: int = 0) -> VvsConfig:
     """vvs_config from a synth.Shape-like object."""
     return VvsConfig(shape.n_layers, shape.d_model, shape.n_heads, shape.d_ff, shape.vocab, shape.logit_lo,
                      shape.logit_hi, shape.grid_h, shape.grid_w, shape.prefix_len, shape.prefix_kind,
                      shape.n_classes, shape.n_prompts, shape.n_nodes if max_nodes is None else max_nodes,
                      shape.dtype, shape.cfg_scale, shape.rms_eps, shape.rope_base, shape.relax_k, shape.relax_delta,
-                     feature_slots, feature_pre_norm)
+                     feature_slots, feature_pre_norm, draft_input)
 
 
 def vvs_query_sizes(cfg: VvsConfig):
@@ -256,6 +258,18 @@ class Context:
         count = torch.empty((self.B,), dtype=torch.int32, device=self.device)
         self._check(lib.vvs_read_features(self.h, _ptr(feats), _ptr(count), _stream()))
         return feats.cpu().numpy(), count.cpu().numpy()
+
+    def vvs_draft(self, target: "Context", n_nodes: int, parent, tree_mask, n_ctx: int, recent_tokens: torch.Tensor,
+                  n_unverified: int, given_tokens: Optional[torch.Tensor], draft_tokens: torch.Tensor, draft_probs: torch.Tensor):
+        """self is the drafter context (draft_input = 1)."""
+        p = None if parent is None else np.ascontiguousarray(parent, dtype=np.int32)
+        m = None if tree_mask is None else np.ascontiguousarray(tree_mask, dtype=np.uint8)
+        assert recent_tokens.dtype == torch.int32 and draft_tokens.dtype == torch.int32 and draft_probs.dtype == torch.float32
+        self._check(lib.vvs_draft(self.h, target.h, n_nodes, None if p is None else p.ctypes.data,
+                                  None if m is None else m.ctypes.data, n_ctx, _ptr(recent_tokens), n_unverified,
+                                  _ptr(given_tokens), _ptr(draft_tokens), _ptr(draft_probs), _stream()))
+        internal = 0 if p is None else len(set(int(v) for v in p if v > 0))
+        self.last_T = n_ctx + (n_nodes - 1 if p is None else internal)
 
     def vvs_accept_from_logits(self, n_nodes: int, parent, tree_mask, raw_logits: torch.Tensor, draft_tokens, draft_probs,
                                uniforms, mode, accept_len, path, next_token):

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libvvs.so")
-SOURCES = ["vvs_host.cpp", "vvs_kernels.hip", "vvs_accept.hip", "vvs_mfma.hip", "vvs_schedule.hip"]
+SOURCES = ["vvs_host.cpp", "vvs_kernels.hip", "vvs_accept.hip", "vvs_mfma.hip", "vvs_schedule.hip", "vvs_draft.hip"]
 
 
 def build(verbose: bool = True) -> str:

@@ -68,6 +68,7 @@ vvs_status plan_sizes(const vvs_config* cfg, Ctx* c, std::string* err) {
   if (g.feature_slots < 0 || g.feature_slots > VVS_MAX_FEATURE_SLOTS)
     return fail(err, VVS_ESIZE, "config: feature_slots must be in [0, VVS_MAX_FEATURE_SLOTS]");
   if (g.feature_pre_norm != 0 && g.feature_pre_norm != 1) return fail(err, VVS_EINVAL, "config: feature_pre_norm must be 0 or 1");
+  if (g.draft_input != 0 && g.draft_input != 1) return fail(err, VVS_EINVAL, "config: draft_input must be 0 or 1");
   int dh = g.d_model / g.n_heads;
   if (dh % 4) return fail(err, VVS_ESIZE, "config: head size must be a multiple of 4 (2D rotary pairs)");
   if (g.d_model % 8 || g.d_ff % 8) return fail(err, VVS_ESIZE, "config: d_model and d_ff must be multiples of 8");
@@ -98,9 +99,10 @@ vvs_status plan_sizes(const vvs_config* cfg, Ctx* c, std::string* err) {
   // GEMM partial-sum buffer: worst case over every M this context can be asked for
   size_t go = 0;
   int d = c->d, F = c->F;
-  const int shapes[4][2] = {{3 * d, d}, {d, d}, {2 * F, d}, {d, F}};
+  const int shapes[5][2] = {{3 * d, d}, {d, d}, {2 * F, d}, {d, F}, {d, 2 * d}};   // the last one: a drafter's input map
   for (int M = 1; M <= c->Mmax; ++M)
     for (auto& sh : shapes) {
+      if (sh[1] == 2 * d && !g.draft_input) continue;
       GemmPlan p = plan_gemm(c, M, sh[0], sh[1]);
       go = std::max(go, (size_t)p.splits * M * sh[0]);
     }
@@ -128,6 +130,7 @@ vvs_status plan_sizes(const vvs_config* cfg, Ctx* c, std::string* err) {
   w.ss = take(sizeof(float) * (size_t)c->Mmax * (((d + 63) / 64 + 3) & ~3));     // per-row, per-64-column sums of squares of the residual
   w.ss2 = take(sizeof(float) * (size_t)c->Mlog * (((d + 63) / 64 + 3) & ~3));
   w.ring = take(c->esz * (size_t)c->R * std::max(g.feature_slots, 1) * d);
+  w.din = take(g.draft_input ? c->esz * (size_t)c->Mmax * 2 * d : 0);                // drafter: [embedding ; feature] rows
   w.total = off;
   // packed weights
   PackedLayout& p = c->p;
@@ -146,7 +149,9 @@ vvs_status plan_sizes(const vvs_config* cfg, Ctx* c, std::string* err) {
   p.wgu = take(e * (size_t)2 * F * d) - base;
   p.wd = take(e * (size_t)d * F) - base;
   p.layer_stride = off - base;
-  p.total = p.layer0 + p.layer_stride * c->L;
+  off = p.layer0 + p.layer_stride * c->L;
+  p.fc = take(g.draft_input ? e * (size_t)2 * d * d : 0);
+  p.total = off;
   return VVS_OK;
 }
 
@@ -239,7 +244,7 @@ vvs_status vvs_query_sizes(const vvs_config* cfg, size_t* kv_bytes, size_t* work
   return VVS_OK;
 }
 
-int32_t vvs_num_weight_tensors(const vvs_config* cfg) { return cfg ? 4 + 9 * cfg->n_layers : 0; }
+int32_t vvs_num_weight_tensors(const vvs_config* cfg) { return cfg ? 4 + 9 * cfg->n_layers + (cfg->draft_input ? 1 : 0) : 0; }
 
 vvs_status vvs_check_tree(int32_t n_nodes, const int32_t* h_parent, const uint8_t* h_tree_mask, int32_t* h_depth,
                           int32_t* h_parent_out) {
@@ -370,6 +375,7 @@ vvs_status vvs_prefill(vvs_ctx* ctx, const void* d_prefix_cond, const void* d_pr
                        const int32_t* d_forced_tokens, const float* d_uniform, int32_t* d_first_token, vvs_stream s) {
   Ctx* c = reinterpret_cast<Ctx*>(ctx);
   if (!c) return VVS_EINVAL;
+  if (c->cfg.draft_input) return fail(&c->err, VVS_EINVAL, "prefill: this is a drafter context (use vvs_draft)");
   if (!c->weights_loaded) return fail(&c->err, VVS_ESTATE, "prefill: weights not loaded");
   if (!d_prefix_cond || !d_uniform || !d_first_token) return fail(&c->err, VVS_EINVAL, "prefill: NULL argument");
   if (c->cfg.prefix_kind == VVS_PREFIX_DENSE && !d_prefix_uncond)
@@ -558,6 +564,83 @@ vvs_status vvs_read_features(vvs_ctx* ctx, float* d_features, int32_t* d_count, 
   if (!c->prefilled) return fail(&c->err, VVS_ESTATE, "read_features: call vvs_prefill first");
   launch_read_features(c, d_features, d_count, (hipStream_t)s);
   return check_launch(c, "read_features");
+}
+
+vvs_status vvs_draft(vvs_ctx* drafter, vvs_ctx* target, int32_t n_nodes, const int32_t* h_parent, const uint8_t* h_tree_mask,
+                     int32_t n_ctx, const int32_t* d_recent_tokens, int32_t n_unverified, const int32_t* d_given_tokens,
+                     int32_t* d_draft_tokens, float* d_draft_probs, vvs_stream s) {
+  Ctx* dr = reinterpret_cast<Ctx*>(drafter);
+  Ctx* tg = reinterpret_cast<Ctx*>(target);
+  if (!dr) return VVS_EINVAL;
+  if (!tg) return fail(&dr->err, VVS_EINVAL, "draft: target context is NULL");
+  if (!dr->cfg.draft_input) return fail(&dr->err, VVS_EINVAL, "draft: the first context was not created with draft_input = 1");
+  if (tg->cfg.draft_input) return fail(&dr->err, VVS_EINVAL, "draft: the target is a drafter context");
+  if (!dr->weights_loaded) return fail(&dr->err, VVS_ESTATE, "draft: drafter weights not loaded");
+  if (!tg->prefilled) return fail(&dr->err, VVS_ESTATE, "draft: call vvs_prefill on the target first");
+  const vvs_config &a = dr->cfg, &b = tg->cfg;
+  if (a.d_model != b.d_model || a.dtype != b.dtype || a.n_prompts != b.n_prompts || a.vocab != b.vocab || a.logit_lo != b.logit_lo ||
+      a.logit_hi != b.logit_hi || a.grid_h != b.grid_h || a.grid_w != b.grid_w)
+    return fail(&dr->err, VVS_EINVAL, "draft: drafter and target differ in d_model, dtype, prompts, vocabulary slice or grid");
+  if (n_nodes < 1) return fail(&dr->err, VVS_EINVAL, "draft: n_nodes < 1");
+  if (n_ctx < 1 || n_ctx > b.feature_slots) return fail(&dr->err, VVS_EINVAL, "draft: n_ctx must be in [1, feature_slots of the target]");
+  if (n_unverified < 0 || n_unverified > VVS_MAX_FEATURE_SLOTS) return fail(&dr->err, VVS_EINVAL, "draft: n_unverified out of range");
+  if (!d_recent_tokens || !d_draft_tokens || !d_draft_probs) return fail(&dr->err, VVS_EINVAL, "draft: NULL argument");
+  TreeDesc shape;
+  vvs_status rc = build_tree(n_nodes, h_parent, h_tree_mask, &shape, &dr->err);
+  if (rc != VVS_OK) return rc;
+  // block tokens of the drafter's forwards: the n_ctx pairs (the last is the root), then the nodes that
+  // have children, ordered by depth and then id, so that a level only appends tokens
+  const int T = n_nodes + 1, k = n_ctx;
+  std::vector<int> order;
+  int last_level = 0;
+  for (int j = 1; j < T; ++j)
+    if (shape.first_child[j] >= 0) { order.push_back(j); last_level = std::max(last_level, (int)shape.depth[j]); }
+  std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return shape.depth[x] < shape.depth[y]; });
+  if (k + (int)order.size() > dr->Tmax)
+    return fail(&dr->err, VVS_ESIZE, "draft: n_ctx + expanded nodes exceeds max_nodes + 1 of the drafter context");
+  std::vector<int> slot(T, -1);
+  slot[0] = k - 1;
+  for (size_t i = 0; i < order.size(); ++i) slot[order[i]] = k + (int)i;
+  hipStream_t st = (hipStream_t)s;
+  launch_draft_state(dr, tg, k, n_unverified, st);
+  launch_draft_zero_leaves(dr, shape, d_draft_probs, st);
+  const int32_t* state = (const int32_t*)(dr->ws + dr->w.state);
+  PosDesc pos{state, state + dr->B, 0, dr->P, dr->cfg.grid_w};
+  DraftLevel lv;
+  memset(&lv, 0, sizeof(lv));
+  lv.k = k;
+  lv.n_nodes = n_nodes;
+  int n_in = 0;
+  for (int level = 0; level <= last_level; ++level) {
+    while (n_in < (int)order.size() && shape.depth[order[n_in]] <= level) ++n_in;
+    lv.Tq = k + n_in;
+    std::vector<int32_t> bp(lv.Tq > 1 ? lv.Tq - 1 : 1);
+    for (int t = 1; t < lv.Tq; ++t) {
+      if (t < k) { bp[t - 1] = t - 1; continue; }
+      const int j = order[t - k];
+      lv.node[t] = (int8_t)j;
+      lv.parent_slot[t] = (int8_t)slot[shape.parent[j]];
+      bp[t - 1] = slot[shape.parent[j]];
+    }
+    TreeDesc blk;
+    rc = build_tree(lv.Tq - 1, bp.data(), nullptr, &blk, &dr->err);
+    if (rc != VVS_OK) return rc;
+    lv.n_sel = 0;
+    for (int j = 0; j < T; ++j)
+      if (shape.first_child[j] >= 0 && shape.depth[j] == level) {
+        lv.sel_node[lv.n_sel] = (int8_t)j;
+        lv.sel_slot[lv.n_sel] = (int8_t)slot[j];
+        ++lv.n_sel;
+      }
+    launch_draft_input(dr, tg, lv, d_recent_tokens, d_draft_tokens, st);
+    launch_forward(dr, blk, pos, lv.Tq, nullptr, nullptr, nullptr, 0, nullptr, 0, 1, st, true);
+    launch_draft_select(dr, lv, shape, d_given_tokens, d_draft_tokens, d_draft_probs, st);
+    lv.Tq_prev = lv.Tq;
+  }
+  rc = check_launch(dr, "draft");
+  if (rc != VVS_OK) return rc;
+  dr->last_T = lv.Tq;
+  return VVS_OK;
 }
 
 vvs_status vvs_read_state(vvs_ctx* ctx, int32_t* d_state, vvs_stream s) {

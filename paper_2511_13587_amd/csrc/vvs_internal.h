@@ -37,13 +37,14 @@ struct GemmPlan { int bm, bn, splits; };
 // Byte offsets into the caller's workspace.
 struct Workspace {
   size_t state, outcome, node_result, tokens, rope_tab, x, h, gemm_out, q, attn, act, hf, logits, probs,
-      pq_work, ss, ss2, ring, ring_state, total;
+      pq_work, ss, ss2, ring, ring_state, din, total;
 };
 
 struct PackedLayout {
   size_t embed, prefix_embed, gf, wout;
   size_t layer0, layer_stride;           // per layer block
   size_t g1, wqkv, wo, g2, wgu, wd;      // offsets inside a layer block
+  size_t fc;                             // drafter contexts: the input map [2d -> d]
   size_t total;
 };
 
@@ -97,7 +98,7 @@ void launch_pack_weights(Ctx* c, const void* const* tensors, hipStream_t s);
 void launch_forward(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int T, const int32_t* d_tokens_bt,
                     const void* d_prefix_cond, const void* d_prefix_uncond, int chunk_start,
                     const int32_t* d_forced, int n_forced, int logits_mode /*0 none, 1 every token, 2 last token of each row*/,
-                    hipStream_t s);
+                    hipStream_t s, bool from_din = false /*drafter: inputs = fc applied to the rows of workspace din*/);
 void launch_build_tokens(Ctx* c, int T, const int32_t* d_draft, hipStream_t s);
 void launch_accept(Ctx* c, const TreeDesc& tree, int T, const float* d_logits, const int32_t* d_draft_tokens,
                    const float* d_q, const float* d_u, int u_stride_b, int u_stride_j, int u_off_acc, int u_off_term,
@@ -109,6 +110,23 @@ void launch_push_prefill_feature(Ctx* c, int T_last_chunk, hipStream_t s);
 void launch_read_features(Ctx* c, float* d_features, int32_t* d_count, hipStream_t s);
 void launch_path_similarity(Ctx* c, const TreeDesc& tree, int n_nodes, const int32_t* d_draft_tokens, float alpha, int stride,
                             float* d_similarity, hipStream_t s);
+
+// One level of a drafting call: which block token is which node of the candidate tree.
+struct DraftLevel {
+  int32_t k;                        // context pairs (block tokens 0 .. k-1)
+  int32_t Tq, Tq_prev;              // block tokens per row of this level's forward and of the previous one
+  int32_t n_nodes;                  // N of the candidate tree
+  int8_t node[VVS_MAX_T];           // block token t >= k: its node id
+  int8_t parent_slot[VVS_MAX_T];    // block token t >= k: block index of the node's parent
+  int32_t n_sel;                    // nodes expanded at this level
+  int8_t sel_node[VVS_MAX_T], sel_slot[VVS_MAX_T];
+};
+void launch_draft_state(Ctx* dr, const Ctx* tg, int k, int n_unverified, hipStream_t s);
+void launch_draft_zero_leaves(Ctx* dr, const TreeDesc& shape, float* d_probs, hipStream_t s);
+void launch_draft_input(Ctx* dr, const Ctx* tg, const DraftLevel& lv, const int32_t* d_recent, const int32_t* d_draft_tokens,
+                        hipStream_t s);
+void launch_draft_select(Ctx* dr, const DraftLevel& lv, const TreeDesc& shape, const int32_t* d_given_tokens, int32_t* d_draft_tokens,
+                         float* d_probs, hipStream_t s);
 void launch_read_state(Ctx* c, int32_t* d_state, hipStream_t s);
 void launch_set_state(Ctx* c, const int32_t* d_state, hipStream_t s);
 void launch_debug_logits(Ctx* c, float* raw, float* mixed, float* probs, hipStream_t s);

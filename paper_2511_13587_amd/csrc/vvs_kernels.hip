@@ -155,6 +155,7 @@ static void pack_weights_t(Ctx* c, const void* const* t, hipStream_t s) {
   const void* const* tail = t + 2 + 9 * c->L;
   gain(tail[0], c->p.gf);
   transpose_into<T>(tail[1], c->pw + c->p.wout, d, c->veff, c->V, c->lo, s, 1, 0, sizeof(T) == 2 ? tail[0] : nullptr);
+  if (c->cfg.draft_input) transpose_into<T>(tail[2], c->pw + c->p.fc, 2 * d, d, d, 0, s);
 }
 
 void launch_pack_weights(Ctx* c, const void* const* tensors, hipStream_t s) {
@@ -471,7 +472,8 @@ static int run_gemm(Ctx* c, const void* A, const void* W, float* C, int M, int N
 // bf16(x) in packed operand order, and per-row sums of squares; the projections that follow a norm
 // take bf16(x) as operand and apply the RMSNorm factor to their output tile (gains are in the weights).
 static void forward_fused(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, const int32_t* d_tokens_bt, const void* pc,
-                          const void* pu, int chunk_start, const int32_t* forced, int n_forced, int logits_mode, hipStream_t s) {
+                          const void* pu, int chunk_start, const int32_t* forced, int n_forced, int logits_mode, hipStream_t s,
+                          bool from_din) {
   const int d = c->d, F = c->F, M = c->R * Tq, NS = (d / 64 + 3) & ~3;   // slabs per row, padded to a multiple of 4 (zeros)
   float* x = (float*)(c->ws + c->w.x);
   bf16_t* xb = (bf16_t*)(c->ws + c->w.h);
@@ -480,7 +482,12 @@ static void forward_fused(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int 
   bf16_t* act = (bf16_t*)(c->ws + c->w.act);
   EmbedArgs ea{Tq, d, c->V, d_tokens_bt ? 0 : 1, d_tokens_bt, pc, pu, c->cfg.prefix_kind, c->cfg.n_classes, c->P, chunk_start,
                n_forced, forced};
-  { Timed timed(c, VVS_K_ELEMENTWISE, s);
+  if (from_din) {             // drafter: x = [embedding ; feature] W_fc, through the residual epilogue on a zeroed x
+    launch_fill_zero(x, sizeof(float) * (size_t)M * d, s);
+    Timed timed(c, VVS_K_GEMM, s);
+    mfma_gemm_resid(c, (const bf16_t*)(c->ws + c->w.din), (const bf16_t*)(c->pw + c->p.fc), x, xb, ss, M, 2 * d, s);
+  } else {
+    Timed timed(c, VVS_K_ELEMENTWISE, s);
     hipLaunchKernelGGL(k_embed_packed, dim3(M), dim3(256), 0, s, x, xb, ss, NS, (const bf16_t*)(c->pw + c->p.embed),
                        (const bf16_t*)(c->pw + c->p.prefix_embed), ea);
   }
@@ -522,11 +529,12 @@ static void forward_fused(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int 
 
 template <typename T>
 static void forward_t(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, const int32_t* d_tokens_bt, const void* pc,
-                      const void* pu, int chunk_start, const int32_t* forced, int n_forced, int logits_mode, hipStream_t s) {
+                      const void* pu, int chunk_start, const int32_t* forced, int n_forced, int logits_mode, hipStream_t s,
+                      bool from_din) {
   const int d = c->d, F = c->F, M = c->R * Tq;
   const bool folded = sizeof(T) == 2;          // bf16: norm gains are folded into the packed weights
   if (folded && ((M + 63) / 64) * (d / 64) >= 128) {
-    forward_fused(c, tree, pos, Tq, d_tokens_bt, pc, pu, chunk_start, forced, n_forced, logits_mode, s);
+    forward_fused(c, tree, pos, Tq, d_tokens_bt, pc, pu, chunk_start, forced, n_forced, logits_mode, s, from_din);
     return;
   }
   float* x = (float*)(c->ws + c->w.x);
@@ -538,12 +546,17 @@ static void forward_t(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, 
   const float* rope = (const float*)(c->ws + c->w.rope_tab);
   EmbedArgs ea{Tq, d, c->V, d_tokens_bt ? 0 : 1, d_tokens_bt, pc, pu, c->cfg.prefix_kind, c->cfg.n_classes, c->P, chunk_start,
                n_forced, forced};
-  { Timed timed(c, VVS_K_ELEMENTWISE, s);
-  hipLaunchKernelGGL(k_embed<T>, dim3(M), dim3(256), 0, s, x, (const T*)(c->pw + c->p.embed),
-                     (const T*)(c->pw + c->p.prefix_embed), ea);
-  }
   int splits = 0;   // partial sums waiting to be added to x
   size_t sstride = 0;
+  if (from_din) {             // drafter: x = 0 + [embedding ; feature] W_fc, added by the first norm kernel
+    launch_fill_zero(x, sizeof(float) * (size_t)M * d, s);
+    splits = run_gemm(c, c->ws + c->w.din, c->pw + c->p.fc, go, M, d, 2 * d, true, s);
+    sstride = (size_t)M * d;
+  } else {
+    Timed timed(c, VVS_K_ELEMENTWISE, s);
+    hipLaunchKernelGGL(k_embed<T>, dim3(M), dim3(256), 0, s, x, (const T*)(c->pw + c->p.embed),
+                       (const T*)(c->pw + c->p.prefix_embed), ea);
+  }
   for (int l = 0; l < c->L; ++l) {
     const char* lw = c->pw + c->p.layer0 + c->p.layer_stride * l;
     T* kc = (T*)c->kv + c->kv_layer_stride * l;
@@ -609,9 +622,10 @@ static void forward_t(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, 
 }
 
 void launch_forward(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int T, const int32_t* d_tokens_bt, const void* pc,
-                    const void* pu, int chunk_start, const int32_t* forced, int n_forced, int logits_mode, hipStream_t s) {
-  if (c->cfg.dtype == VVS_BF16) forward_t<bf16_t>(c, tree, pos, T, d_tokens_bt, pc, pu, chunk_start, forced, n_forced, logits_mode, s);
-  else forward_t<float>(c, tree, pos, T, d_tokens_bt, pc, pu, chunk_start, forced, n_forced, logits_mode, s);
+                    const void* pu, int chunk_start, const int32_t* forced, int n_forced, int logits_mode, hipStream_t s, bool from_din) {
+  if (c->cfg.dtype == VVS_BF16)
+    forward_t<bf16_t>(c, tree, pos, T, d_tokens_bt, pc, pu, chunk_start, forced, n_forced, logits_mode, s, from_din);
+  else forward_t<float>(c, tree, pos, T, d_tokens_bt, pc, pu, chunk_start, forced, n_forced, logits_mode, s, from_din);
 }
 
 // ------------------------------------------------------------------------------------------------ KV commit

@@ -1,0 +1,224 @@
+"""GPU parity of the drafting call (vvs_draft: Algorithm 2 "C_t <- M_D(f_t, a)"; Section 3, "Stale
+Feature Reusability") against the CPU checker's drafter, through the C ABI.
+
+The drafter's tree rule takes the ids with the largest mixed logits, so a token is only compared when
+the checker's own gap between the chosen logit and the next one is wider than the logit tolerance;
+below a node whose token may legitimately differ nothing more is compared in that run.  A second run
+hands the checker's tokens to the library (d_given_tokens) and compares every distribution."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2511_13587_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gc():
+    from tests import gpu_common
+    return gpu_common
+
+
+class DraftSide:
+    """Drafter context + checker drafter (+ a checker with perturbed rounding for the noise floor)."""
+
+    def __init__(self, gc, pair, max_block, std=0.02, shadow=False):
+        from oracle import vvs_drafter as vd
+        self.gc, self.pair, shape = gc, pair, pair.shape
+        self.dshape = shape.replace(n_layers=1)
+        self.dw = synth.make_drafter_weights(shape, pair.w, std=std, gain_jitter=0.1)
+        self.cfg = gc.vb.make_config(self.dshape, max_nodes=max_block - 1, feature_slots=0,
+                                     feature_pre_norm=pair.cfg.feature_pre_norm, draft_input=1)
+        self.ctx = gc.vb.Context(self.cfg)
+        self.ctx.load_weights_from_host(self.dw, synth.drafter_weight_names())
+        ocfg = dict(dataclasses.asdict(shape), feature_pre_norm=pair.cfg.feature_pre_norm)
+        self.oracle = vd.Drafter(ocfg, self.dw)
+        self.shadow = None
+        if shadow:
+            self.shadow = vd.Drafter(ocfg, self.dw)
+            gc.perturbed_rounding(self.shadow.m)
+        self.floor = 0.0
+        self.worst = 0.0                 # largest log-probability difference seen by compare()
+
+    def draft(self, parent, k, recent, n_unverified=0, given=None):
+        pair, shape = self.pair, self.pair.shape
+        B, N = shape.n_prompts, len(parent)
+        dev = pair.dev
+        d_recent = torch.from_numpy(np.ascontiguousarray(recent, dtype=np.int32)).to(dev)
+        d_given = None if given is None else torch.from_numpy(np.ascontiguousarray(given, dtype=np.int32)).to(dev)
+        tok = torch.full((B, N), -7, dtype=torch.int32, device=dev)
+        q = torch.full((B, N + 1, shape.v_eff), -1.0, dtype=torch.float32, device=dev)
+        self.ctx.vvs_draft(pair.ctx, N, np.asarray(parent, dtype=np.int32), None, k, d_recent, n_unverified, d_given, tok, q)
+        torch.cuda.synchronize()
+        root = pair.oracle.n_emitted - 1 + n_unverified
+        feats = [pair.oracle.features(r)[-k:] for r in range(2 * B)]
+        otok, oq = self.oracle.draft(parent, recent, feats, root, given_tokens=given)
+        if self.shadow is not None:
+            sfeats = [pair.shadow.features(r)[-k:] for r in range(2 * B)]
+            self.shadow.draft(parent, recent, sfeats, root, given_tokens=otok)
+            both = ~np.isnan(self.oracle.mixed)
+            self.floor = max(self.floor, float(np.abs(self.shadow.mixed[both] - self.oracle.mixed[both]).max()))
+        return tok.cpu().numpy(), q.cpu().numpy(), otok, oq
+
+    def compare(self, parent, got_tok, got_q, otok, oq, tol_mixed, label, tokens_given=False):
+        """Returns (distributions compared, nodes whose subtree was left out because of a near tie)."""
+        shape = self.pair.shape
+        T = len(parent) + 1
+        kids = [[c for c in range(1, T) if parent[c - 1] == j] for j in range(T)]
+        compared = skipped = 0
+        for b in range(shape.n_prompts):
+            dead = set()
+            for j in range(T):
+                if j and (int(parent[j - 1]) in dead):
+                    dead.add(j)
+                if not kids[j]:
+                    assert (got_q[b, j] == 0).all(), (label, b, j, "leaf row not zero")
+                    continue
+                if j in dead:
+                    continue
+                want, got = oq[b, j], got_q[b, j]
+                assert np.isfinite(got).all() and abs(got.sum() - 1) < 1e-4, (label, b, j)
+                if shape.dtype == synth.DTYPE_FP32:
+                    assert np.abs(got - want).max() <= 1e-3 * max(1.0, want.max()), (label, b, j, np.abs(got - want).max())
+                big = want > 1e-7
+                err = np.abs(np.log(got[big]) - np.log(want[big])).max()
+                self.worst = max(self.worst, float(err))
+                assert err <= 2 * tol_mixed, f"{label}: prompt {b} node {j}: log-probabilities differ by {err} (bound {2 * tol_mixed})"
+                compared += 1
+                if tokens_given:
+                    assert [got_tok[b, c - 1] for c in kids[j]] == [otok[b, c - 1] for c in kids[j]]
+                    continue
+                mixed = np.sort(self.oracle.mixed[b, j])[::-1]
+                for rank, c in enumerate(kids[j]):
+                    clear = mixed[rank] - mixed[rank + 1] > 2 * tol_mixed and (rank == 0 or mixed[rank - 1] - mixed[rank] > 2 * tol_mixed)
+                    if clear:
+                        assert got_tok[b, c - 1] == otok[b, c - 1], f"{label}: prompt {b} node {c}: token {got_tok[b, c - 1]} vs {otok[b, c - 1]}"
+                    elif got_tok[b, c - 1] != otok[b, c - 1]:
+                        dead.add(c)
+                        skipped += 1
+                    assert shape.logit_lo <= got_tok[b, c - 1] < shape.logit_hi
+                assert len(set(got_tok[b, c - 1] for c in kids[j])) == len(kids[j])
+        return compared, skipped
+
+    def close(self):
+        self.ctx.close()
+
+
+def test_tiny_drafting_loop_fp32(gc):
+    """fp32 shape: draft -> verify -> commit for several steps, the context growing from 1 to 5 pairs, then
+    a drafting call after two tokens were accepted without verification (stale features).  Distributions
+    to 1e-3 of their peak, tokens identical outside near ties, given-token mode identical tokens."""
+    shape = synth.TINY.replace(n_nodes=9, n_prompts=2)
+    parent = synth.tree_parents((3, 4, 2), 9, seed=3)
+    pair = gc.Pair(shape, gain_jitter=0.1)
+    side = DraftSide(gc, pair, max_block=5 + 9, std=0.05)
+    first, ofirst, _ = pair.prefill()
+    assert (first == ofirst).all()
+    seq = [[int(first[b])] for b in range(shape.n_prompts)]
+    tol = gc.mixed_tol(shape)
+    steps = compared = 0
+    ks = []
+    while steps < 6:
+        k = min(5, min(len(pair.oracle.features(r)) for r in range(2 * shape.n_prompts)), min(len(s) for s in seq))
+        recent = np.array([s[-k:] for s in seq])
+        tok, q, otok, oq = side.draft(parent, k, recent)
+        c, s = side.compare(parent, tok, q, otok, oq, tol, f"step {steps} k={k}")
+        compared += c
+        ks.append(k)
+        if not np.array_equal(tok, otok):
+            break                                               # a near tie went the other way: the two sequences part here
+        u = synth.make_uniforms(shape, len(parent), steps)
+        out, oout = pair.verify(parent, otok, oq.astype(np.float32), u, mask=synth.ancestor_mask(parent))
+        gc.decisions_match(out, oout, pair.oracle.traces, shape.logit_lo)
+        if not ((out[0] == oout[0]).all() and (out[2] == oout[2]).all()):
+            break
+        for b in range(shape.n_prompts):
+            seq[b] += pair.oracle.emitted_tokens(b)
+        pair.commit()
+        steps += 1
+    assert steps >= 4 and max(ks) == 5 and ks[0] == 1 and compared >= 20
+    # verification-free step: two tokens of the last tree's first path are taken over unverified
+    k = 5
+    extra = np.array([[otok[b, 0], otok[b, [c for c in range(1, 10) if parent[c - 1] == 1][0] - 1]] for b in range(shape.n_prompts)])
+    recent = np.array([(seq[b] + list(extra[b]))[-k:] for b in range(shape.n_prompts)])
+    tok, q, otok2, oq2 = side.draft(parent, k, recent, n_unverified=2)
+    side.compare(parent, tok, q, otok2, oq2, tol, "stale features")
+    tok, q, otok3, oq3 = side.draft(parent, k, recent, n_unverified=2, given=otok2)
+    assert np.array_equal(otok3, otok2)
+    c, _ = side.compare(parent, tok, q, otok3, oq3, tol, "given tokens", tokens_given=True)
+    assert c == shape.n_prompts * len(set(int(p) for p in parent))
+    side.close()
+    pair.close()
+
+
+def test_drafting_argument_errors(gc):
+    shape = synth.TINY.replace(n_nodes=4, n_prompts=2)
+    pair = gc.Pair(shape, with_oracle=False)
+    side = DraftSide(gc, pair, max_block=6)
+    vb = gc.vb
+    dev = pair.dev
+    recent = torch.zeros((2, 5), dtype=torch.int32, device=dev)
+    tok = torch.zeros((2, 4), dtype=torch.int32, device=dev)
+    q = torch.zeros((2, 5, shape.v_eff), dtype=torch.float32, device=dev)
+    chain = np.arange(4, dtype=np.int32)
+
+    def status(fn):
+        with pytest.raises(vb.VvsError) as e:
+            fn()
+        return e.value.status
+
+    assert status(lambda: side.ctx.vvs_draft(pair.ctx, 4, chain, None, 1, recent, 0, None, tok, q)) == vb.VVS_ESTATE   # target not prefilled
+    pair.prefill(run_oracle=False)
+    assert status(lambda: side.ctx.vvs_draft(pair.ctx, 4, chain, None, 0, recent, 0, None, tok, q)) == vb.VVS_EINVAL
+    assert status(lambda: side.ctx.vvs_draft(pair.ctx, 4, chain, None, 6, recent, 0, None, tok, q)) == vb.VVS_EINVAL
+    assert status(lambda: side.ctx.vvs_draft(pair.ctx, 4, chain, None, 1, recent, 9, None, tok, q)) == vb.VVS_EINVAL
+    assert status(lambda: side.ctx.vvs_draft(pair.ctx, 4, chain, None, 4, recent, 0, None, tok, q)) == vb.VVS_ESIZE    # 4 pairs + 3 expanded nodes > 6
+    assert status(lambda: pair.ctx.vvs_draft(pair.ctx, 4, chain, None, 1, recent, 0, None, tok, q)) == vb.VVS_EINVAL   # not a drafter context
+    assert status(lambda: side.ctx.vvs_draft(side.ctx, 4, chain, None, 1, recent, 0, None, tok, q)) == vb.VVS_EINVAL   # target is a drafter
+    first = torch.zeros(2, dtype=torch.int32, device=dev)
+    with pytest.raises(vb.VvsError):
+        side.ctx.vvs_prefill(first, None, None, torch.zeros(2, device=dev), first)
+    side.ctx.vvs_draft(pair.ctx, 4, chain, None, 1, recent, 0, None, tok, q)       # a valid call: one pair, a chain of 4
+    torch.cuda.synchronize()
+    assert (q.cpu().numpy()[:, 4] == 0).all() and np.allclose(q.cpu().numpy()[:, :4].sum(-1), 1, atol=1e-4)
+    side.close()
+    pair.close()
+
+
+def test_xl_shape_drafting_bf16(gc):
+    """Config 3's shape (bf16; target cut to 2 layers, drafter of 1 block): five pairs of context, a
+    36-node tree of the same kind as the benchmark's.  The early levels run the split-K kernels, the last
+    ones (>= 385 block rows) the 5-kernel layer.  Log-probabilities within twice the mixed-logit bound (noise floor measured with a
+    checker whose rounding points are perturbed); tokens identical outside near ties; with the checker's
+    tokens given, every distribution is compared."""
+    base = synth.XL_TREE.replace(n_layers=2)
+    parent = synth.tree_parents((4, 6, 8, 8, 6, 4), 36)
+    n_internal = len(set(int(p) for p in parent if p > 0))
+    pair = gc.Pair(base.replace(n_nodes=36, tree_widths=None), shadow=True)
+    side = DraftSide(gc, pair, max_block=5 + n_internal, shadow=True)
+    shape = pair.shape
+    first, ofirst, _ = pair.prefill(n_forced=45, robust_u=True)
+    assert (first == ofirst).all()
+    # five tokens that no logit noise can reject: a chain that is accepted without verification
+    chain = np.arange(5, dtype=np.int32)
+    cq, ctoks = synth.make_draft(shape.replace(n_nodes=5), chain, 0)
+    out, oout = pair.verify(chain, ctoks, cq, synth.make_uniforms(shape, 5, 0), n_post=5)
+    assert (out[0] == 5).all() and (oout[0] == 5).all()
+    pair.commit()
+    # the five latest tokens; the last one is the checker's pending token on both sides (the drafter takes its
+    # tokens as an input, so a near tie in that draw on the GPU does not matter here)
+    recent = np.concatenate([ctoks[:, 1:], oout[2][:, None]], axis=1)
+    tok, q, otok, oq = side.draft(parent, 5, recent)
+    tol = max(gc.mixed_tol(side.dshape), 3.0 * side.floor)     # the floor is measured on mixed logits
+    c1, s1 = side.compare(parent, tok, q, otok, oq, tol, "free run")
+    tok2, q2, otok2, oq2 = side.draft(parent, 5, recent, given=otok)
+    c2, _ = side.compare(parent, tok2, q2, otok2, oq2, tol, "given tokens", tokens_given=True)
+    print(f"xl drafting: mixed-logit noise floor {side.floor:.4f}, bound {tol:.4f}, largest log-probability difference {side.worst:.4f}; free run compared {c1} distributions, "
+          f"{s1} subtrees left out after near ties; given tokens compared {c2}")
+    assert c2 == shape.n_prompts * (n_internal + 1) and c1 >= shape.n_prompts
+    assert 5 + n_internal >= 25                                  # the last levels take the 5-kernel layer path (16 x 25 rows)
+    side.close()
+    pair.close()
