@@ -158,12 +158,80 @@ __global__ __launch_bounds__(1024) void k_draft_select(const float* __restrict__
   }
 }
 
+// The same for slices of at most 16 * 1024 ids: a thread keeps its 16 mixed logits in registers, so the
+// rows are read once and a taken id is simply removed from its owner's registers.
+__global__ __launch_bounds__(1024) void k_draft_select_regs(const float* __restrict__ logits, DraftLevel lv, TreeDesc shape,
+                                                            const int32_t* __restrict__ given, int32_t* __restrict__ draft_tokens,
+                                                            float* __restrict__ probs, int V, int lo, float cfg_scale) {
+  constexpr int NR = 16;
+  __shared__ float red[16];
+  __shared__ float s_bv[16];
+  __shared__ int s_bi[16];
+  __shared__ int s_win;
+  const int b = blockIdx.x, j = lv.sel_node[blockIdx.y], t = lv.sel_slot[blockIdx.y];
+  const float* lc = logits + ((size_t)(2 * b) * lv.Tq + t) * V;
+  const float* lu = logits + ((size_t)(2 * b + 1) * lv.Tq + t) * V;
+  float* out = probs + ((size_t)b * shape.T + j) * V;
+  float mixed[NR];
+  float mx = -INFINITY;
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    const int i = threadIdx.x + r * 1024;
+    mixed[r] = -INFINITY;
+    if (i < V) mixed[r] = lu[i] + cfg_scale * (lc[i] - lu[i]);
+    mx = fmaxf(mx, mixed[r]);
+  }
+  mx = block_max(mx, red);
+  float e[NR];
+  float sum = 0.f;
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    e[r] = threadIdx.x + r * 1024 < V ? expf(mixed[r] - mx) : 0.f;
+    sum += e[r];
+  }
+  sum = block_sum(sum, red);
+  const float inv = 1.0f / sum;
+#pragma unroll
+  for (int r = 0; r < NR; ++r)
+    if (threadIdx.x + r * 1024 < V) out[threadIdx.x + r * 1024] = e[r] * inv;
+  for (int c = shape.first_child[j]; c >= 0; c = shape.next_sibling[c]) {
+    if (given) {
+      if (threadIdx.x == 0) draft_tokens[b * lv.n_nodes + c - 1] = given[b * lv.n_nodes + c - 1];
+      continue;
+    }
+    Best best{-INFINITY, 0x7fffffff};
+#pragma unroll
+    for (int r = 0; r < NR; ++r)                       // ascending ids: a later equal value does not replace an earlier one
+      if (mixed[r] > best.v) best = Best{mixed[r], (int)threadIdx.x + r * 1024};
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) best = better(best, Best{__shfl_xor(best.v, o, 64), __shfl_xor(best.i, o, 64)});
+    if ((threadIdx.x & 63) == 0) { s_bv[threadIdx.x >> 6] = best.v; s_bi[threadIdx.x >> 6] = best.i; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      Best w{s_bv[0], s_bi[0]};
+      for (int q = 1; q < 16; ++q) w = better(w, Best{s_bv[q], s_bi[q]});
+      s_win = w.i;
+      draft_tokens[b * lv.n_nodes + c - 1] = lo + w.i;
+    }
+    __syncthreads();
+    const int win = s_win;
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+      if (threadIdx.x + r * 1024 == win) mixed[r] = -INFINITY;
+    __syncthreads();                                   // s_win and the per-wave slots are rewritten by the next child
+  }
+}
+
 void launch_draft_select(Ctx* dr, const DraftLevel& lv, const TreeDesc& shape, const int32_t* d_given_tokens, int32_t* d_draft_tokens,
                          float* d_probs, hipStream_t s) {
   if (!lv.n_sel) return;
   Timed timed(dr, VVS_K_ACCEPT, s);
-  hipLaunchKernelGGL(k_draft_select, dim3(dr->B, lv.n_sel), dim3(1024), 0, s, (const float*)(dr->ws + dr->w.logits), lv, shape,
-                     d_given_tokens, d_draft_tokens, d_probs, dr->veff, dr->lo, dr->cfg.cfg_scale);
+  if (dr->veff <= 16 * 1024)
+    hipLaunchKernelGGL(k_draft_select_regs, dim3(dr->B, lv.n_sel), dim3(1024), 0, s, (const float*)(dr->ws + dr->w.logits), lv, shape,
+                       d_given_tokens, d_draft_tokens, d_probs, dr->veff, dr->lo, dr->cfg.cfg_scale);
+  else
+    hipLaunchKernelGGL(k_draft_select, dim3(dr->B, lv.n_sel), dim3(1024), 0, s, (const float*)(dr->ws + dr->w.logits), lv, shape,
+                       d_given_tokens, d_draft_tokens, d_probs, dr->veff, dr->lo, dr->cfg.cfg_scale);
 }
 
 }  // namespace vvs

@@ -533,7 +533,8 @@ static void forward_t(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, 
                       bool from_din) {
   const int d = c->d, F = c->F, M = c->R * Tq;
   const bool folded = sizeof(T) == 2;          // bf16: norm gains are folded into the packed weights
-  if (folded && ((M + 63) / 64) * (d / 64) >= 128) {
+  // a drafter runs one block per level of its tree: fewer launches matter more there than full tiles
+  if (folded && (c->cfg.draft_input || ((M + 63) / 64) * (d / 64) >= 128)) {
     forward_fused(c, tree, pos, Tq, d_tokens_bt, pc, pu, chunk_start, forced, n_forced, logits_mode, s, from_din);
     return;
   }

@@ -189,11 +189,12 @@ def test_drafting_argument_errors(gc):
 
 
 def test_xl_shape_drafting_bf16(gc):
-    """Config 3's shape (bf16; target cut to 2 layers, drafter of 1 block): five pairs of context, a
-    36-node tree of the same kind as the benchmark's.  The early levels run the split-K kernels, the last
-    ones (>= 385 block rows) the 5-kernel layer.  Log-probabilities within twice the mixed-logit bound (noise floor measured with a
-    checker whose rounding points are perturbed); tokens identical outside near ties; with the checker's
-    tokens given, every distribution is compared."""
+    """Config 3's shape (bf16; target cut to 2 layers, drafter of 1 block, which always takes the 5-kernel
+    layer path): five pairs of context, a 36-node tree of the same kind as the benchmark's (block rows grow
+    from 80 to 448 over the levels, so the small-tile and the 64-row-tile GEMM variants both run).
+    Log-probabilities within twice the mixed-logit bound (noise floor measured with a checker whose
+    rounding points are perturbed); tokens identical outside near ties; with the checker's tokens given,
+    every distribution is compared."""
     base = synth.XL_TREE.replace(n_layers=2)
     parent = synth.tree_parents((4, 6, 8, 8, 6, 4), 36)
     n_internal = len(set(int(p) for p in parent if p > 0))
@@ -219,6 +220,82 @@ def test_xl_shape_drafting_bf16(gc):
     print(f"xl drafting: mixed-logit noise floor {side.floor:.4f}, bound {tol:.4f}, largest log-probability difference {side.worst:.4f}; free run compared {c1} distributions, "
           f"{s1} subtrees left out after near ties; given tokens compared {c2}")
     assert c2 == shape.n_prompts * (n_internal + 1) and c1 >= shape.n_prompts
-    assert 5 + n_internal >= 25                                  # the last levels take the 5-kernel layer path (16 x 25 rows)
+    side.close()
+    pair.close()
+
+
+def test_whole_pipeline_with_drafter_and_dynamic_schedule_fp32(gc):
+    """Algorithm 2 end to end on the fp32 shape, every stage from the library: draft (vvs_draft on the cached
+    features) -> decision (vvs_path_similarity + vvs_skip_dynamic, Algorithm 1) -> either a target pass
+    (vvs_verify_post over the unverified tokens of the last step and the new tree, then vvs_kv_commit) or a
+    verification-free step (vvs_select_unverified).  The checker runs the same loop; the emitted sequences,
+    the skip decisions and the state agree, and the unverified tokens make the next draft use stale features."""
+    from oracle import vvs_schedule as vs
+    vb = gc.vb
+    shape = synth.TINY.replace(n_nodes=12)
+    tree = np.array([0, 0, 1, 1, 2, 3, 3], dtype=np.int32)           # paths [1 3 6] [1 3 7] [1 4] [2 5]
+    N = len(tree)
+    pair = gc.Pair(shape, gain_jitter=0.1)
+    side = DraftSide(gc, pair, max_block=5 + 3, std=0.05)
+    E = synth.make_codebook_embeddings(shape.vocab)
+    pair.ctx.vvs_set_codebook(torch.from_numpy(E).to(pair.dev))
+    first, ofirst, _ = pair.prefill()
+    assert (first == ofirst).all()
+    seq = [int(first[0])]                                             # emitted tokens (verified or not)
+    unverified = []
+    rng = np.random.default_rng(8)
+    G = shape.grid
+    tol = gc.mixed_tol(shape)
+    step = passes = skipped = stale_drafts = 0
+    last_verified = True
+    threshold, alpha = 0.45, 0.8
+    sims = []
+    while int(pair.oracle.n_emitted[0]) + len(unverified) < G and step < 200:
+        n_post = len(unverified)
+        k = min(5, len(pair.oracle.features(0)), len(seq))
+        recent = np.array([seq[-k:]])
+        tok, q, otok, oq = side.draft(tree, k, recent, n_unverified=n_post)
+        side.compare(tree, tok, q, otok, oq, tol, f"step {step}")
+        if not np.array_equal(tok, otok):
+            break                                                     # near tie in the tree rule: the sequences part here
+        stale_drafts += n_post > 0
+        d_tok = torch.from_numpy(otok.astype(np.int32)).to(pair.dev)
+        sim = float(pair.ctx.vvs_path_similarity(N, tree, None, d_tok, alpha, 2).cpu().numpy()[0])
+        osim = vs.path_similarity(tree, otok[0], E, alpha, 2)
+        assert abs(sim - osim) < 1e-5
+        sims.append(osim)
+        room = G - int(pair.oracle.n_emitted[0]) - n_post
+        skip = vb.vvs_skip_dynamic(sim, threshold, last_verified)
+        assert skip == vs.skip_dynamic(osim, threshold, last_verified)
+        if skip and abs(osim - threshold) > 1e-4 and room > 4:
+            usel = float(rng.random(dtype=np.float32))
+            st, kept = vb.vvs_select_unverified(N, tree, None, usel)
+            assert st == vb.VVS_OK and list(kept) == vs.select_unverified(tree, usel)
+            unverified = [int(otok[0, j - 1]) for j in kept]
+            seq += unverified
+            skipped += 1
+            last_verified = False
+        else:
+            parent = np.array(list(range(n_post)) + [int(p) + n_post for p in tree], dtype=np.int32)
+            toks = np.concatenate([np.array([unverified], dtype=np.int64).reshape(1, n_post), otok], axis=1)
+            qq = np.concatenate([np.zeros((1, n_post, shape.v_eff)), oq], axis=1).astype(np.float32)
+            u = synth.make_uniforms(shape.replace(n_nodes=len(parent)), len(parent), step)
+            out, oout = pair.verify(parent, toks, qq, u, n_post=n_post)
+            gc.check_logits(pair, f"step {step}")
+            gc.decisions_match(out, oout, pair.oracle.traces, shape.logit_lo)
+            if not ((out[0] == oout[0]).all() and (out[2] == oout[2]).all()):
+                break
+            seq += [int(toks[0, j - 1]) for j in oout[1][0][n_post + 1:]] + [int(oout[2][0])]
+            pair.commit()
+            unverified = []
+            passes += 1
+            last_verified = True
+            st_ = pair.ctx.vvs_read_state()
+            assert st_[1, 0] == pair.oracle.n_emitted[0] and st_[2, 0] == pair.oracle.pending[0]
+            assert len(seq) == int(pair.oracle.n_emitted[0])
+        step += 1
+    print(f"pipeline: {len(seq)} tokens, {passes} target passes, {skipped} verification-free steps, {stale_drafts} drafts on stale "
+          f"features, similarity {min(sims):.3f}..{max(sims):.3f}")
+    assert passes >= 8 and skipped >= 3 and stale_drafts >= 3
     side.close()
     pair.close()
