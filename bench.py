@@ -144,6 +144,7 @@ def main():
     ap.add_argument("--post", type=int, default=0,
                     help="post verification: this many unverified tokens of a previous verification-free step ride in front of the "
                          "draft tree (vvs_verify_post); 0 = the plain verify pass of the headline workload")
+    ap.add_argument("--no-drafter", action="store_true", help="leave out the separate timing of the draft side (vvs_draft)")
     ap.add_argument("--layers", type=int, default=0, help="override depth (debugging only; the result is then not the named workload)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -327,27 +328,28 @@ def main():
                         "mean_similarity": float(sim.mean().item())}
     # the draft side (a one-block drafter of the same width with random weights, five cached features as context,
     # the same tree shape, greedy top-k children), timed on its own: a second workload, not part of `value`
-    tree = synth.tree_parents(shape.tree_widths, shape.n_nodes - args.post)
-    n_expanded = len(set(int(p_) for p_ in tree if p_ > 0))
-    n_ctx = min(5, ctx.cfg.feature_slots)
-    dshape = shape.replace(n_layers=1)
-    dctx = vb.Context(vb.make_config(dshape, max_nodes=n_ctx + n_expanded - 1, feature_slots=0, draft_input=1))
-    dctx.load_weights_from_host(synth.make_drafter_weights(shape, weights), synth.drafter_weight_names())
-    recent = torch.from_numpy(np.random.default_rng(3).integers(shape.logit_lo, shape.logit_hi, (B, n_ctx)).astype(np.int32)).to(dev)
-    d_tok = torch.zeros((B, len(tree)), dtype=torch.int32, device=dev)
-    d_q = torch.zeros((B, len(tree) + 1, shape.v_eff), dtype=torch.float32, device=dev)
-    for _ in range(3):
-        dctx.vvs_draft(ctx, len(tree), tree, None, n_ctx, recent, 0, None, d_tok, d_q)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(30):
-        dctx.vvs_draft(ctx, len(tree), tree, None, n_ctx, recent, 0, None, d_tok, d_q)
-    torch.cuda.synchronize()
-    out["drafter"] = {"ms_per_call": (time.perf_counter() - t0) / 30 * 1e3, "blocks": 1, "context_pairs": n_ctx,
-                      "tree_nodes": len(tree), "levels": int(synth.node_depths(tree).max()), "expanded_nodes": n_expanded + 1,
-                      "weights": "random"}
-    dctx.close()
-    del dctx
+    if not args.no_drafter:
+        tree = synth.tree_parents(shape.tree_widths, shape.n_nodes - args.post)
+        n_expanded = len(set(int(p_) for p_ in tree if p_ > 0))
+        n_ctx = min(5, ctx.cfg.feature_slots)
+        dshape = shape.replace(n_layers=1)
+        dctx = vb.Context(vb.make_config(dshape, max_nodes=n_ctx + n_expanded - 1, feature_slots=0, draft_input=1))
+        dctx.load_weights_from_host(synth.make_drafter_weights(shape, weights), synth.drafter_weight_names())
+        recent = torch.from_numpy(np.random.default_rng(3).integers(shape.logit_lo, shape.logit_hi, (B, n_ctx)).astype(np.int32)).to(dev)
+        d_tok = torch.zeros((B, len(tree)), dtype=torch.int32, device=dev)
+        d_q = torch.zeros((B, len(tree) + 1, shape.v_eff), dtype=torch.float32, device=dev)
+        for _ in range(3):
+            dctx.vvs_draft(ctx, len(tree), tree, None, n_ctx, recent, 0, None, d_tok, d_q)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(30):
+            dctx.vvs_draft(ctx, len(tree), tree, None, n_ctx, recent, 0, None, d_tok, d_q)
+        torch.cuda.synchronize()
+        out["drafter"] = {"ms_per_call": (time.perf_counter() - t0) / 30 * 1e3, "blocks": 1, "context_pairs": n_ctx,
+                          "tree_nodes": len(tree), "levels": int(synth.node_depths(tree).max()), "expanded_nodes": n_expanded + 1,
+                          "weights": "random"}
+        dctx.close()
+        del dctx
     ctx.close()
     del ctx
     if not args.no_cpu_baseline:

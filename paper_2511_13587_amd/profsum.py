@@ -3,7 +3,12 @@
 
     python -m paper_2511_13587_amd.profsum kernels <results.db>
     python -m paper_2511_13587_amd.profsum counters <results.db>
+    python -m paper_2511_13587_amd.profsum window <results.db> <first kernel substring> <last kernel substring>
     python -m paper_2511_13587_amd.profsum traffic <fetch.db> <write.db> <kernel substring> <grid_x list, workgroups> [out.json]
+
+`window`: the dispatches between the first launch of one kernel and the last launch of another (e.g. the
+drafting calls of a bench run: from the first k_draft_state to the last k_draft_select), per kernel and per
+call of the first kernel.
 
 `traffic`: HBM bytes per launch of one kernel from a FETCH_SIZE run and a WRITE_SIZE run (KiB per
 dispatch), each scaled by what the same counter reads for the 256 MiB k_copy_bytes launches of the
@@ -33,6 +38,23 @@ def kernels(db: str, top: int = 30) -> str:
                        "or name like '%commit_kv%' group by 1, 2, 3, 4 order by 1, 2, 3, 4").fetchall()
     for n, gx, gy, gz, c, a, mn in rows:
         out.append(f"{short(n)[:48]:48s} grid ({gx:5d},{gy:3d},{gz:2d}) calls {c:6d} avg {a / 1e3:8.2f} us min {mn / 1e3:8.2f} us")
+    return "\n".join(out)
+
+
+def window(db: str, first: str, last: str) -> str:
+    cur = sqlite3.connect(db).cursor()
+    t0 = cur.execute("select min(start) from kernels where name like ?", (f"%{first}%",)).fetchone()[0]
+    t1 = cur.execute("select max(end) from kernels where name like ?", (f"%{last}%",)).fetchone()[0]
+    calls = cur.execute("select count(*) from kernels where name like ?", (f"%{first}%",)).fetchone()[0]
+    rows = cur.execute("select name, count(*), sum(end-start), avg(end-start) from kernels where start >= ? and end <= ? "
+                       "group by name order by 3 desc", (t0, t1)).fetchall()
+    busy = sum(r[2] for r in rows)
+    n = sum(r[1] for r in rows)
+    out = [f"window: first {first} .. last {last}: {calls} calls, {n} launches ({n / calls:.1f} per call), "
+           f"kernel time {busy / calls / 1e3:.1f} us per call, span {(t1 - t0) / calls / 1e3:.1f} us per call",
+           f"{'kernel':64s} {'per call':>9s} {'avg_us':>9s} {'us/call':>9s} {'pct':>6s}"]
+    for name, c, sm, a in rows:
+        out.append(f"{short(name)[:64]:64s} {c / calls:9.2f} {a / 1e3:9.2f} {sm / calls / 1e3:9.2f} {100 * sm / busy:6.2f}")
     return "\n".join(out)
 
 
@@ -75,6 +97,8 @@ if __name__ == "__main__":
     if len(sys.argv) >= 6 and sys.argv[1] == "traffic":
         print(traffic(sys.argv[2], sys.argv[3], sys.argv[4], [int(g) for g in sys.argv[5].split(",")],
                       sys.argv[6] if len(sys.argv) > 6 else None))
+    elif len(sys.argv) == 5 and sys.argv[1] == "window":
+        print(window(sys.argv[2], sys.argv[3], sys.argv[4]))
     elif len(sys.argv) == 3 and sys.argv[1] in ("kernels", "counters"):
         print(kernels(sys.argv[2]) if sys.argv[1] == "kernels" else counters(sys.argv[2]))
     else:
