@@ -299,3 +299,59 @@ def test_whole_pipeline_with_drafter_and_dynamic_schedule_fp32(gc):
     assert passes >= 8 and skipped >= 3 and stale_drafts >= 3
     side.close()
     pair.close()
+
+
+def test_drafting_edges_fp32(gc):
+    """Degenerate calls on the fp32 shape: more context pairs than cached features and than emitted tokens
+    (missing features read as zeros, the pairs start at image index 0), a chain-shaped tree (greedy decoding
+    of the drafter), a star (every candidate a child of the root), and the pre-norm kind of feature."""
+    shape = synth.TINY.replace(n_nodes=8, n_prompts=2)
+    for pre_norm in (0, 1):
+        pair = gc.Pair(shape, gain_jitter=0.1, feature_pre_norm=pre_norm)
+        side = DraftSide(gc, pair, max_block=3 + 8, std=0.05)
+        first, ofirst, _ = pair.prefill()
+        assert (first == ofirst).all()
+        tol = gc.mixed_tol(shape)
+        rng = np.random.default_rng(4)
+        # right after the prefill: one cached feature, one emitted token, but three pairs asked for
+        recent = np.concatenate([rng.integers(0, shape.vocab, (2, 2)), first[:, None]], axis=1)
+        zero = np.zeros((2, shape.d_model))
+        feats_before = [pair.oracle.ring[r] for r in range(4)]
+        for r in range(4):
+            pair.oracle.ring[r] = [zero[0], zero[1]] + list(feats_before[r])       # what the library reads for the missing ones
+        for parent in (np.arange(8), np.zeros(8, dtype=np.int64), np.array([0, 0, 1, 1, 2, 2, 3, 4])):
+            tok, q, otok, oq = side.draft(parent.astype(np.int32), 3, recent)
+            c, _ = side.compare(parent, tok, q, otok, oq, tol, f"pre_norm {pre_norm} parent {list(parent)}")
+            assert c >= 2 and np.array_equal(tok, otok)
+        for r in range(4):
+            pair.oracle.ring[r] = feats_before[r]
+        side.close()
+        pair.close()
+
+
+def test_7b_like_slice_drafting_bf16(gc):
+    """Config 4's structure at reduced width (head size 128, 65536-id vocabulary, ids 4096 .. 12287 allowed):
+    the drafted ids carry the slice offset and the distributions cover the slice only."""
+    base = synth.SEVEN_B.replace(n_layers=2, d_model=1024, n_heads=8, d_ff=2816)
+    parent = np.array([0, 0, 1, 1, 2, 3], dtype=np.int32)
+    pair = gc.Pair(base, shadow=True)
+    side = DraftSide(gc, pair, max_block=2 + 3, shadow=True)
+    shape = pair.shape
+    first, ofirst, _ = pair.prefill(n_forced=40, robust_u=True)
+    assert (first == ofirst).all()
+    chain = np.arange(3, dtype=np.int32)
+    cq, ctoks = synth.make_draft(shape.replace(n_nodes=3), chain, 0)
+    out, oout = pair.verify(chain, ctoks, cq, synth.make_uniforms(shape, 3, 0), n_post=3)
+    assert (out[0] == 3).all() and (oout[0] == 3).all()
+    pair.commit()
+    recent = np.concatenate([ctoks[:, 2:], oout[2][:, None]], axis=1)
+    tok, q, otok, oq = side.draft(parent, 2, recent)
+    tol = max(gc.mixed_tol(side.dshape), 3.0 * side.floor)
+    c1, s1 = side.compare(parent, tok, q, otok, oq, tol, "free run")
+    tok2, q2, otok2, oq2 = side.draft(parent, 2, recent, given=otok)
+    c2, _ = side.compare(parent, tok2, q2, otok2, oq2, tol, "given tokens", tokens_given=True)
+    assert c2 == shape.n_prompts * 4 and (tok >= 4096).all() and (tok < 12288).all()
+    print(f"7b-like drafting: floor {side.floor:.4f}, bound {tol:.4f}, worst log-probability difference {side.worst:.4f}; "
+          f"{c1} free-run distributions, {s1} subtrees after near ties")
+    side.close()
+    pair.close()
