@@ -176,3 +176,42 @@ def test_ragged_prompts_some_finished_fp32(gc):
     for row in range(shape.n_rows):
         assert np.abs(feats[row, 0] - pair.oracle.features(row)[0]).max() < 1e-4
     pair.close()
+
+
+def test_rerun_is_bit_identical_bf16(gc):
+    """No kernel of the path uses atomics or an order that depends on scheduling: the same verify call on
+    the same state gives bit-identical logits, probabilities and outcome, and so does the same drafting
+    call (XL width, 2 layers, the 26-node tree)."""
+    shape = synth.XL_TREE.replace(n_layers=2)
+    parent = synth.tree_parents(shape.tree_widths, shape.n_nodes)
+    pair = gc.Pair(shape, with_oracle=False)
+    pair.prefill(n_forced=45, run_oracle=False)
+    state = torch.from_numpy(pair.ctx.vvs_read_state()).to(pair.dev)
+    q, toks = synth.make_draft(shape, parent, 0)
+    u = synth.make_uniforms(shape, shape.n_nodes, 0)
+    runs = []
+    for _ in range(3):
+        pair.ctx.vvs_set_state(state)
+        out, _ = pair.verify(parent, toks, q, u, run_oracle=False, mask=synth.ancestor_mask(parent))
+        raw, mixed, probs = pair.gpu_logits()
+        runs.append((out, raw, probs))
+    for out, raw, probs in runs[1:]:
+        assert np.array_equal(raw, runs[0][1]) and np.array_equal(probs, runs[0][2])
+        assert all(np.array_equal(a, b) for a, b in zip(out, runs[0][0]))
+    pair.commit(run_oracle=False)
+    vb = gc.vb
+    n_exp = len(set(int(p) for p in parent if p > 0))
+    dctx = vb.Context(vb.make_config(shape.replace(n_layers=1), max_nodes=5 + n_exp - 1, feature_slots=0, draft_input=1))
+    dctx.load_weights_from_host(synth.make_drafter_weights(shape, pair.w), synth.drafter_weight_names())
+    recent = torch.from_numpy(np.random.default_rng(2).integers(0, shape.vocab, (shape.n_prompts, 5)).astype(np.int32)).to(pair.dev)
+    got = []
+    for _ in range(3):
+        tok = torch.zeros((shape.n_prompts, shape.n_nodes), dtype=torch.int32, device=pair.dev)
+        dq = torch.zeros((shape.n_prompts, shape.n_nodes + 1, shape.v_eff), dtype=torch.float32, device=pair.dev)
+        dctx.vvs_draft(pair.ctx, shape.n_nodes, parent, None, 5, recent, 0, None, tok, dq)
+        torch.cuda.synchronize()
+        got.append((tok.cpu().numpy(), dq.cpu().numpy()))
+    for tok, dq in got[1:]:
+        assert np.array_equal(tok, got[0][0]) and np.array_equal(dq, got[0][1])
+    dctx.close()
+    pair.close()
