@@ -36,6 +36,9 @@ GemmPlan plan_gemm(const Ctx* c, int M, int N, int K) {
     const int t128 = ((M + 63) / 64) * (N / 128);
     if (t128 >= 160 && t128 <= 256) { p.bn = 128; return p; }
   }
+  // up to 32 rows (weight streaming): 32 x 128 tiles under the same condition - with 64-column tiles such an
+  // N gives between one and two workgroups per CU, and the kernel lasts as long as the CUs that got two
+  if (p.bm == 32 && N % 128 == 0 && N / 128 >= 160 && N / 128 <= 256) { p.bn = 128; return p; }
   const int tiles = ((M + p.bm - 1) / p.bm) * (N / 64);
   const int kb = K / 16;
   int splits = 1;

@@ -337,7 +337,7 @@ __global__ void k_rope_kv(const float* __restrict__ qkv, int splits, size_t spli
   if (img >= 0) { gr = min(img / pos.grid_w, rope_pos - 1); gc = img % pos.grid_w; }
   const bool in_cache = slot >= 0 && slot < S_cap;
   const size_t n3 = (size_t)3 * d;
-  for (int i = threadIdx.x; i < (d >> 1); i += blockDim.x) {
+  for (int i = blockIdx.y * blockDim.x + threadIdx.x; i < (d >> 1); i += gridDim.y * blockDim.x) {   // one pair per thread
     const int e0 = 2 * i, hd = e0 / dh, e = e0 % dh;
     const int seg = e / half, ip = (e % half) >> 1;
     float cs = 1.f, sn = 0.f;
@@ -573,7 +573,7 @@ static void forward_t(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, 
     } else {
       sp = run_gemm(c, h, lw + c->p.wqkv, go, M, 3 * d, d, true, s);
       Timed timed(c, VVS_K_ELEMENTWISE, s);
-      hipLaunchKernelGGL(k_rope_kv<T>, dim3(M), dim3(256), 0, s, go, sp, (size_t)M * 3 * d, q, kc, vc, rope, tree, pos, Tq, d, c->dh,
+      hipLaunchKernelGGL(k_rope_kv<T>, dim3(M, ((d >> 1) + 255) / 256), dim3(256), 0, s, go, sp, (size_t)M * 3 * d, q, kc, vc, rope, tree, pos, Tq, d, c->dh,
                          c->kv_row_stride, c->kv_head_stride, c->S_cap, c->rope_pos);
     }
     if (c->cfg.dtype == VVS_BF16) {

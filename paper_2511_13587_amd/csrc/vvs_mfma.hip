@@ -636,7 +636,8 @@ static void gemm_dispatch(const bf16_t* A, const bf16_t* W, float* C, int M, int
   if constexpr (EPI != EPI_RESID) {
     if (p.bm == 128 && p.bn == 128) { launch_gemm_shared<2, 2, 6, EPI>(A, W, C, M, N, K, ep, s); return; }
   }
-  if (p.bm == 32) launch_gemm_direct<1, 2, 8, EPI>(A, W, C, M, N, K, p.splits, ep, s);
+  if (p.bm == 32 && p.bn == 128) launch_gemm_direct<1, 4, 4, EPI>(A, W, C, M, N, K, p.splits, ep, s);
+  else if (p.bm == 32) launch_gemm_direct<1, 2, 8, EPI>(A, W, C, M, N, K, p.splits, ep, s);
   else if (p.bn == 128) launch_gemm_direct<2, 4, 4, EPI>(A, W, C, M, N, K, p.splits, ep, s);
   else launch_gemm_direct<2, 2, 6, EPI>(A, W, C, M, N, K, p.splits, ep, s);
 }

@@ -20,7 +20,7 @@ def bf16_round(a):
 
 
 # ------------------------------------------------------------------------------------------------ GEMM unit parity
-@pytest.mark.parametrize("m,n,k", [(48, 2304, 768), (432, 1280, 3456), (100, 128, 64), (1, 64, 64), (27, 3840, 1280),
+@pytest.mark.parametrize("m,n,k", [(48, 2304, 768), (432, 1280, 3456), (100, 128, 64), (1, 64, 64), (27, 3840, 1280), (28, 22016, 256),
                                    (300, 6912, 1280), (1024, 3840, 1280),
                                    (432, 6912, 1280), (257, 20480, 64), (193, 20480, 448)])
 def test_gemm_bf16_mfma(gc, m, n, k):
