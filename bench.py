@@ -301,11 +301,12 @@ def main():
         "value": value, "unit": "verified tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if shape.dtype == synth.DTYPE_BF16 else "f32", "data": "synthetic",
-        "config": {"workload": shape.name, "layers": shape.n_layers, "d_model": shape.d_model, "prompts": B,
-                   "rows": shape.n_rows, "draft_nodes": N, "tree_depth": int(synth.node_depths(parent).max()),
+        "config": {"workload": shape.name, "prompts": B, "rows": shape.n_rows, "draft_nodes": N, "tree_depth": int(synth.node_depths(parent).max()),
                    "cache_len_mean": S_mean, "mode": args.mode, "draft_noise_std": args.draft_noise,
                    "launch": "hip graph replay" if args.graph else "eager", "post_verified_tokens": args.post,
                    "draft_sets": n_sets},
+        "shape": {"layers": shape.n_layers, "d_model": shape.d_model, "heads": shape.n_heads, "d_ff": shape.d_ff,
+                  "allowed_ids": shape.v_eff, "grid": [shape.grid_h, shape.grid_w], "prefix_len": shape.prefix_len},
         "verify_latency_ms": ms_per_step, "mean_accept_len": float(accept.mean()),
         "emitted_tokens_per_step": emitted, "scored_draft_tokens_per_s": B * N / (ms_per_step * 1e-3),
         "whole_pass": {"algorithmic_GB": total_bytes / 1e9, "algorithmic_TFLOP": (cnt["gemm_flops"] + cnt["attn_flops"]) / 1e12,
