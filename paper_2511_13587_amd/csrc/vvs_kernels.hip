@@ -533,8 +533,11 @@ static void forward_t(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, 
                       bool from_din) {
   const int d = c->d, F = c->F, M = c->R * Tq;
   const bool folded = sizeof(T) == 2;          // bf16: norm gains are folded into the packed weights
-  // a drafter runs one block per level of its tree: fewer launches matter more there than full tiles
-  if (folded && (c->cfg.draft_input || ((M + 63) / 64) * (d / 64) >= 128)) {
+  // 5 kernels per layer when the projections fill the chip without a K split - or when a layer's weights are so
+  // small (below ~48 MB: the B and XL widths, a drafter) that a launch costs more than streaming them: then fewer
+  // launches win even with few tiles.  Wide layers with few rows stream their weights through K-split GEMMs.
+  const size_t layer_weight_bytes = sizeof(T) * ((size_t)4 * d * d + (size_t)3 * d * F);
+  if (folded && (((M + 63) / 64) * (d / 64) >= 128 || layer_weight_bytes <= ((size_t)48 << 20))) {
     forward_fused(c, tree, pos, Tq, d_tokens_bt, pc, pu, chunk_start, forced, n_forced, logits_mode, s, from_din);
     return;
   }

@@ -330,9 +330,10 @@ def test_drafting_edges_fp32(gc):
 
 
 def test_7b_like_slice_drafting_bf16(gc):
-    """Config 4's structure at reduced width (head size 128, 65536-id vocabulary, ids 4096 .. 12287 allowed):
-    the drafted ids carry the slice offset and the distributions cover the slice only."""
-    base = synth.SEVEN_B.replace(n_layers=2, d_model=1024, n_heads=8, d_ff=2816)
+    """Config 4's structure at half its width (head size 128, 65536-id vocabulary, ids 4096 .. 12287 allowed):
+    the drafted ids carry the slice offset and the distributions cover the slice only; a drafter block this
+    wide (101 MB) takes the K-split plan with separate norm / rotary kernels."""
+    base = synth.SEVEN_B.replace(n_layers=2, d_model=2048, n_heads=16, d_ff=5504)
     parent = np.array([0, 0, 1, 1, 2, 3], dtype=np.int32)
     pair = gc.Pair(base, shadow=True)
     side = DraftSide(gc, pair, max_block=2 + 3, shadow=True)

@@ -179,8 +179,9 @@ def test_xl_tree_reduced_depth(gc):
 
 def test_7b_slice_reduced(gc):
     """Config 4's structure (head size 128, 65536-id vocabulary with an 8192-id slice, chain K = 6)
-    at reduced width and depth."""
-    shape = synth.SEVEN_B.replace(n_layers=2, d_model=1024, n_heads=8, d_ff=2816)
+    at half its width and 2 layers: wide enough (101 MB of weights per layer) for the plan that streams
+    the weights through K-split GEMMs with separate norm / rotary kernels."""
+    shape = synth.SEVEN_B.replace(n_layers=2, d_model=2048, n_heads=16, d_ff=5504)
     for n_forced in (0, 40):
         stats = run_bf16_case(gc, shape, n_forced=n_forced, calls=2)
         print("7b-like:", n_forced, stats)
