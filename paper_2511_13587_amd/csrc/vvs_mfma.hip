@@ -483,8 +483,8 @@ __global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ A
 // every MFMA group runs on fragments requested one group earlier.  One barrier per stage: it orders
 // the LDS writes of stage s+2 before their reads in iteration s+1 and the reads of stage s before the
 // slot is overwritten in iteration s+1.  The epilogues are the same as above with a single partial tile.
-template <int WM, int WN, int D, int EPI>
-__global__ __launch_bounds__(256) void k_gemm_shared(const uint4* __restrict__ Ap, const uint4* __restrict__ Wp, float* __restrict__ C,
+template <int WM, int WN, int D, int EPI, int OCC = 1>
+__global__ __launch_bounds__(256, OCC) void k_gemm_shared(const uint4* __restrict__ Ap, const uint4* __restrict__ Wp, float* __restrict__ C,
                                                      int M, int N, int K, const GemmEpi ep) {
   constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32, LDC = BN + 4;
   constexpr int NA = 2 * (BM / 32), NBLK = NA + 2 * (BN / 32), PER = NBLK / 4;   // 1 KiB blocks per stage; per wave
@@ -610,14 +610,14 @@ __global__ __launch_bounds__(256) void k_gemm_shared(const uint4* __restrict__ A
   VVS_PHASE_MARK(4);
 }
 
-template <int WM, int WN, int D, int EPI>
+template <int WM, int WN, int D, int EPI, int OCC = 1>
 static void launch_gemm_shared(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, const GemmEpi& ep, hipStream_t s) {
   constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32;
   constexpr size_t lds_tile = (size_t)BM * (BN + 4) * sizeof(float), lds_stage = (size_t)3 * (2 * (BM + BN) / 32) * 1024;
   constexpr size_t lds = lds_tile > lds_stage ? lds_tile : lds_stage;
-  allow_dynamic_lds(reinterpret_cast<const void*>(&k_gemm_shared<WM, WN, D, EPI>), lds);
+  allow_dynamic_lds(reinterpret_cast<const void*>(&k_gemm_shared<WM, WN, D, EPI, OCC>), lds);
   dim3 grid((N / BN) * ((M + BM - 1) / BM), 1, 1);
-  hipLaunchKernelGGL((k_gemm_shared<WM, WN, D, EPI>), grid, dim3(256), lds, s, (const uint4*)A, (const uint4*)W, C, M, N, K, ep);
+  hipLaunchKernelGGL((k_gemm_shared<WM, WN, D, EPI, OCC>), grid, dim3(256), lds, s, (const uint4*)A, (const uint4*)W, C, M, N, K, ep);
 }
 
 template <int TM, int TN, int D, int EPI>
@@ -633,6 +633,11 @@ static void launch_gemm_direct(const bf16_t* A, const bf16_t* W, float* C, int M
 
 template <int EPI>
 static void gemm_dispatch(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, GemmPlan p, const GemmEpi& ep, hipStream_t s) {
+  if constexpr (EPI == EPI_PARTIAL || EPI == EPI_SWIGLU) {
+    // many tiles per CU: two workgroups share a CU (half the registers each, 3 stages ahead instead of 6), so that
+    // one's barrier and LDS waits are covered by the other's MFMAs
+    if (p.bm == 128 && p.bn == 128 && ((M + 127) / 128) * (N / 128) >= 512) { launch_gemm_shared<2, 2, 3, EPI, 2>(A, W, C, M, N, K, ep, s); return; }
+  }
   if constexpr (EPI != EPI_RESID) {
     if (p.bm == 128 && p.bn == 128) { launch_gemm_shared<2, 2, 6, EPI>(A, W, C, M, N, K, ep, s); return; }
   }

@@ -22,7 +22,7 @@ def bf16_round(a):
 # ------------------------------------------------------------------------------------------------ GEMM unit parity
 @pytest.mark.parametrize("m,n,k", [(48, 2304, 768), (432, 1280, 3456), (100, 128, 64), (1, 64, 64), (27, 3840, 1280), (28, 22016, 256),
                                    (300, 6912, 1280), (1024, 3840, 1280),
-                                   (432, 6912, 1280), (257, 20480, 64), (193, 20480, 448)])
+                                   (432, 6912, 1280), (257, 20480, 64), (193, 20480, 448), (1000, 8192, 192)])
 def test_gemm_bf16_mfma(gc, m, n, k):
     """Spans every tile shape and split-K plan of both GEMM kernels (per-wave operands; operands shared
     through LDS: full groups of stages, tail stages only, both), ragged M, one row."""
