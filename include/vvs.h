@@ -231,7 +231,8 @@ vvs_status vvs_path_similarity(vvs_ctx* ctx, int32_t n_nodes, const int32_t* h_p
 
 /* One drafting call (Algorithm 2: "f_t <- Retrieve(C, a); C_t <- M_D(f_t, a)"; Section 3, "Stale
  * Feature Reusability"; Section 4.1): the drafter - a context created with draft_input = 1, one or more
- * decoder blocks of the target's kind, the same d_model, dtype, B, id slice and grid as the target -
+ * decoder blocks of the target's kind, the same d_model, dtype, B, id slice, grid and kind of feature
+ * (feature_pre_norm) as the target -
  * is conditioned on the n_ctx most recent features of the target's token-level feature cache paired,
  * by recency, with the n_ctx most recent tokens of the sequence, and fills a candidate tree of a fixed
  * shape level by level: node j >= 1 gets the input W_fc [embedding of its token ; feature the drafter

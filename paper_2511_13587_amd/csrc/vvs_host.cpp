@@ -584,6 +584,8 @@ vvs_status vvs_draft(vvs_ctx* drafter, vvs_ctx* target, int32_t n_nodes, const i
   if (a.d_model != b.d_model || a.dtype != b.dtype || a.n_prompts != b.n_prompts || a.vocab != b.vocab || a.logit_lo != b.logit_lo ||
       a.logit_hi != b.logit_hi || a.grid_h != b.grid_h || a.grid_w != b.grid_w)
     return fail(&dr->err, VVS_EINVAL, "draft: drafter and target differ in d_model, dtype, prompts, vocabulary slice or grid");
+  if (a.feature_pre_norm != b.feature_pre_norm)
+    return fail(&dr->err, VVS_EINVAL, "draft: drafter and target keep different kinds of feature (feature_pre_norm)");
   if (n_nodes < 1) return fail(&dr->err, VVS_EINVAL, "draft: n_nodes < 1");
   if (n_ctx < 1 || n_ctx > b.feature_slots) return fail(&dr->err, VVS_EINVAL, "draft: n_ctx must be in [1, feature_slots of the target]");
   if (n_unverified < 0 || n_unverified > VVS_MAX_FEATURE_SLOTS) return fail(&dr->err, VVS_EINVAL, "draft: n_unverified out of range");

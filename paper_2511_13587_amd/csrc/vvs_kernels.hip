@@ -570,6 +570,9 @@ static void forward_t(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, 
     }
     int sp;
     GemmPlan pq = plan_gemm(c, M, 3 * d, d);
+    // with 160+ tiles an unsplit projection streams its weights as fast as a split one, and its epilogue
+    // does the rotary embedding and the cache write: one kernel less
+    if (pq.splits > 1 && ((M + pq.bm - 1) / pq.bm) * (3 * d / pq.bn) >= 160) pq.splits = 1;
     if (c->cfg.dtype == VVS_BF16 && pq.splits == 1) {
       Timed timed(c, VVS_K_GEMM, s);           // projection + rotary + cache write in one kernel
       mfma_gemm_qkv(c, l, (const bf16_t*)h, (const bf16_t*)(lw + c->p.wqkv), nullptr, tree, pos, Tq, pq, s);
