@@ -215,3 +215,63 @@ def test_rerun_is_bit_identical_bf16(gc):
         assert np.array_equal(tok, got[0][0]) and np.array_equal(dq, got[0][1])
     dctx.close()
     pair.close()
+
+
+def test_hip_graph_replay_of_a_whole_step_bf16(gc):
+    """A step (roll back the state, draft, verify, commit) is captured once into a HIP graph - the library only
+    launches kernels, it records no memset or copy node - and replayed several times with eager work and
+    synchronisations in between; every replay must reproduce the eager results bit for bit."""
+    shape = synth.XL_TREE.replace(n_layers=2)
+    parent = synth.tree_parents(shape.tree_widths, shape.n_nodes)
+    mask = synth.ancestor_mask(parent)
+    N, B = shape.n_nodes, shape.n_prompts
+    pair = gc.Pair(shape, with_oracle=False)
+    pair.prefill(n_forced=45, run_oracle=False)
+    vb = gc.vb
+    dev = pair.dev
+    n_exp = len(set(int(p) for p in parent if p > 0))
+    dctx = vb.Context(vb.make_config(shape.replace(n_layers=1), max_nodes=1 + n_exp - 1, feature_slots=0, draft_input=1))
+    dctx.load_weights_from_host(synth.make_drafter_weights(shape, pair.w), synth.drafter_weight_names())
+    state = torch.from_numpy(pair.ctx.vvs_read_state()).to(dev)
+    recent = torch.from_numpy(pair.ctx.vvs_read_state()[2:3].T.copy()).to(dev)          # the pending tokens
+    u = torch.from_numpy(synth.make_uniforms(shape, N, 0)).to(dev)
+    tok = torch.zeros((B, N), dtype=torch.int32, device=dev)
+    dq = torch.zeros((B, N + 1, shape.v_eff), dtype=torch.float32, device=dev)
+
+    def step():
+        pair.ctx.vvs_set_state(state)
+        dctx.vvs_draft(pair.ctx, N, parent, None, 1, recent, 0, None, tok, dq)
+        pair.ctx.vvs_verify(N, parent, mask, tok, dq, u, 0, pair.accept_len, pair.path, pair.next_token)
+        pair.ctx.vvs_kv_commit()
+
+    def snapshot():
+        torch.cuda.synchronize()
+        k, v = pair.ctx.vvs_debug_kv(1, 3, int(state[0, 1].item()) + 4)
+        return [t.cpu().numpy().copy() for t in (tok, dq, pair.accept_len, pair.path, pair.next_token, k, v)] + [pair.ctx.vvs_read_state()]
+
+    step()          # the first commit replaces the prefill's feature by the committed path's: from the second
+    step()          # step on, the newest cached feature - the drafter's input here - is the same every time
+    want = snapshot()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                                          # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for i in range(3):
+        tok.fill_(-1)
+        dq.fill_(0.5)
+        pair.accept_len.fill_(77)
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        for a, b in zip(got, want):
+            assert np.array_equal(a, b), f"replay {i} differs from the eager step"
+        step()                                                          # eager work between the replays
+        for a, b in zip(snapshot(), want):
+            assert np.array_equal(a, b)
+    dctx.close()
+    pair.close()
