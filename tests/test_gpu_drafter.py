@@ -356,3 +356,23 @@ def test_7b_like_slice_drafting_bf16(gc):
           f"{c1} free-run distributions, {s1} subtrees after near ties")
     side.close()
     pair.close()
+
+
+def test_drafting_with_a_wide_id_slice_fp32(gc):
+    """More than 16384 allowed ids: the selection kernel that keeps the mixed logits in memory instead of in
+    registers.  Same checks as the other fp32 cases."""
+    shape = synth.TINY.replace(n_nodes=7, n_prompts=2, vocab=20480, logit_lo=0, logit_hi=20480)
+    parent = np.array([0, 0, 0, 1, 1, 2, 4], dtype=np.int32)
+    pair = gc.Pair(shape, gain_jitter=0.1)
+    side = DraftSide(gc, pair, max_block=1 + 4, std=0.05)
+    first, ofirst, _ = pair.prefill()
+    assert (first == ofirst).all()
+    tok, q, otok, oq = side.draft(parent, 1, first[:, None])
+    c, s = side.compare(parent, tok, q, otok, oq, gc.mixed_tol(shape), "wide slice")
+    assert c >= 6 and np.array_equal(tok, otok)
+    u = synth.make_uniforms(shape, len(parent), 0)
+    out, oout = pair.verify(parent, otok, oq.astype(np.float32), u, mask=synth.ancestor_mask(parent))
+    gc.check_logits(pair, "wide slice verify")
+    gc.decisions_match(out, oout, pair.oracle.traces, shape.logit_lo)
+    side.close()
+    pair.close()
