@@ -31,30 +31,25 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_correlated_draft(ctx, vb, synth, shape, parent, torch, noise_std, bufs, n_post=0, draft_index=0):
-    """Synthetic drafter of tunable quality.  Level by level: run a verify pass, read the target's
-    mixed logits at the nodes of depth k, let the draft distribution of those nodes be the normalised
-    exponential of (target logits + Gaussian noise), and draw their children from it without
-    replacement.  After depth passes every internal node has a draft distribution that resembles the
-    target's, as a trained drafter's would.  Not timed."""
-    dev = ctx.device
-    B, N, V = shape.n_prompts, shape.n_nodes, shape.v_eff
+def correlated_draft(synth, shape, parent, noise_std, draft_index, mixed_logits_of):
+    """Synthetic drafter of tunable quality.  Level by level: get the target's mixed logits for the current
+    draft (mixed_logits_of(q, toks, u) -> [B, T, V_eff]: one verify pass of whoever is asked - the library on
+    the GPU, or the checker for its own baseline), let the draft distribution of the nodes of depth k be the
+    normalised exponential of (target logits + Gaussian noise), and draw their children from it without
+    replacement.  After depth passes every internal node has a draft distribution that resembles the target's,
+    as a trained drafter's would.  Not timed."""
+    B, N, V = mixed_logits_of.n_prompts, shape.n_nodes, shape.v_eff
     T = N + 1
     depth = synth.node_depths(parent)
     rng = np.random.default_rng(shape.seed + 99 + 7919 * draft_index)
     q = np.full((B, T, V), 1.0 / V, dtype=np.float32)
     toks = rng.integers(shape.logit_lo, shape.logit_hi, size=(B, N)).astype(np.int32)
-    u = synth.make_uniforms(shape, N, draft_index)
-    state = bufs["state"]
+    u = synth.make_uniforms(shape, N, draft_index)[:B]
     children = {}
     for j in range(1, T):
         children.setdefault(int(parent[j - 1]), []).append(j)
     for level in range(int(depth.max())):
-        ctx.vvs_set_state(state)
-        ctx.vvs_verify_post(N, n_post, parent, None, torch.from_numpy(toks).to(dev), torch.from_numpy(q).to(dev),
-                            torch.from_numpy(u).to(dev), vb.VVS_STRICT, bufs["a"], bufs["path"], bufs["next"])
-        _, mixed, _ = ctx.vvs_debug_logits()
-        mixed = mixed.cpu().numpy()
+        mixed = mixed_logits_of(q, toks, u)
         for j in [j for j in range(T) if depth[j] == level and j in children]:
             lg = mixed[:, j, :].astype(np.float64) + noise_std * rng.standard_normal((B, V))
             lg -= lg.max(axis=1, keepdims=True)
@@ -69,8 +64,25 @@ def build_correlated_draft(ctx, vb, synth, shape, parent, torch, noise_std, bufs
                 picks = rng.choice(V, size=len(kids), replace=False, p=w) if nz >= len(kids) else rng.choice(V, size=len(kids), replace=False)
                 for c, x in zip(kids, picks):
                     toks[b, c - 1] = shape.logit_lo + int(x)
-    ctx.vvs_set_state(state)
     return q, toks, u
+
+
+def build_correlated_draft(ctx, vb, synth, shape, parent, torch, noise_std, bufs, n_post=0, draft_index=0):
+    """correlated_draft() with the library's own verify pass as the source of the target logits."""
+    dev = ctx.device
+    state = bufs["state"]
+
+    def gpu_mixed(q, toks, u):
+        ctx.vvs_set_state(state)
+        ctx.vvs_verify_post(shape.n_nodes, n_post, parent, None, torch.from_numpy(toks).to(dev), torch.from_numpy(q).to(dev),
+                            torch.from_numpy(u).to(dev), vb.VVS_STRICT, bufs["a"], bufs["path"], bufs["next"])
+        _, mixed, _ = ctx.vvs_debug_logits()
+        return mixed.cpu().numpy()
+
+    gpu_mixed.n_prompts = shape.n_prompts
+    out = correlated_draft(synth, shape, parent, noise_std, draft_index, gpu_mixed)
+    ctx.vvs_set_state(state)
+    return out
 
 
 def algorithmic_counts(shape, S_mean):
@@ -88,11 +100,12 @@ def algorithmic_counts(shape, S_mean):
                 attn_flops=attn_flops, M=M)
 
 
-def cpu_baseline(shape, weights, synth, n_forced, u_first, parent, q, toks, u, mode, nbr, log_fn, n_sample=2, reps=5, n_post=0):
+def cpu_baseline(shape, weights, synth, n_forced, u_first, parent, noise_std, mode, nbr, log_fn, n_sample=2, reps=5, n_post=0):
     """The CPU checker as it stands, timed on a bounded sample of the same workload: the first
-    n_sample prompts (2 CFG rows each) at the same cache length, with the same tree, draft
-    distributions, drafted tokens and uniforms as the GPU run.  The prefill that builds the cache is
-    not timed; verify is timed `reps` times (it does not change the cache), commit once."""
+    n_sample prompts (2 CFG rows each) at the same cache length, with the same tree and a draft of the
+    same recipe (draft set 0), built from the checker's OWN target logits - nothing the checker is given
+    comes from the GPU library.  The prefill that builds the cache and the passes that build the draft
+    are not timed; verify is timed `reps` times (it does not change the cache), commit once."""
     from oracle import vvs_oracle as vo
     try:
         from threadpoolctl import threadpool_info
@@ -110,8 +123,17 @@ def cpu_baseline(shape, weights, synth, n_forced, u_first, parent, q, toks, u, m
     o.prefill(pc[:n_sample], pu, None if forced is None else forced[:n_sample], u_first[:n_sample])
     log_fn(f"cpu baseline: building the cache of the sample took {time.perf_counter() - t0:.1f} s (not counted)")
     t0 = time.perf_counter()
+
+    def cpu_mixed(q_, toks_, u_):
+        o.verify(parent, toks_, q_, u_, 0, n_post=n_post)
+        return o.mixed_logits
+
+    cpu_mixed.n_prompts = n_sample
+    q, toks, u = correlated_draft(synth, s1, parent, noise_std, 0, cpu_mixed)
+    log_fn(f"cpu baseline: building the draft from the checker's own logits took {time.perf_counter() - t0:.1f} s (not counted)")
+    t0 = time.perf_counter()
     for _ in range(reps):
-        a, _, _ = o.verify(parent, toks[:n_sample], q[:n_sample], u[:n_sample], mode, n_post=n_post)
+        a, _, _ = o.verify(parent, toks, q, u, mode, n_post=n_post)
     t_verify = (time.perf_counter() - t0) / reps
     t0 = time.perf_counter()
     o.kv_commit()
@@ -119,8 +141,8 @@ def cpu_baseline(shape, weights, synth, n_forced, u_first, parent, q, toks, u, m
     dt = t_verify + t_commit
     emitted = float(a.sum() + len(a))
     return {"value": emitted / dt, "unit": "verified tokens/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{n_sample} of {shape.n_prompts} prompts ({2 * n_sample} CFG rows), same {s1.n_nodes}-node tree, drafts and "
-                      f"uniforms as the GPU run, cache length {s1.prefix_len}+{n_forced}; verify {t_verify:.2f} s (mean of {reps}) + "
+            "sample": f"{n_sample} of {shape.n_prompts} prompts ({2 * n_sample} CFG rows), same {s1.n_nodes}-node tree, a draft of the same "
+                      f"recipe built from the checker's own logits, cache length {s1.prefix_len}+{n_forced}; verify {t_verify:.2f} s (mean of {reps}) + "
                       f"commit {t_commit:.3f} s for {emitted:.0f} emitted / {n_sample * s1.n_nodes} scored draft tokens"}
 
 
@@ -204,8 +226,6 @@ def main():
     for di in range(max(1, args.drafts)):
         q_i, toks_i, u_i = build_correlated_draft(ctx, vb, synth, shape, parent, torch, args.draft_noise, bufs, args.post, di)
         drafts.append((torch.from_numpy(q_i).to(dev), torch.from_numpy(toks_i).to(dev), torch.from_numpy(u_i).to(dev)))
-        if di == 0:
-            q, toks, u = q_i, toks_i, u_i                # the CPU baseline replays draft set 0
     dq, dtoks, du = drafts[0]
     counter = [0]
 
@@ -356,7 +376,7 @@ def main():
     if not args.no_cpu_baseline:
         try:
             nbr_host = synth.make_codebook_neighbours(shape.vocab, shape.relax_k) if shape.relax_k else None
-            out["cpu_baseline"] = cpu_baseline(shape, weights, synth, n_forced, u0_host, parent, q, toks, u, mode, nbr_host, log, n_post=args.post)
+            out["cpu_baseline"] = cpu_baseline(shape, weights, synth, n_forced, u0_host, parent, args.draft_noise, mode, nbr_host, log, n_post=args.post)
         except MemoryError as e:           # pragma: no cover
             out["cpu_baseline"] = {"value": None, "unit": "verified tokens/s", "cores": os.cpu_count(), "kind": "oracle",
                                    "sample": f"failed: {e}"}
