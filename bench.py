@@ -12,6 +12,7 @@ at mid-image cache length.  Prints one JSON line."""
 import argparse
 import dataclasses
 import json
+import re
 import os
 import sys
 import time
@@ -307,11 +308,12 @@ def main():
         ach = bytes_launch / t_launch / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS}
     traffic = None
-    tfile = os.path.join(ROOT, "profiles", f"traffic_{shape.name}.json")
+    tfile = os.path.join(ROOT, "profiles", f"hbm_traffic_{shape.name}.txt")
     if dom == "gemm" and os.path.exists(tfile) and not args.layers and not args.post:
-        # HBM bytes per launch from the committed rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command,
-        # scaled by the same counters' reading for a plain copy kernel
-        traffic = json.load(open(tfile)).get("hbm_bytes_per_launch")
+        # HBM bytes per launch from the committed summary of the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+        # command, scaled by the same counters' reading for a plain copy kernel (its last line)
+        m = re.search(r"HBM traffic per launch \(fetch \+ write\): ([0-9.]+) MB", open(tfile).read())
+        traffic = float(m.group(1)) * 1e6 if m else None
     roof.update(traffic=traffic, kernel=kernel, launches_per_step=n_launch, avg_launch_us=t_launch * 1e6,
                 algorithmic_bytes_per_launch=bytes_launch, algorithmic_flops_per_launch=flops_launch)
     total_bytes = cnt["w_bytes"] + cnt["kv_read"] + cnt["kv_write"] + cnt["q_read"]
