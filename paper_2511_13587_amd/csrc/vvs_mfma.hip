@@ -431,10 +431,13 @@ __global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ A
   // epilogue inputs: requested behind the first operand loads (nothing waits for them before the main loop ends)
   RowScale<BM> rowscale;
   rowscale.load(tile_m, M, ep);
-  pre.start(tile_m, tile_n, M, N, ep);
+  if (EPI != EPI_QKV || nk <= 0) pre.start(tile_m, tile_n, M, N, ep);
   __builtin_amdgcn_sched_barrier(0);
   VVS_PHASE_MARK(1);
   for (int kb = 0; kb < nk; kb += D) {
+    // EPI_QKV: the rotary factors depend on a loaded value (the row's cache length); asking for them after the
+    // first group of k-steps instead of in front of the loop keeps that wait off the path to the first MFMA
+    if (EPI == EPI_QKV && kb == D) pre.start(tile_m, tile_n, M, N, ep);
 #pragma unroll
     for (int i = 0; i < D; ++i) {
       if (kb + i < nk) {
@@ -452,6 +455,7 @@ __global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ A
       __builtin_amdgcn_sched_barrier(0);
     }
   }
+  if (EPI == EPI_QKV && nk > 0 && nk <= D) pre.start(tile_m, tile_n, M, N, ep);   // a K range of a single group
   VVS_PHASE_MARK(2);
   pre.to_lds(s_pos, s_rope, ep);
   rowscale.finish(rs, tile_m, M, ep);
