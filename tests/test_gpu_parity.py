@@ -199,6 +199,28 @@ def test_7b_slice_full_width_one_layer(gc):
     print("7b width L=1 (raw, mixed, prob, floor):", stats)
 
 
+def test_many_rows_prefill_chunk_bf16(gc):
+    """A prefill chunk of 52 rows x 64 tokens = 3328 GEMM rows at the XL width (one layer): several rounds of
+    tiles per CU in every projection, and enough 128 x 128 tiles (1404) for the two-workgroups-per-CU
+    instantiation of gate/up.  Last-position logits against the checker (bound: 3e-2 or three times the
+    checker's own noise), cached K and V of two rows."""
+    shape = synth.XL_TREE.replace(n_layers=1, n_prompts=26, prefix_len=64, n_nodes=4, tree_widths=None)
+    pair = gc.Pair(shape, shadow=True)
+    pair.prefill()
+    raw, _, _ = pair.gpu_logits()
+    err = np.abs(raw[:, 0] - pair.oracle.prefill_logits).max()
+    print("many-row prefill: logit error", err, "floor", pair.floor)
+    assert err <= gc.logit_tol(shape, pair.floor), (err, pair.floor)
+    S = pair.oracle.kv_len(0)
+    for row in (0, 51):
+        k, v = pair.ctx.vvs_debug_kv(0, row, S)
+        ok = pair.oracle.kc[row][0].reshape(S, -1)
+        ov = pair.oracle.vc[row][0].reshape(S, -1)
+        assert np.abs(k.cpu().numpy() - ok).max() < 0.06 * max(1.0, np.abs(ok).max())
+        assert np.abs(v.cpu().numpy() - ov).max() < 0.06 * max(1.0, np.abs(ov).max())
+    pair.close()
+
+
 def test_xl_stress_reduced_depth_relaxed(gc):
     """Config 5's shape (60-node tree, relaxed acceptance with 50 neighbours, delta 0.2), 2 layers,
     4 prompts."""
