@@ -614,6 +614,135 @@ __global__ __launch_bounds__(256, OCC) void k_gemm_shared(const uint4* __restric
   VVS_PHASE_MARK(4);
 }
 
+// The same tile with the stages loaded straight from global memory into LDS (global_load_lds_dwordx4: lane l
+// of a wave writes the 16 bytes it asked for to LDS address M0 + 16 l, which is exactly the packed block
+// layout).  In k_gemm_shared every operand byte crosses the vector registers twice - once on its way from
+// memory to LDS, once as a fragment - and the register file's ports, shared with the MFMA operand reads, are
+// what that kernel's main loop is bound by; here the staging hop is gone, and so are its registers, so NS = 8
+// stages can be in flight in LDS.  The compiler knows nothing of these loads (inline asm): the waits are
+// written out by hand.  Iteration s: request stage s + NS - 1 into the slot stage s - 1 has left; multiply
+// (fragments as in k_gemm_shared); wait until this wave's part of stage s + 2 has landed - loads return in
+// order, so "at most PER * (NS - 3) younger loads outstanding" - and meet the other waves at the barrier.
+__device__ __forceinline__ void lds_dma16(const void* g, uint32_t lds_byte_addr) {
+  const uint32_t a = __builtin_amdgcn_readfirstlane(lds_byte_addr);     // wave-uniform by construction
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(a), "v"(g) : "memory");
+}
+template <int WM, int WN, int NS, int EPI>
+__global__ __launch_bounds__(256) void k_gemm_shared_dma(const uint4* __restrict__ Ap, const uint4* __restrict__ Wp, float* __restrict__ C,
+                                                         int M, int N, int K, const GemmEpi ep) {
+  static_assert(EPI == EPI_PARTIAL || EPI == EPI_SWIGLU, "epilogues without per-row LDS tables");
+  static_assert((NS & (NS - 1)) == 0 && NS >= 4, "slot index by masking");
+  constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32, LDC = BN + 4;
+  constexpr int NA = 2 * (BM / 32), NBLK = NA + 2 * (BN / 32), PER = NBLK / 4;
+  static_assert(NBLK % 4 == 0, "blocks of a stage are dealt to 4 waves");
+  static_assert(PER * (NS - 1) <= 60, "the load counter has 6 bits");
+  extern __shared__ float red[];           // main loop: u32x4 stage[NS][NBLK][64]; afterwards: float [BM][LDC]
+  u32x4* stage = (u32x4*)red;
+  const uint32_t lds_base = (uint32_t)(uintptr_t)stage;
+  VVS_PHASE_MARK(0);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wr = wave >> 1, wc = wave & 1;
+  const int MT = (M + BM - 1) / BM, NT = N / BN;
+  int tile_m, tile_n;
+  {                                        // same XCD-aware order as k_gemm_direct
+    const int id = blockIdx.x, grp = id / (8 * MT), rem = id % (8 * MT);
+    const int cols = min(8, NT - grp * 8);
+    tile_m = rem / cols;
+    tile_n = grp * 8 + rem % cols;
+  }
+  __shared__ float rs[BM];
+  EpiPre<BM, BN, EPI> pre;
+  const int KB = K >> 4, nst = KB >> 1;
+  const int last_rb = (M - 1) >> 5;
+  RowScale<BM> rowscale;                   // the epilogue's inputs first: they are the oldest loads and so never wait behind a stage
+  rowscale.load(tile_m, M, ep);
+  pre.start(tile_m, tile_n, M, N, ep);
+  __builtin_amdgcn_sched_barrier(0);
+  const u32x4* src[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int j = wave + 4 * i;
+    const int rb = j < NA ? min(tile_m * (BM / 32) + (j >> 1), last_rb) : tile_n * (BN / 32) + ((j - NA) >> 1);
+    src[i] = (const u32x4*)(j < NA ? Ap : Wp) + ((size_t)rb * KB + (j & 1)) * 64 + lane;
+  }
+  // stage t -> slot t % NS; stages past the end repeat the last one (never read)
+  auto request = [&](int t) {
+    const size_t kk = (size_t)min(t, nst - 1) * 128;
+    const uint32_t slot = lds_base + (uint32_t)((t & (NS - 1)) * NBLK) * 1024u;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) lds_dma16(src[i] + kk, slot + (uint32_t)(wave + 4 * i) * 1024u);
+  };
+  floatx16 acc[WM][WN];
+#pragma unroll
+  for (int i = 0; i < WM; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+#pragma unroll
+  for (int t = 0; t < NS - 1; ++t) request(t);
+  VVS_PHASE_MARK(1);
+#define VVS_WAIT_STAGES asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PER * (NS - 3)) : "memory")
+  VVS_WAIT_STAGES;                         // stages 0 and 1 of this wave have landed
+  __syncthreads();                         // ... and everybody else's
+#define VVS_S2F(FA, FB, T, KBO)                                                                                       \
+  {                                                                                                                   \
+    const int sl = ((T) & (NS - 1)) * NBLK;                                                                           \
+    _Pragma("unroll") for (int t = 0; t < WM; ++t)                                                                    \
+        FA[t] = __builtin_bit_cast(bf16x8, stage[(sl + (wr * WM + t) * 2 + (KBO)) * 64 + lane]);                      \
+    _Pragma("unroll") for (int t = 0; t < WN; ++t)                                                                    \
+        FB[t] = __builtin_bit_cast(bf16x8, stage[(sl + NA + (wc * WN + t) * 2 + (KBO)) * 64 + lane]);                 \
+  }
+#define VVS_MMA(FA, FB)                                                                                               \
+  {                                                                                                                   \
+    _Pragma("unroll") for (int ti = 0; ti < WM; ++ti)                                                                 \
+        _Pragma("unroll") for (int tj = 0; tj < WN; ++tj)                                                             \
+            acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FA[ti], FB[tj], acc[ti][tj], 0, 0, 0);              \
+  }
+  bf16x8 fa0[WM], fb0[WN], fa1[WM], fb1[WN];
+  VVS_S2F(fa0, fb0, 0, 0)
+  for (int s = 0; s < nst; ++s) {
+    request(s + NS - 1);                   // into the slot of stage s - 1: everybody finished reading it before the last barrier
+    VVS_S2F(fa1, fb1, s, 1)
+    __builtin_amdgcn_sched_barrier(0);
+    VVS_MMA(fa0, fb0)
+    __builtin_amdgcn_sched_barrier(0);
+    VVS_S2F(fa0, fb0, s + 1, 0)
+    __builtin_amdgcn_sched_barrier(0);
+    VVS_MMA(fa1, fb1)
+    VVS_WAIT_STAGES;                       // this wave's part of stage s + 2
+    __syncthreads();
+  }
+#undef VVS_MMA
+#undef VVS_S2F
+  VVS_PHASE_MARK(2);
+  rowscale.finish(rs, tile_m, M, ep);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the repeated last stages still in flight must land before the tile reuses their LDS
+#undef VVS_WAIT_STAGES
+  __syncthreads();                         // the stage buffers become the output tile
+#pragma unroll
+  for (int i = 0; i < WM; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        red[((wr * WM + i) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * LDC + (wc * WN + j) * 32 + (lane & 31)] = acc[i][j][r];
+  __syncthreads();
+  VVS_PHASE_MARK(3);
+  tile_epilogue<BM, BN, 1, EPI>(red, rs, tile_m, tile_n, M, N, C, ep, pre, nullptr, nullptr);
+  VVS_PHASE_MARK(4);
+}
+
+template <int WM, int WN, int NS, int EPI>
+static void launch_gemm_shared_dma(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, const GemmEpi& ep, hipStream_t s) {
+  constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32;
+  constexpr size_t lds_tile = (size_t)BM * (BN + 4) * sizeof(float), lds_stage = (size_t)NS * (2 * (BM + BN) / 32) * 1024;
+  constexpr size_t lds = lds_tile > lds_stage ? lds_tile : lds_stage;
+  allow_dynamic_lds(reinterpret_cast<const void*>(&k_gemm_shared_dma<WM, WN, NS, EPI>), lds);
+  dim3 grid((N / BN) * ((M + BM - 1) / BM), 1, 1);
+  hipLaunchKernelGGL((k_gemm_shared_dma<WM, WN, NS, EPI>), grid, dim3(256), lds, s, (const uint4*)A, (const uint4*)W, C, M, N, K, ep);
+}
+
 template <int WM, int WN, int D, int EPI, int OCC = 1>
 static void launch_gemm_shared(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, const GemmEpi& ep, hipStream_t s) {
   constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32;
@@ -641,6 +770,10 @@ static void gemm_dispatch(const bf16_t* A, const bf16_t* W, float* C, int M, int
     // many tiles per CU: two workgroups share a CU (half the registers each, 3 stages ahead instead of 6), so that
     // one's barrier and LDS waits are covered by the other's MFMAs
     if (p.bm == 128 && p.bn == 128 && ((M + 127) / 128) * (N / 128) >= 512) { launch_gemm_shared<2, 2, 3, EPI, 2>(A, W, C, M, N, K, ep, s); return; }
+    // a single round of tiles (at most one workgroup per CU): the stages are loaded straight into LDS, 6 in flight.
+    // With more tiles than CUs its 128 KiB of LDS would keep a second workgroup off the CU, and the variants
+    // that stage through registers win (384 tiles: 28 against 32 us; 512 tiles: 33 against 37 us).
+    if (p.bm == 128 && p.bn == 128 && ((M + 127) / 128) * (N / 128) <= 256) { launch_gemm_shared_dma<2, 2, 8, EPI>(A, W, C, M, N, K, ep, s); return; }
   }
   if constexpr (EPI != EPI_RESID) {
     if (p.bm == 128 && p.bn == 128) { launch_gemm_shared<2, 2, 6, EPI>(A, W, C, M, N, K, ep, s); return; }
