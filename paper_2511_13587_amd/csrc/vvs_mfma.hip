@@ -487,8 +487,8 @@ __global__ __launch_bounds__(256) void k_gemm_direct(const uint4* __restrict__ A
 // every MFMA group runs on fragments requested one group earlier.  One barrier per stage: it orders
 // the LDS writes of stage s+2 before their reads in iteration s+1 and the reads of stage s before the
 // slot is overwritten in iteration s+1.  The epilogues are the same as above with a single partial tile.
-template <int WM, int WN, int D, int EPI, int OCC = 1>
-__global__ __launch_bounds__(256, OCC) void k_gemm_shared(const uint4* __restrict__ Ap, const uint4* __restrict__ Wp, float* __restrict__ C,
+template <int WM, int WN, int D, int EPI>
+__global__ __launch_bounds__(256) void k_gemm_shared(const uint4* __restrict__ Ap, const uint4* __restrict__ Wp, float* __restrict__ C,
                                                      int M, int N, int K, const GemmEpi ep) {
   constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32, LDC = BN + 4;
   constexpr int NA = 2 * (BM / 32), NBLK = NA + 2 * (BN / 32), PER = NBLK / 4;   // 1 KiB blocks per stage; per wave
@@ -743,14 +743,14 @@ static void launch_gemm_shared_dma(const bf16_t* A, const bf16_t* W, float* C, i
   hipLaunchKernelGGL((k_gemm_shared_dma<WM, WN, NS, EPI>), grid, dim3(256), lds, s, (const uint4*)A, (const uint4*)W, C, M, N, K, ep);
 }
 
-template <int WM, int WN, int D, int EPI, int OCC = 1>
+template <int WM, int WN, int D, int EPI>
 static void launch_gemm_shared(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, const GemmEpi& ep, hipStream_t s) {
   constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32;
   constexpr size_t lds_tile = (size_t)BM * (BN + 4) * sizeof(float), lds_stage = (size_t)3 * (2 * (BM + BN) / 32) * 1024;
   constexpr size_t lds = lds_tile > lds_stage ? lds_tile : lds_stage;
-  allow_dynamic_lds(reinterpret_cast<const void*>(&k_gemm_shared<WM, WN, D, EPI, OCC>), lds);
+  allow_dynamic_lds(reinterpret_cast<const void*>(&k_gemm_shared<WM, WN, D, EPI>), lds);
   dim3 grid((N / BN) * ((M + BM - 1) / BM), 1, 1);
-  hipLaunchKernelGGL((k_gemm_shared<WM, WN, D, EPI, OCC>), grid, dim3(256), lds, s, (const uint4*)A, (const uint4*)W, C, M, N, K, ep);
+  hipLaunchKernelGGL((k_gemm_shared<WM, WN, D, EPI>), grid, dim3(256), lds, s, (const uint4*)A, (const uint4*)W, C, M, N, K, ep);
 }
 
 template <int TM, int TN, int D, int EPI>
@@ -767,13 +767,13 @@ static void launch_gemm_direct(const bf16_t* A, const bf16_t* W, float* C, int M
 template <int EPI>
 static void gemm_dispatch(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, GemmPlan p, const GemmEpi& ep, hipStream_t s) {
   if constexpr (EPI == EPI_PARTIAL || EPI == EPI_SWIGLU) {
-    // many tiles per CU: two workgroups share a CU (half the registers each, 3 stages ahead instead of 6), so that
-    // one's barrier and LDS waits are covered by the other's MFMAs
-    if (p.bm == 128 && p.bn == 128 && ((M + 127) / 128) * (N / 128) >= 512) { launch_gemm_shared<2, 2, 3, EPI, 2>(A, W, C, M, N, K, ep, s); return; }
-    // a single round of tiles (at most one workgroup per CU): the stages are loaded straight into LDS, 6 in flight.
-    // With more tiles than CUs its 128 KiB of LDS would keep a second workgroup off the CU, and the variants
-    // that stage through registers win (384 tiles: 28 against 32 us; 512 tiles: 33 against 37 us).
-    if (p.bm == 128 && p.bn == 128 && ((M + 127) / 128) * (N / 128) <= 256) { launch_gemm_shared_dma<2, 2, 8, EPI>(A, W, C, M, N, K, ep, s); return; }
+    // the stages are loaded straight into LDS.  A single round of tiles (at most one workgroup per CU): 8 slots, 6
+    // stages in flight.  Two or more full rounds: 4 slots, so that the LDS (the 68 KB of the output tile) lets two
+    // workgroups share a CU and cover each other's barrier waits.  In between (257 .. 511 tiles) the variant that
+    // stages through registers is the faster one (384 tiles: 28 against 32 us).
+    const int tiles = ((M + 127) / 128) * (N / 128);
+    if (p.bm == 128 && p.bn == 128 && tiles <= 256) { launch_gemm_shared_dma<2, 2, 8, EPI>(A, W, C, M, N, K, ep, s); return; }
+    if (p.bm == 128 && p.bn == 128 && tiles >= 512) { launch_gemm_shared_dma<2, 2, 4, EPI>(A, W, C, M, N, K, ep, s); return; }
   }
   if constexpr (EPI != EPI_RESID) {
     if (p.bm == 128 && p.bn == 128) { launch_gemm_shared<2, 2, 6, EPI>(A, W, C, M, N, K, ep, s); return; }
