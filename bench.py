@@ -168,6 +168,8 @@ def main():
                     help="post verification: this many unverified tokens of a previous verification-free step ride in front of the "
                          "draft tree (vvs_verify_post); 0 = the plain verify pass of the headline workload")
     ap.add_argument("--no-drafter", action="store_true", help="leave out the separate timing of the draft side (vvs_draft)")
+    ap.add_argument("--norm-mode", choices=["auto", "separate"], default="auto",
+                    help="vvs_config.norm_mode: separate = always the normalisation kernels that round where the definition does")
     ap.add_argument("--layers", type=int, default=0, help="override depth (debugging only; the result is then not the named workload)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -191,7 +193,7 @@ def main():
     t0 = time.perf_counter()
     weights = synth.make_weights(shape)
     log(f"weights generated in {time.perf_counter() - t0:.1f} s")
-    ctx = vb.Context(vb.make_config(shape))
+    ctx = vb.Context(vb.make_config(shape, norm_mode=vb.VVS_NORM_SEPARATE if args.norm_mode == "separate" else vb.VVS_NORM_AUTO))
     ctx.load_weights_from_host(weights, synth.weight_names(shape))
     dev = ctx.device
     if shape.relax_k:
@@ -326,7 +328,7 @@ def main():
         "config": {"workload": shape.name, "prompts": B, "rows": shape.n_rows, "draft_nodes": N, "tree_depth": int(synth.node_depths(parent).max()),
                    "cache_len_mean": S_mean, "mode": args.mode, "draft_noise_std": args.draft_noise,
                    "launch": "hip graph replay" if args.graph else "eager", "post_verified_tokens": args.post,
-                   "draft_sets": n_sets},
+                   "draft_sets": n_sets, "layer_plan": "fused (5 kernels)" if ctx.vvs_plan_is_fused(N + 1) else "separate normalisation kernels"},
         "shape": {"layers": shape.n_layers, "d_model": shape.d_model, "heads": shape.n_heads, "d_ff": shape.d_ff,
                   "allowed_ids": shape.v_eff, "grid": [shape.grid_h, shape.grid_w], "prefix_len": shape.prefix_len},
         "verify_latency_ms": ms_per_step, "mean_accept_len": float(accept.mean()),

@@ -79,7 +79,18 @@ typedef struct {
                                     1: a drafter context for vvs_draft: the input of a token is
                                     W_fc [embedding ; feature], and the weight list ends with one
                                     more tensor fc [2 d, d] */
+  int32_t norm_mode;             /* bf16 contexts, where the output of an RMSNorm is rounded to bf16:
+                                    VVS_NORM_AUTO: the library chooses per call - separate
+                                      normalisation kernels (below), or, where that is faster, the
+                                      fused layer: the operand of the projection behind a norm is
+                                      bf16(x g) and the row factor rsqrt(mean x^2 + eps) multiplies the
+                                      fp32 result of the projection (equal in exact arithmetic, a
+                                      different rounding of the same operand);
+                                    VVS_NORM_SEPARATE: always separate normalisation kernels, which
+                                      round bf16(x * rsqrt(mean x^2 + eps) * g), the definition's own
+                                      rounding point (more launches per layer) */
 } vvs_config;
+enum { VVS_NORM_AUTO = 0, VVS_NORM_SEPARATE = 1 };
 #define VVS_MAX_FEATURE_SLOTS 8
 
 /* Sizes in bytes of the three device buffers a context needs.  VVS_ESIZE if the shape is not
@@ -260,6 +271,11 @@ vvs_status vvs_draft(vvs_ctx* drafter, vvs_ctx* target, int32_t n_nodes, const i
                      const uint8_t* h_tree_mask, int32_t n_ctx, const int32_t* d_recent_tokens,
                      int32_t n_unverified, const int32_t* d_given_tokens, int32_t* d_draft_tokens,
                      float* d_draft_probs, vvs_stream s);
+
+/* 1 if a forward over n_tokens query tokens per row (a verify call with n_tokens - 1 draft nodes, or a
+ * prefill chunk) takes the fused layer described at vvs_config.norm_mode, 0 if it runs the separate
+ * normalisation kernels.  Host only; ctx must not be NULL. */
+int32_t vvs_plan_is_fused(const vvs_ctx* ctx, int32_t n_tokens);
 
 /* Per-prompt state: int32 [3, B] out = cached length S_b, emitted image tokens, pending token. */
 vvs_status vvs_read_state(vvs_ctx* ctx, int32_t* d_state, vvs_stream s);

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libvvs.so")
 VVS_OK, VVS_EINVAL, VVS_ESTATE, VVS_ESIZE, VVS_EHIP = 0, -1, -2, -3, -4
 VVS_FP32, VVS_BF16 = 0, 1
 VVS_STRICT, VVS_RELAXED = 0, 1
+VVS_NORM_AUTO, VVS_NORM_SEPARATE = 0, 1
 VVS_MAX_T = 64
 VVS_K_GEMM, VVS_K_ATTENTION, VVS_K_ACCEPT, VVS_K_ELEMENTWISE, VVS_K_COMMIT = range(5)
 
@@ -28,7 +29,8 @@ class VvsConfig(C.Structure):
                                          "max_nodes", "dtype")] + \
                [("cfg_scale", C.c_float), ("rms_eps", C.c_float), ("rope_base", C.c_float),
                 ("relax_k", C.c_int32), ("relax_delta", C.c_float),
-                ("feature_slots", C.c_int32), ("feature_pre_norm", C.c_int32), ("draft_input", C.c_int32)]
+                ("feature_slots", C.c_int32), ("feature_pre_norm", C.c_int32), ("draft_input", C.c_int32),
+                ("norm_mode", C.c_int32)]
 
 
 class VvsError(RuntimeError):
@@ -52,6 +54,7 @@ def _load():
         "vvs_load_weights": (i32, [vp, C.POINTER(vp), i32, vp]),
         "vvs_set_neighbors": (i32, [vp, vp]),
         "vvs_check_tree": (i32, [i32, vp, vp, vp, vp]),
+        "vvs_plan_is_fused": (i32, [vp, i32]),
         "vvs_prefill": (i32, [vp, vp, vp, i32, vp, vp, vp, vp]),
         "vvs_verify": (i32, [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]),
         "vvs_verify_post": (i32, [vp, i32, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]),
@@ -84,13 +87,13 @@ lib, EXPORTS = _load()
 
 
 def make_config(shape, max_nodes: Optional[int] = None, feature_slots: int = 5, feature_pre_norm: int = 0,
-                draft_input: int = 0) -> VvsConfig:
+                draft_input: int = 0, norm_mode: int = 0) -> VvsConfig:
     """vvs_config from a synth.Shape-like object."""
     return VvsConfig(shape.n_layers, shape.d_model, shape.n_heads, shape.d_ff, shape.vocab, shape.logit_lo,
                      shape.logit_hi, shape.grid_h, shape.grid_w, shape.prefix_len, shape.prefix_kind,
                      shape.n_classes, shape.n_prompts, shape.n_nodes if max_nodes is None else max_nodes,
                      shape.dtype, shape.cfg_scale, shape.rms_eps, shape.rope_base, shape.relax_k, shape.relax_delta,
-                     feature_slots, feature_pre_norm, draft_input)
+                     feature_slots, feature_pre_norm, draft_input, norm_mode)
 
 
 def vvs_query_sizes(cfg: VvsConfig):
@@ -284,6 +287,9 @@ class Context:
         self._check(lib.vvs_kv_commit(self.h, _stream()))
 
     # -- inspection ----------------------------------------------------------------------------
+    def vvs_plan_is_fused(self, n_tokens: int) -> bool:
+        return bool(lib.vvs_plan_is_fused(self.h, n_tokens))
+
     def vvs_read_state(self) -> np.ndarray:
         out = torch.empty((3, self.B), dtype=torch.int32, device=self.device)
         self._check(lib.vvs_read_state(self.h, _ptr(out), _stream()))

@@ -396,18 +396,18 @@ __global__ __launch_bounds__(64) void k_walk(const int32_t* __restrict__ node_re
   if (keep) keep[2 * B + b * VVS_MAX_T + i] = v;
 }
 
-void launch_accept(Ctx* c, const TreeDesc& tree, int T, const float* d_logits, const int32_t* d_draft_tokens, const float* d_q,
-                   const float* d_u, int usb, int usj, int uoa, int uot, int mode, bool use_state, int32_t* d_accept_len,
-                   int32_t* d_path, int32_t* d_next, bool keep_outcome, hipStream_t s) {
+static void launch_accept_on(Ctx* c, const TreeDesc& tree, int T, const float* d_logits, const int32_t* d_draft_tokens, const float* d_q,
+                             const float* d_u, int usb, int usj, int uoa, int uot, int mode, bool use_state, int32_t* d_accept_len,
+                             int32_t* d_path, int32_t* d_next, int32_t* keep, float* probs, float* work, int32_t* node_result, hipStream_t s) {
   Timed timed(c, VVS_K_ACCEPT, s);
   AcceptArgs a;
   a.logits = d_logits; a.draft = d_draft_tokens; a.q = d_q; a.u = d_u;
   a.usb = usb; a.usj = usj; a.uoa = uoa; a.uot = uot;
   a.nbr = c->nbr;
   a.n_emitted = use_state ? (const int32_t*)(c->ws + c->w.state) + c->B : nullptr;
-  a.probs = (float*)(c->ws + c->w.probs);
-  a.work = (float*)(c->ws + c->w.pq_work);
-  a.node_result = (int32_t*)(c->ws + c->w.node_result);
+  a.probs = probs;
+  a.work = work;
+  a.node_result = node_result;
   a.T = T; a.veff = c->veff; a.lo = c->lo; a.mode = mode; a.relax_k = c->cfg.relax_k; a.G = c->G;
   a.scale = c->cfg.cfg_scale; a.delta = c->cfg.relax_delta;
   const size_t pq_bytes = (size_t)2 * c->veff * sizeof(float);
@@ -417,8 +417,15 @@ void launch_accept(Ctx* c, const TreeDesc& tree, int T, const float* d_logits, c
   } else {
     hipLaunchKernelGGL(k_accept_node<false>, dim3(T, c->B), dim3(1024), 0, s, a, tree);
   }
-  int32_t* keep = keep_outcome ? (int32_t*)(c->ws + c->w.outcome) : nullptr;
   hipLaunchKernelGGL(k_walk, dim3(c->B), dim3(64), 0, s, (const int32_t*)a.node_result, c->B, d_accept_len, d_path, d_next, keep);
+}
+
+void launch_accept(Ctx* c, const TreeDesc& tree, int T, const float* d_logits, const int32_t* d_draft_tokens, const float* d_q,
+                   const float* d_u, int usb, int usj, int uoa, int uot, int mode, bool use_state, int32_t* d_accept_len,
+                   int32_t* d_path, int32_t* d_next, bool keep_outcome, hipStream_t s) {
+  launch_accept_on(c, tree, T, d_logits, d_draft_tokens, d_q, d_u, usb, usj, uoa, uot, mode, use_state, d_accept_len, d_path, d_next,
+                   keep_outcome ? (int32_t*)(c->ws + c->w.outcome) : nullptr, (float*)(c->ws + c->w.probs), (float*)(c->ws + c->w.pq_work),
+                   (int32_t*)(c->ws + c->w.node_result), s);
 }
 
 __global__ void k_prefill_finish(const int32_t* __restrict__ node_result, int32_t* __restrict__ state, int32_t* __restrict__ first,

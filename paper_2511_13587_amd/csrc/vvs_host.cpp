@@ -51,6 +51,19 @@ GemmPlan plan_gemm(const Ctx* c, int M, int N, int K) {
   return p;
 }
 
+// The fused layer (5 kernels, no separate normalisation) is taken when a layer's weights are so small (below
+// ~48 MB: the B and XL widths, a drafter) that a launch costs more than streaming them: then fewer launches
+// win.  Wide layers stream their weights through K-split GEMMs with separate normalisation kernels, which
+// also round the norm's output where the definition does: the other placement costs more accuracy the wider
+// the layer is (measured without any kernel: 2 x the noise floor of a correct bf16 evaluation at d = 1280,
+// 3 x at d = 4096).
+bool plan_fused(const Ctx* c, int M) {
+  (void)M;
+  if (c->cfg.dtype != VVS_BF16 || c->cfg.norm_mode == VVS_NORM_SEPARATE) return false;
+  const size_t layer_weight_bytes = c->esz * ((size_t)4 * c->d * c->d + (size_t)3 * c->d * c->F);
+  return layer_weight_bytes <= ((size_t)48 << 20);
+}
+
 vvs_status plan_sizes(const vvs_config* cfg, Ctx* c, std::string* err) {
   if (!cfg) return fail(err, VVS_EINVAL, "config is NULL");
   const vvs_config& g = *cfg;
@@ -72,6 +85,7 @@ vvs_status plan_sizes(const vvs_config* cfg, Ctx* c, std::string* err) {
     return fail(err, VVS_ESIZE, "config: feature_slots must be in [0, VVS_MAX_FEATURE_SLOTS]");
   if (g.feature_pre_norm != 0 && g.feature_pre_norm != 1) return fail(err, VVS_EINVAL, "config: feature_pre_norm must be 0 or 1");
   if (g.draft_input != 0 && g.draft_input != 1) return fail(err, VVS_EINVAL, "config: draft_input must be 0 or 1");
+  if (g.norm_mode != VVS_NORM_AUTO && g.norm_mode != VVS_NORM_SEPARATE) return fail(err, VVS_EINVAL, "config: unknown norm_mode");
   int dh = g.d_model / g.n_heads;
   if (dh % 4) return fail(err, VVS_ESIZE, "config: head size must be a multiple of 4 (2D rotary pairs)");
   if (g.d_model % 8 || g.d_ff % 8) return fail(err, VVS_ESIZE, "config: d_model and d_ff must be multiples of 8");
@@ -245,6 +259,11 @@ vvs_status vvs_query_sizes(const vvs_config* cfg, size_t* kv_bytes, size_t* work
   if (workspace_bytes) *workspace_bytes = c.w.total;
   if (packed_weight_bytes) *packed_weight_bytes = c.p.total;
   return VVS_OK;
+}
+
+int32_t vvs_plan_is_fused(const vvs_ctx* ctx, int32_t n_tokens) {
+  const Ctx* c = (const Ctx*)ctx;
+  return c && n_tokens >= 1 && plan_fused(c, c->R * n_tokens) ? 1 : 0;
 }
 
 int32_t vvs_num_weight_tensors(const vvs_config* cfg) { return cfg ? 4 + 9 * cfg->n_layers + (cfg->draft_input ? 1 : 0) : 0; }

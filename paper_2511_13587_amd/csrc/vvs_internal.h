@@ -89,6 +89,7 @@ struct Timed {
 // ---- host planner (vvs_host.cpp)
 vvs_status plan_sizes(const vvs_config* cfg, Ctx* c, std::string* err);
 GemmPlan plan_gemm(const Ctx* c, int M, int N, int K);
+bool plan_fused(const Ctx* c, int M);   // true: the fused 5-kernel layer runs for M GEMM rows
 vvs_status build_tree(int n_nodes, const int32_t* h_parent, const uint8_t* h_mask, TreeDesc* out, std::string* err);
 
 // ---- launchers (kernels_*.hip); all asynchronous on the stream

@@ -57,10 +57,9 @@ __global__ void k_transpose(const T* __restrict__ in, T* __restrict__ out, int K
 // in[k][col0 + n].  One thread per 16-byte chunk; the 32 lanes of a half-block read 32 consecutive n.
 // Row block nb of the source lands in row block nb * nb_stride + nb_off of the destination (gate and
 // up projections are interleaved block by block so that one GEMM tile holds both for the same units).
-// gain (optional, one value per input feature k): the RMSNorm gain in front of this projection, folded
-// into the weights: bf16(w * g[k]).
+// The weights are copied bit for bit: the packed operand holds exactly the bf16 values the caller gave.
 __global__ void k_pack_w(const bf16_t* __restrict__ in, uint4* __restrict__ out, int K, int N, int ld, int col0, int nb_stride,
-                         int nb_off, const bf16_t* __restrict__ gain) {
+                         int nb_off) {
   const size_t chunk = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t total = (size_t)(N >> 5) * (K >> 4) * 64;
   if (chunk >= total) return;
@@ -71,11 +70,7 @@ __global__ void k_pack_w(const bf16_t* __restrict__ in, uint4* __restrict__ out,
   uint32_t w[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    uint32_t lo = in[(size_t)(k0 + 2 * i) * ld + col0 + n], hi = in[(size_t)(k0 + 2 * i + 1) * ld + col0 + n];
-    if (gain) {
-      lo = f2bf(bf2f((bf16_t)lo) * bf2f(gain[k0 + 2 * i]));
-      hi = f2bf(bf2f((bf16_t)hi) * bf2f(gain[k0 + 2 * i + 1]));
-    }
+    const uint32_t lo = in[(size_t)(k0 + 2 * i) * ld + col0 + n], hi = in[(size_t)(k0 + 2 * i + 1) * ld + col0 + n];
     w[i] = lo | (hi << 16);
   }
   out[(((size_t)nb * nb_stride + nb_off) * (K >> 4) + kb) * 64 + lane] = make_uint4(w[0], w[1], w[2], w[3]);
@@ -96,12 +91,11 @@ __global__ void k_pack_a(const bf16_t* __restrict__ in, uint4* __restrict__ out,
 }
 
 template <typename T>
-static void transpose_into(const void* in, void* out, int K, int N, int ld, int col0, hipStream_t s, int nb_stride = 1, int nb_off = 0,
-                           const void* gain = nullptr) {
+static void transpose_into(const void* in, void* out, int K, int N, int ld, int col0, hipStream_t s, int nb_stride = 1, int nb_off = 0) {
   if (sizeof(T) == 2) {
     const size_t total = (size_t)(N >> 5) * (K >> 4) * 64;
     hipLaunchKernelGGL(k_pack_w, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const bf16_t*)in, (uint4*)out, K, N, ld, col0,
-                       nb_stride, nb_off, (const bf16_t*)gain);
+                       nb_stride, nb_off);
     return;
   }
   dim3 grid((N + 31) / 32, (K + 31) / 32);
@@ -136,16 +130,13 @@ static void pack_weights_t(Ctx* c, const void* const* t, hipStream_t s) {
     size_t base = c->p.layer0 + c->p.layer_stride * l;
     gain(w[0], base + c->p.g1);
     char* qkv = c->pw + base + c->p.wqkv;
-    // bf16: the gains of the three norms are folded into the projection that follows each of them
-    const void* fold1 = sizeof(T) == 2 ? w[0] : nullptr;
-    const void* fold2 = sizeof(T) == 2 ? w[5] : nullptr;
-    for (int i = 0; i < 3; ++i) transpose_into<T>(w[1 + i], qkv + (size_t)i * d * d * sizeof(T), d, d, d, 0, s, 1, 0, fold1);
+    for (int i = 0; i < 3; ++i) transpose_into<T>(w[1 + i], qkv + (size_t)i * d * d * sizeof(T), d, d, d, 0, s);
     transpose_into<T>(w[4], c->pw + base + c->p.wo, d, d, d, 0, s);
     gain(w[5], base + c->p.g2);
     char* gu = c->pw + base + c->p.wgu;
     if (sizeof(T) == 2) {            // bf16: gate / up interleaved in blocks of 32 output features
-      transpose_into<T>(w[6], gu, d, F, F, 0, s, 2, 0, fold2);
-      transpose_into<T>(w[7], gu, d, F, F, 0, s, 2, 1, fold2);
+      transpose_into<T>(w[6], gu, d, F, F, 0, s, 2, 0);
+      transpose_into<T>(w[7], gu, d, F, F, 0, s, 2, 1);
     } else {
       transpose_into<T>(w[6], gu, d, F, F, 0, s);
       transpose_into<T>(w[7], gu + (size_t)F * d * sizeof(T), d, F, F, 0, s);
@@ -154,7 +145,7 @@ static void pack_weights_t(Ctx* c, const void* const* t, hipStream_t s) {
   }
   const void* const* tail = t + 2 + 9 * c->L;
   gain(tail[0], c->p.gf);
-  transpose_into<T>(tail[1], c->pw + c->p.wout, d, c->veff, c->V, c->lo, s, 1, 0, sizeof(T) == 2 ? tail[0] : nullptr);
+  transpose_into<T>(tail[1], c->pw + c->p.wout, d, c->veff, c->V, c->lo, s);
   if (c->cfg.draft_input) transpose_into<T>(tail[2], c->pw + c->p.fc, 2 * d, d, d, 0, s);
 }
 
@@ -206,10 +197,12 @@ __global__ void k_embed(float* __restrict__ x, const T* __restrict__ embed, cons
   for (int i = threadIdx.x; i < a.d; i += blockDim.x) x[(size_t)m * a.d + i] = ld(src + i);
 }
 
-// Embedding for the path without separate normalisation kernels: x (fp32), bf16(x) in packed operand
-// order, and the row's sum of squares (slab 0 holds the whole sum, the other slabs 0).
+// Embedding for the path without separate normalisation kernels: x (fp32), bf16(x * g) in packed operand
+// order (g = gain of the norm that follows), and the row's sum of squares (slab 0 holds the whole sum, the
+// other slabs 0).
 __global__ __launch_bounds__(256) void k_embed_packed(float* __restrict__ x, bf16_t* __restrict__ xb, float* __restrict__ ss, int NS,
-                                                      const bf16_t* __restrict__ embed, const bf16_t* __restrict__ prefix_tab, EmbedArgs a) {
+                                                      const bf16_t* __restrict__ embed, const bf16_t* __restrict__ prefix_tab,
+                                                      const float* __restrict__ g, EmbedArgs a) {
   __shared__ float red[16];
   const int m = blockIdx.x;
   const bf16_t* src = embed_source(embed, prefix_tab, a, m);
@@ -221,7 +214,9 @@ __global__ __launch_bounds__(256) void k_embed_packed(float* __restrict__ x, bf1
 #pragma unroll
     for (int i = 0; i < 4; ++i) { v[2 * i] = bf2f((bf16_t)(w[i] & 0xFFFF)); v[2 * i + 1] = bf2f((bf16_t)(w[i] >> 16)); }
     store8(x, m, k0, a.d, v);
-    *(uint4*)(xb + pack_index(m, k0, a.d)) = raw;
+    const float4 ga = *(const float4*)(g + k0), gb = *(const float4*)(g + k0 + 4);
+    const float hv[8] = {v[0] * ga.x, v[1] * ga.y, v[2] * ga.z, v[3] * ga.w, v[4] * gb.x, v[5] * gb.y, v[6] * gb.z, v[7] * gb.w};
+    store8(xb, m, k0, a.d, hv);
 #pragma unroll
     for (int i = 0; i < 8; ++i) sq += v[i] * v[i];
   }
@@ -229,14 +224,15 @@ __global__ __launch_bounds__(256) void k_embed_packed(float* __restrict__ x, bf1
   if (threadIdx.x < NS) ss[(size_t)m * NS + threadIdx.x] = threadIdx.x == 0 ? sq : 0.f;
 }
 
-// Rows (i * stride + off) of x -> packed bf16 rows i, with their sums of squares (for the lm_head of a prefill)
-__global__ __launch_bounds__(256) void k_gather_rows(const float* __restrict__ x, const float* __restrict__ ss, bf16_t* __restrict__ xb2,
-                                                     float* __restrict__ ss2, int d, int NS, int stride, int off) {
+// Rows (i * stride + off) of x, times the gain g -> packed bf16 rows i, with their sums of squares (for the lm_head of a prefill)
+__global__ __launch_bounds__(256) void k_gather_rows(const float* __restrict__ x, const float* __restrict__ ss, const float* __restrict__ g,
+                                                     bf16_t* __restrict__ xb2, float* __restrict__ ss2, int d, int NS, int stride, int off) {
   const int i = blockIdx.x;
   const size_t m = (size_t)i * stride + off;
   for (int k0 = threadIdx.x * 8; k0 < d; k0 += 256 * 8) {
     const float4 a = *(const float4*)(x + m * d + k0), b = *(const float4*)(x + m * d + k0 + 4);
-    const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    const float4 ga = *(const float4*)(g + k0), gb = *(const float4*)(g + k0 + 4);
+    const float v[8] = {a.x * ga.x, a.y * ga.y, a.z * ga.z, a.w * ga.w, b.x * gb.x, b.y * gb.y, b.z * gb.z, b.w * gb.w};
     store8(xb2, i, k0, d, v);
   }
   if (threadIdx.x < NS) ss2[(size_t)i * NS + threadIdx.x] = ss[m * NS + threadIdx.x];
@@ -300,7 +296,7 @@ __global__ __launch_bounds__(256) void k_add_rmsnorm(float* __restrict__ x, cons
   for (int j = 0; j < NCH; ++j) {
     const int k0 = (threadIdx.x + 256 * j) * 8;
     if (k0 < d) {
-      float gv[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};       // g == nullptr: the gain lives in the next projection's weights
+      float gv[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
       if (g) {
         const float4 ga = *(const float4*)(g + k0), gb = *(const float4*)(g + k0 + 4);
         gv[0] = ga.x; gv[1] = ga.y; gv[2] = ga.z; gv[3] = ga.w; gv[4] = gb.x; gv[5] = gb.y; gv[6] = gb.z; gv[7] = gb.w;
@@ -469,8 +465,9 @@ static int run_gemm(Ctx* c, const void* A, const void* W, float* C, int M, int N
 // ------------------------------------------------------------------------------------------------ one forward over T tokens per row
 // bf16, enough rows that no projection needs a grid-level K split: 5 kernels per layer.  The residual
 // stream is kept three ways by whoever updates it (embedding kernel, O / down epilogues): fp32 x,
-// bf16(x) in packed operand order, and per-row sums of squares; the projections that follow a norm
-// take bf16(x) as operand and apply the RMSNorm factor to their output tile (gains are in the weights).
+// bf16(x * g) in packed operand order (g = gain of the norm that reads it next), and per-row sums of
+// squares; the projections that follow a norm take bf16(x * g) as operand and apply the RMSNorm row
+// factor to their output tile.  The packed weights are the caller's bf16 values, unchanged.
 static void forward_fused(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, const int32_t* d_tokens_bt, const void* pc,
                           const void* pu, int chunk_start, const int32_t* forced, int n_forced, int logits_mode, hipStream_t s,
                           bool from_din) {
@@ -482,14 +479,16 @@ static void forward_fused(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int 
   bf16_t* act = (bf16_t*)(c->ws + c->w.act);
   EmbedArgs ea{Tq, d, c->V, d_tokens_bt ? 0 : 1, d_tokens_bt, pc, pu, c->cfg.prefix_kind, c->cfg.n_classes, c->P, chunk_start,
                n_forced, forced};
+  const float* g_first = (const float*)(c->pw + c->p.layer0 + c->p.g1);   // gain of the first layer's first norm
+  const float* gf = (const float*)(c->pw + c->p.gf);
   if (from_din) {             // drafter: x = [embedding ; feature] W_fc, through the residual epilogue on a zeroed x
     launch_fill_zero(x, sizeof(float) * (size_t)M * d, s);
     Timed timed(c, VVS_K_GEMM, s);
-    mfma_gemm_resid(c, (const bf16_t*)(c->ws + c->w.din), (const bf16_t*)(c->pw + c->p.fc), x, xb, ss, M, 2 * d, s);
+    mfma_gemm_resid(c, (const bf16_t*)(c->ws + c->w.din), (const bf16_t*)(c->pw + c->p.fc), x, xb, ss, g_first, M, 2 * d, s);
   } else {
     Timed timed(c, VVS_K_ELEMENTWISE, s);
     hipLaunchKernelGGL(k_embed_packed, dim3(M), dim3(256), 0, s, x, xb, ss, NS, (const bf16_t*)(c->pw + c->p.embed),
-                       (const bf16_t*)(c->pw + c->p.prefix_embed), ea);
+                       (const bf16_t*)(c->pw + c->p.prefix_embed), g_first, ea);
   }
   const GemmPlan pq = plan_gemm(c, M, 3 * d, d), pg = plan_gemm(c, M, 2 * F, d);
   for (int l = 0; l < c->L; ++l) {
@@ -501,13 +500,15 @@ static void forward_fused(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int 
       mfma_attention(c, l, tree, pos, Tq, s);
     }
     { Timed timed(c, VVS_K_GEMM, s);
-      mfma_gemm_resid(c, attn, (const bf16_t*)(lw + c->p.wo), x, xb, ss, M, d, s);
+      mfma_gemm_resid(c, attn, (const bf16_t*)(lw + c->p.wo), x, xb, ss, (const float*)(lw + c->p.g2), M, d, s);
     }
     { Timed timed(c, VVS_K_GEMM, s);
       mfma_gemm_swiglu(c, xb, (const bf16_t*)(lw + c->p.wgu), act, ss, M, F, d, pg, s);
     }
     { Timed timed(c, VVS_K_GEMM, s);
-      mfma_gemm_resid(c, act, (const bf16_t*)(lw + c->p.wd), x, xb, ss, M, F, s);
+      // the next reader of x is the next layer's first norm, or the final norm
+      const float* g_next = l + 1 < c->L ? (const float*)(lw + c->p.layer_stride + c->p.g1) : gf;
+      mfma_gemm_resid(c, act, (const bf16_t*)(lw + c->p.wd), x, xb, ss, g_next, M, F, s);
     }
   }
   if (logits_mode == 0) return;
@@ -520,7 +521,7 @@ static void forward_fused(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int 
     bf16_t* hf = (bf16_t*)(c->ws + c->w.hf);
     float* ss2 = (float*)(c->ws + c->w.ss2);
     { Timed timed(c, VVS_K_ELEMENTWISE, s);
-      hipLaunchKernelGGL(k_gather_rows, dim3(c->R), dim3(256), 0, s, x, ss, hf, ss2, d, NS, Tq, Tq - 1);
+      hipLaunchKernelGGL(k_gather_rows, dim3(c->R), dim3(256), 0, s, x, ss, gf, hf, ss2, d, NS, Tq, Tq - 1);
     }
     Timed timed(c, VVS_K_GEMM, s);
     mfma_gemm_scaled(c, hf, wout, logits, ss2, c->R, c->veff, d, plan_gemm(c, c->R, c->veff, d), s);
@@ -532,12 +533,7 @@ static void forward_t(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, 
                       const void* pu, int chunk_start, const int32_t* forced, int n_forced, int logits_mode, hipStream_t s,
                       bool from_din) {
   const int d = c->d, F = c->F, M = c->R * Tq;
-  const bool folded = sizeof(T) == 2;          // bf16: norm gains are folded into the packed weights
-  // 5 kernels per layer when the projections fill the chip without a K split - or when a layer's weights are so
-  // small (below ~48 MB: the B and XL widths, a drafter) that a launch costs more than streaming them: then fewer
-  // launches win even with few tiles.  Wide layers with few rows stream their weights through K-split GEMMs.
-  const size_t layer_weight_bytes = sizeof(T) * ((size_t)4 * d * d + (size_t)3 * d * F);
-  if (folded && (((M + 63) / 64) * (d / 64) >= 128 || layer_weight_bytes <= ((size_t)48 << 20))) {
+  if (plan_fused(c, M)) {
     forward_fused(c, tree, pos, Tq, d_tokens_bt, pc, pu, chunk_start, forced, n_forced, logits_mode, s, from_din);
     return;
   }
@@ -566,7 +562,7 @@ static void forward_t(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, 
     T* kc = (T*)c->kv + c->kv_layer_stride * l;
     T* vc = (T*)c->kv + c->kv_v_off + c->kv_layer_stride * l;
     { Timed timed(c, VVS_K_ELEMENTWISE, s);
-    launch_add_rmsnorm<T>(M, x, go, splits, sstride, d, folded ? nullptr : (const float*)(lw + c->p.g1), c->cfg.rms_eps, h, 1, 0, s);
+    launch_add_rmsnorm<T>(M, x, go, splits, sstride, d, (const float*)(lw + c->p.g1), c->cfg.rms_eps, h, 1, 0, s);
     }
     int sp;
     GemmPlan pq = plan_gemm(c, M, 3 * d, d);
@@ -593,7 +589,7 @@ static void forward_t(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, 
     }
     sp = run_gemm(c, attn, lw + c->p.wo, go, M, d, d, true, s);
     { Timed timed(c, VVS_K_ELEMENTWISE, s);
-    launch_add_rmsnorm<T>(M, x, go, sp, (size_t)M * d, d, folded ? nullptr : (const float*)(lw + c->p.g2), c->cfg.rms_eps, h, 1, 0, s);
+    launch_add_rmsnorm<T>(M, x, go, sp, (size_t)M * d, d, (const float*)(lw + c->p.g2), c->cfg.rms_eps, h, 1, 0, s);
     }
     GemmPlan pg = plan_gemm(c, M, 2 * F, d);
     if (c->cfg.dtype == VVS_BF16 && pg.splits == 1) {
@@ -612,7 +608,7 @@ static void forward_t(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int Tq, 
   if (logits_mode == 0) return;
   T* hf = (T*)(c->ws + c->w.hf);
   float* logits = (float*)(c->ws + c->w.logits);
-  const float* gf = folded ? nullptr : (const float*)(c->pw + c->p.gf);
+  const float* gf = (const float*)(c->pw + c->p.gf);
   int Ml;
   if (logits_mode == 1) {     // every token
     Ml = M;

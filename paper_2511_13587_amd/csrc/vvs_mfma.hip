@@ -44,19 +44,20 @@ __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast
 //                rotary embedding to q and k, write q (bf16 row-major) and put k / v into the cache
 //                slots of their tokens (one K split only);
 //   EPI_RESID  : O / down projection: x += tile (fp32 residual stream, each element owned by one
-//                thread), also written as the packed bf16 operand of the next projection, plus the
-//                sum of squares of the tile's 64 columns per row (one K split only).
-// Row scale: RMSNorm is x * s_m * g with s_m = rsqrt(mean_k x_mk^2 + eps).  The gain g is folded into
-// the weights when they are packed, the operand is bf16(x) itself, and s_m - a per-row factor that
-// commutes with the contraction - multiplies the accumulated tile in the epilogue; s_m comes from the
+//                thread), also written, times the gain of the norm that follows, as the packed bf16
+//                operand of the next projection, plus the sum of squares of the tile's 64 columns per
+//                row (one K split only).
+// Row scale: RMSNorm is x * s_m * g with s_m = rsqrt(mean_k x_mk^2 + eps).  The operand of the projection
+// behind a norm is bf16(x * g), written by whoever produced x, and s_m - a per-row factor that commutes
+// with the contraction - multiplies the accumulated tile in the epilogue; s_m comes from the
 // per-64-column sums of squares that the producer of x (EPI_RESID or the embedding kernel) left in ss.
-// This removes the separate normalisation pass between two projections.
+// This removes the separate normalisation pass between two projections; the weights stay as given.
 enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_QKV = 2, EPI_RESID = 3 };
 
 struct GemmEpi {
   const float* ss; int NS; float eps; int dnorm;           // row scale (ss == nullptr: no scaling); ss[M][NS]
   bf16_t* act; int F;                                      // EPI_SWIGLU
-  float* x; bf16_t* xb; float* ss_out;                     // EPI_RESID
+  float* x; bf16_t* xb; float* ss_out; const float* g_next; // EPI_RESID (g_next: gain of the norm that reads x next)
   bf16_t* q; bf16_t* kc; bf16_t* vc; const float* rope;    // EPI_QKV
   int T, d, dh, S_cap, rope_pos;
   size_t row_stride, head_stride;
@@ -121,7 +122,7 @@ struct EpiPre {
   static constexpr int NR = 2 * kRopeNpMax / G / 2;         // float4 (two factor pairs) per thread
   int kv, ne, slot, img;
   float4 rp[NR];
-  float4 x0[UR], x1[UR];
+  float4 x0[UR], x1[UR], g0[UR], g1[UR];
 
   // m / T for 0 <= m < 2^20 (the quotient of the rounded product cannot cross an integer: the exact
   // value is at least 0.5 / T away from one)
@@ -166,6 +167,8 @@ struct EpiPre {
         const float* xp = ep.x + (size_t)min(m0 + row, M - 1) * N + n0 + c8;   // clamped rows are never stored
         x0[j] = *(const float4*)xp;
         x1[j] = *(const float4*)(xp + 4);
+        g0[j] = *(const float4*)(ep.g_next + n0 + c8);
+        g1[j] = *(const float4*)(ep.g_next + n0 + c8 + 4);
       }
     }
   }
@@ -245,7 +248,9 @@ __device__ __forceinline__ void tile_epilogue(const float* red, const float* rs,
         float v[8] = {xa.x + a.x, xa.y + a.y, xa.z + a.z, xa.w + a.w, xb4.x + b.x, xb4.y + b.y, xb4.z + b.z, xb4.w + b.w};
         *(float4*)xp = make_float4(v[0], v[1], v[2], v[3]);
         *(float4*)(xp + 4) = make_float4(v[4], v[5], v[6], v[7]);
-        store8(ep.xb, m, n0 + c8, N, v);
+        const float4 ga = pre.g0[j], gb = pre.g1[j];
+        const float hv[8] = {v[0] * ga.x, v[1] * ga.y, v[2] * ga.z, v[3] * ga.w, v[4] * gb.x, v[5] * gb.y, v[6] * gb.z, v[7] * gb.w};
+        store8(ep.xb, m, n0 + c8, N, hv);
 #pragma unroll
         for (int i = 0; i < 8; ++i) sq += v[i] * v[i];
       }
@@ -623,10 +628,16 @@ __global__ __launch_bounds__(256) void k_gemm_shared(const uint4* __restrict__ A
 // written out by hand.  Iteration s: request stage s + NS - 1 into the slot stage s - 1 has left; multiply
 // (fragments as in k_gemm_shared); wait until this wave's part of stage s + 2 has landed - loads return in
 // order, so "at most PER * (NS - 3) younger loads outstanding" - and meet the other waves at the barrier.
+// M0 is written here, so it is on the clobber list: the compiler must not keep a value of its own in it across
+// the statement (it names M0 "reserved" and warns about any clobber of it; that warning is silenced for this
+// one statement).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void lds_dma16(const void* g, uint32_t lds_byte_addr) {
   const uint32_t a = __builtin_amdgcn_readfirstlane(lds_byte_addr);     // wave-uniform by construction
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(a), "v"(g) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(a), "v"(g) : "memory", "m0");
 }
+#pragma clang diagnostic pop
 template <int WM, int WN, int NS, int EPI>
 __global__ __launch_bounds__(256) void k_gemm_shared_dma(const uint4* __restrict__ Ap, const uint4* __restrict__ Wp, float* __restrict__ C,
                                                          int M, int N, int K, const GemmEpi ep) {
@@ -801,10 +812,11 @@ void mfma_gemm_scaled(Ctx* c, const bf16_t* A, const bf16_t* W, float* C, const 
   gemm_dispatch<EPI_PARTIAL>(A, W, C, M, N, K, p, ep, s);
 }
 
-// x += A W; also leaves bf16(x) packed and the per-slab sums of squares of the new x
-void mfma_gemm_resid(Ctx* c, const bf16_t* A, const bf16_t* W, float* x, bf16_t* xb, float* ss_out, int M, int K, hipStream_t s) {
+// x += A W; also leaves bf16(x * g_next) packed and the per-slab sums of squares of the new x
+void mfma_gemm_resid(Ctx* c, const bf16_t* A, const bf16_t* W, float* x, bf16_t* xb, float* ss_out, const float* g_next, int M, int K,
+                     hipStream_t s) {
   GemmEpi ep{};
-  ep.x = x; ep.xb = xb; ep.ss_out = ss_out; ep.NS = (c->d / 64 + 3) & ~3;
+  ep.x = x; ep.xb = xb; ep.ss_out = ss_out; ep.g_next = g_next; ep.NS = (c->d / 64 + 3) & ~3;
   launch_gemm_direct<2, 2, 6, EPI_RESID>(A, W, nullptr, M, c->d, K, 1, ep, s);
 }
 
@@ -943,25 +955,33 @@ __global__ __launch_bounds__(NW * 64, (DH * NQB >= 256 ? 1 : 2)) void k_attn_mfm
           const float m_new = fmaxf(m_run[qb], mx);
           const float m_safe = m_new == -INFINITY ? 0.f : m_new;
           const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_safe) * c_exp);
-          uint32_t pk[4];
+          // The softmax weights are not rounded to bf16 (the definition keeps them exact): each un-normalised
+          // weight e goes into the P V product as the sum of two bf16 values, hi = bf16(e) and lo = bf16(e - hi)
+          // (e to 2^-17), with two MFMAs per V block - the matrix cores idle in this kernel anyway - and the
+          // normaliser sums the fp32 weights themselves.
+          uint32_t pk[4], pl[4];
           float rs = 0.f;
 #pragma unroll
           for (int i = 0; i < 8; i += 2) {
-            // hardware exp2 (arguments <= 0; results below the normal range are 0 either way after the bf16 rounding)
-            const uint32_t pp = pack2bf(__builtin_amdgcn_exp2f((sv[i] - m_safe) * c_exp), __builtin_amdgcn_exp2f((sv[i + 1] - m_safe) * c_exp));
-            rs += __uint_as_float(pp << 16) + __uint_as_float(pp & 0xFFFF0000u);
+            // hardware exp2 (arguments <= 0)
+            const float e0 = __builtin_amdgcn_exp2f((sv[i] - m_safe) * c_exp), e1 = __builtin_amdgcn_exp2f((sv[i + 1] - m_safe) * c_exp);
+            const uint32_t pp = pack2bf(e0, e1);
+            rs += e0 + e1;
             pk[i >> 1] = pp;
+            pl[i >> 1] = pack2bf(e0 - __uint_as_float(pp << 16), e1 - __uint_as_float(pp & 0xFFFF0000u));
           }
           rs += __shfl_xor(rs, 16, 64);
           rs += __shfl_xor(rs, 32, 64);
           l_run[qb] = l_run[qb] * alpha + rs;
           m_run[qb] = m_new;
           const bf16x8 pf = as_bf16x8(make_uint4(pk[0], pk[1], pk[2], pk[3]));
+          const bf16x8 pfl = as_bf16x8(make_uint4(pl[0], pl[1], pl[2], pl[3]));
 #pragma unroll
           for (int dt = 0; dt < DT; ++dt) {
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) o[qb][dt][rr] *= alpha;
             o[qb][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[p][dt], pf, o[qb][dt], 0, 0, 0);
+            o[qb][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[p][dt], pfl, o[qb][dt], 0, 0, 0);
           }
         }
       }

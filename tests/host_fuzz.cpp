@@ -141,7 +141,7 @@ int main() {
   // 2. size queries on random configurations never crash and refuse what they cannot serve
   for (int it = 0; it < 2000; ++it) {
     vvs_config c = base_config(it & 1, it & 2);
-    switch (ri(0, 9)) {
+    switch (ri(0, 10)) {
       case 0: c.d_model = ri(-8, 300); break;
       case 1: c.n_heads = ri(-1, 9); break;
       case 2: c.max_nodes = ri(-2, 80); break;
@@ -151,6 +151,7 @@ int main() {
       case 6: c.n_prompts = ri(-1, 5); break;
       case 7: c.draft_input = ri(-1, 2); break;
       case 8: c.relax_k = ri(-1, 70); break;
+      case 9: c.norm_mode = ri(-1, 2); break;
       default: break;
     }
     size_t a = 0, b = 0, d = 0;

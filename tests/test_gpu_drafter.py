@@ -213,7 +213,7 @@ def test_xl_shape_drafting_bf16(gc):
     # tokens as an input, so a near tie in that draw on the GPU does not matter here)
     recent = np.concatenate([ctoks[:, 1:], oout[2][:, None]], axis=1)
     tok, q, otok, oq = side.draft(parent, 5, recent)
-    tol = max(gc.mixed_tol(side.dshape), 3.0 * side.floor)     # the floor is measured on mixed logits
+    tol = max(gc.mixed_tol(side.dshape), gc.FLOOR_FACTOR_FUSED * side.floor)     # the floor is measured on mixed logits
     c1, s1 = side.compare(parent, tok, q, otok, oq, tol, "free run")
     tok2, q2, otok2, oq2 = side.draft(parent, 5, recent, given=otok)
     c2, _ = side.compare(parent, tok2, q2, otok2, oq2, tol, "given tokens", tokens_given=True)
@@ -347,7 +347,7 @@ def test_7b_like_slice_drafting_bf16(gc):
     pair.commit()
     recent = np.concatenate([ctoks[:, 2:], oout[2][:, None]], axis=1)
     tok, q, otok, oq = side.draft(parent, 2, recent)
-    tol = max(gc.mixed_tol(side.dshape), 3.0 * side.floor)
+    tol = max(gc.mixed_tol(side.dshape), gc.FLOOR_FACTOR * side.floor)
     c1, s1 = side.compare(parent, tok, q, otok, oq, tol, "free run")
     tok2, q2, otok2, oq2 = side.draft(parent, 2, recent, given=otok)
     c2, _ = side.compare(parent, tok2, q2, otok2, oq2, tol, "given tokens", tokens_given=True)
