@@ -189,6 +189,25 @@ vvs_status vvs_accept_from_logits(vvs_ctx* ctx, int32_t n_nodes, const int32_t* 
                                   const float* d_uniforms, int32_t mode, int32_t* d_accept_len,
                                   int32_t* d_path, int32_t* d_next_token, vvs_stream s);
 
+/* vvs_accept_from_logits for callers that cannot allocate device memory and have no workspace to lend: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same result.
+ * The stage's scratch (per-node partial results and per-node target distributions, which the other entry
+ * points keep in the caller's workspace) lives in a static device array inside the library, of
+ * VVS_NOALLOC_MAX_PROMPTS * VVS_MAX_T * 8 + VVS_NOALLOC_MAX_PROB_FLOATS * 4 bytes (about 16 MiB), held by every
+ * GPU the library runs on until the process ends.  The call allocates and frees nothing.  VVS_ESIZE when
+ * n_prompts > VVS_NOALLOC_MAX_PROMPTS, n_prompts * (n_nodes + 1) * V_eff > VVS_NOALLOC_MAX_PROB_FLOATS, or V_eff > 18432.
+ * All calls on one GPU share that GPU's array: calls that overlap on one GPU (other streams, other contexts)
+ * race; calls on one stream are safe.  The array keeps the last call's contents; nothing in it has to be cleared
+ * (every entry a call reads is written by that call first).  Does not touch the KV cache, the workspace, or
+ * the outcome kept for vvs_kv_commit; vvs_debug_logits does not see its distributions. */
+#define VVS_NOALLOC_MAX_PROMPTS 64
+#define VVS_NOALLOC_MAX_PROB_FLOATS (4 << 20)
+vvs_status vvs_accept_from_logits_noalloc(vvs_ctx* ctx, int32_t n_nodes, const int32_t* h_parent,
+                                          const uint8_t* h_tree_mask, const float* d_raw_logits,
+                                          const int32_t* d_draft_tokens, const float* d_draft_probs,
+                                          const float* d_uniforms, int32_t mode, int32_t* d_accept_len,
+                                          int32_t* d_path, int32_t* d_next_token, vvs_stream s);
+
 /* Section 4.1: moves the K/V of the pending token and of the accepted path of the last vvs_verify
  * into consecutive cache slots S_b .. S_b + a_b, advances S_b and n_emitted_b by a_b + 1 and makes
  * next_token the pending token.  Exactly one commit per verify. */

@@ -66,6 +66,7 @@ def _load():
         "vvs_path_similarity": (i32, [vp, i32, vp, vp, vp, C.c_float, i32, vp, vp]),
         "vvs_draft": (i32, [vp, vp, i32, vp, vp, i32, vp, i32, vp, vp, vp, vp]),
         "vvs_accept_from_logits": (i32, [vp, i32, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]),
+        "vvs_accept_from_logits_noalloc": (i32, [vp, i32, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]),
         "vvs_kv_commit": (i32, [vp, vp]),
         "vvs_read_state": (i32, [vp, vp, vp]),
         "vvs_set_state": (i32, [vp, vp, vp]),
@@ -282,6 +283,15 @@ class Context:
                                                None if m is None else m.ctypes.data, _ptr(raw_logits), _ptr(draft_tokens),
                                                _ptr(draft_probs), _ptr(uniforms), mode, _ptr(accept_len), _ptr(path),
                                                _ptr(next_token), _stream()))
+
+    def vvs_accept_from_logits_noalloc(self, n_nodes: int, parent, tree_mask, raw_logits: torch.Tensor, draft_tokens, draft_probs,
+                                       uniforms, mode, accept_len, path, next_token):
+        p = None if parent is None else np.ascontiguousarray(parent, dtype=np.int32)
+        m = None if tree_mask is None else np.ascontiguousarray(tree_mask, dtype=np.uint8)
+        self._check(lib.vvs_accept_from_logits_noalloc(self.h, n_nodes, None if p is None else p.ctypes.data,
+                                                       None if m is None else m.ctypes.data, _ptr(raw_logits), _ptr(draft_tokens),
+                                                       _ptr(draft_probs), _ptr(uniforms), mode, _ptr(accept_len), _ptr(path),
+                                                       _ptr(next_token), _stream()))
 
     def vvs_kv_commit(self):
         self._check(lib.vvs_kv_commit(self.h, _stream()))

@@ -428,6 +428,50 @@ void launch_accept(Ctx* c, const TreeDesc& tree, int T, const float* d_logits, c
                    (int32_t*)(c->ws + c->w.node_result), s);
 }
 
+// ------------------------------------------------------------------------------------------------ acceptance stage without any allocation
+// The acceptance stage for callers that cannot allocate device memory and have no workspace to hand over: its
+// two scratch buffers - the per-node results between k_accept_node and k_walk, and the per-node target
+// distributions k_accept_node writes - live in one static device array.  Every GPU holds its own copy of the
+// array at its own address; the address is looked up once per device (hipGetSymbolAddress, with that device
+// current) and kept.  Nothing in the array has to start at zero: k_accept_node writes every entry that k_walk
+// or a later phase reads.  Two calls that overlap on one GPU (two streams, two contexts) share the array and race.
+constexpr size_t kNoAllocNodeBytes = (size_t)VVS_NOALLOC_MAX_PROMPTS * VVS_MAX_T * 2 * sizeof(int32_t);
+constexpr size_t kNoAllocProbBytes = (size_t)VVS_NOALLOC_MAX_PROB_FLOATS * sizeof(float);
+static __device__ __align__(256) unsigned char scratch[kNoAllocNodeBytes + kNoAllocProbBytes];
+
+constexpr int kMaxDevices = 64;
+static unsigned char* g_scratch_ptr[kMaxDevices];   // per device: address of that device's copy of `scratch`
+
+vvs_status launch_accept_noalloc(Ctx* c, const TreeDesc& tree, int T, const float* d_logits, const int32_t* d_draft_tokens,
+                                 const float* d_q, const float* d_u, int mode, int32_t* d_accept_len, int32_t* d_path, int32_t* d_next,
+                                 hipStream_t s, std::string* err) {
+  if (c->B > VVS_NOALLOC_MAX_PROMPTS || (size_t)c->B * T * c->veff > (size_t)VVS_NOALLOC_MAX_PROB_FLOATS) {
+    *err = "accept_from_logits_noalloc: n_prompts * (n_nodes + 1) * V_eff exceeds VVS_NOALLOC_MAX_PROB_FLOATS (or n_prompts exceeds "
+           "VVS_NOALLOC_MAX_PROMPTS): the static scratch array is too small for this call";
+    return VVS_ESIZE;
+  }
+  if ((size_t)2 * c->veff * sizeof(float) > kAcceptLdsMax) {
+    *err = "accept_from_logits_noalloc: the allowed-id slice is too wide for the LDS-resident acceptance kernel";
+    return VVS_ESIZE;
+  }
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) { *err = "accept_from_logits_noalloc: hipGetDevice failed"; return VVS_EHIP; }
+  if (!g_scratch_ptr[dev]) {
+    unsigned char* p = nullptr;
+    e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      *err = std::string("accept_from_logits_noalloc: hipGetSymbolAddress: ") + hipGetErrorString(e);
+      return VVS_EHIP;
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  unsigned char* base = g_scratch_ptr[dev];
+  launch_accept_on(c, tree, T, d_logits, d_draft_tokens, d_q, d_u, 2 * T, 2, 0, 1, mode, false, d_accept_len, d_path, d_next, nullptr,
+                   (float*)(base + kNoAllocNodeBytes), nullptr, (int32_t*)base, s);
+  return VVS_OK;
+}
+
 __global__ void k_prefill_finish(const int32_t* __restrict__ node_result, int32_t* __restrict__ state, int32_t* __restrict__ first,
                                  int B, int kv_len, int n_emitted) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;

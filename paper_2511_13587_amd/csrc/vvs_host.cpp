@@ -506,6 +506,26 @@ vvs_status vvs_accept_from_logits(vvs_ctx* ctx, int32_t n_nodes, const int32_t* 
   return check_launch(c, "accept_from_logits");
 }
 
+vvs_status vvs_accept_from_logits_noalloc(vvs_ctx* ctx, int32_t n_nodes, const int32_t* h_parent, const uint8_t* h_tree_mask,
+                                          const float* d_raw_logits, const int32_t* d_draft_tokens, const float* d_draft_probs,
+                                          const float* d_uniforms, int32_t mode, int32_t* d_accept_len, int32_t* d_path,
+                                          int32_t* d_next_token, vvs_stream s) {
+  Ctx* c = reinterpret_cast<Ctx*>(ctx);
+  if (!c) return VVS_EINVAL;
+  if (!d_raw_logits) return fail(&c->err, VVS_EINVAL, "accept_from_logits_noalloc: logits are NULL");
+  vvs_status rc = check_verify_args(c, "accept_from_logits_noalloc", n_nodes, d_draft_tokens, d_draft_probs, d_uniforms, mode,
+                                    d_accept_len, d_path, d_next_token);
+  if (rc != VVS_OK) return rc;
+  TreeDesc tree;
+  rc = build_tree(n_nodes, h_parent, h_tree_mask, &tree, &c->err);
+  if (rc != VVS_OK) return rc;
+  std::string msg;
+  rc = launch_accept_noalloc(c, tree, n_nodes + 1, d_raw_logits, d_draft_tokens, d_draft_probs, d_uniforms, mode, d_accept_len, d_path,
+                             d_next_token, (hipStream_t)s, &msg);
+  if (rc != VVS_OK) return fail(&c->err, rc, msg);
+  return check_launch(c, "accept_from_logits_noalloc");
+}
+
 vvs_status vvs_kv_commit(vvs_ctx* ctx, vvs_stream s) {
   Ctx* c = reinterpret_cast<Ctx*>(ctx);
   if (!c) return VVS_EINVAL;

@@ -105,6 +105,9 @@ void launch_accept(Ctx* c, const TreeDesc& tree, int T, const float* d_logits, c
                    const float* d_q, const float* d_u, int u_stride_b, int u_stride_j, int u_off_acc, int u_off_term,
                    int mode, bool use_state, int32_t* d_accept_len, int32_t* d_path, int32_t* d_next,
                    bool keep_outcome, hipStream_t s);
+vvs_status launch_accept_noalloc(Ctx* c, const TreeDesc& tree, int T, const float* d_logits, const int32_t* d_draft_tokens,
+                                 const float* d_q, const float* d_u, int mode, int32_t* d_accept_len, int32_t* d_path, int32_t* d_next,
+                                 hipStream_t s, std::string* err);
 void launch_prefill_finish(Ctx* c, int n_forced, int32_t* d_first, hipStream_t s);
 void launch_commit(Ctx* c, hipStream_t s);
 void launch_push_prefill_feature(Ctx* c, int T_last_chunk, hipStream_t s);

@@ -44,6 +44,8 @@ void launch_forward(Ctx* c, const TreeDesc& tree, const PosDesc&, int T, const i
 void launch_build_tokens(Ctx* c, int T, const int32_t*, hipStream_t) { memset(c->ws + c->w.tokens, 0, sizeof(int32_t) * c->B * T); ++g_launches; }
 void launch_accept(Ctx*, const TreeDesc&, int, const float*, const int32_t*, const float*, const float*, int, int, int, int, int, bool, int32_t*,
                    int32_t*, int32_t*, bool, hipStream_t) { ++g_launches; }
+vvs_status launch_accept_noalloc(Ctx*, const TreeDesc&, int, const float*, const int32_t*, const float*, const float*, int, int32_t*, int32_t*,
+                                 int32_t*, hipStream_t, std::string*) { ++g_launches; return VVS_OK; }
 void launch_prefill_finish(Ctx*, int, int32_t*, hipStream_t) { ++g_launches; }
 void launch_commit(Ctx*, hipStream_t) { ++g_launches; }
 void launch_push_prefill_feature(Ctx*, int, hipStream_t) { ++g_launches; }
