@@ -13,7 +13,8 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libvvs.so")
+# VVS_LIBRARY: another build of the same library (for comparing builds); default: the in-tree one
+LIB_PATH = os.environ.get("VVS_LIBRARY") or os.path.join(_HERE, "libvvs.so")
 
 VVS_OK, VVS_EINVAL, VVS_ESTATE, VVS_ESIZE, VVS_EHIP = 0, -1, -2, -3, -4
 VVS_FP32, VVS_BF16 = 0, 1

@@ -3,12 +3,17 @@
 
     python -m paper_2511_13587_amd.profsum kernels <results.db>
     python -m paper_2511_13587_amd.profsum counters <results.db>
+    python -m paper_2511_13587_amd.profsum pivot <results.db> [<results.db> ...]
     python -m paper_2511_13587_amd.profsum window <results.db> <first kernel substring> <last kernel substring>
     python -m paper_2511_13587_amd.profsum traffic <fetch.db> <write.db> <kernel substring> <grid_x list, workgroups> [out.json]
 
 `window`: the dispatches between the first launch of one kernel and the last launch of another (e.g. the
 drafting calls of a bench run: from the first k_draft_state to the last k_draft_select), per kernel and per
 call of the first kernel.
+
+`pivot`: one line per (hot kernel, grid) with every counter of the given --pmc runs as a column (average per
+dispatch, summed over the chip's instances as rocprofv3 reports them), for reading ratios such as MFMA-busy
+cycles per CU-busy cycle.
 
 `traffic`: HBM bytes per launch of one kernel from a FETCH_SIZE run and a WRITE_SIZE run (KiB per
 dispatch), each scaled by what the same counter reads for the 256 MiB k_copy_bytes launches of the
@@ -68,6 +73,24 @@ def counters(db: str) -> str:
     return "\n".join(out)
 
 
+def pivot(dbs) -> str:
+    table, names = {}, []
+    for db in dbs:
+        cur = sqlite3.connect(db).cursor()
+        rows = cur.execute("select kernel_name, grid_size_x / workgroup_size_x, grid_size_y / workgroup_size_y, grid_size_z / workgroup_size_z, "
+                           "counter_name, count(*), avg(value) from counters_collection where kernel_name like '%gemm%' or kernel_name like "
+                           "'%attn%' or kernel_name like '%accept_node%' or kernel_name like '%commit_kv%' or kernel_name like '%rmsnorm%' "
+                           "group by 1, 2, 3, 4, 5").fetchall()
+        for n, gx, gy, gz, cn, c, v in rows:
+            table.setdefault((short(n)[:44], gx, gy, gz), {"dispatches": c})[cn] = v
+            if cn not in names:
+                names.append(cn)
+    out = [f"{'kernel':44s} {'grid':>14s} {'disp':>6s} " + " ".join(f"{n[-22:]:>22s}" for n in names)]
+    for (n, gx, gy, gz), row in sorted(table.items()):
+        out.append(f"{n:44s} {f'({gx},{gy},{gz})':>14s} {row['dispatches']:6d} " + " ".join(f"{row.get(k, float('nan')):22.1f}" for k in names))
+    return "\n".join(out)
+
+
 def traffic(fetch_db: str, write_db: str, kernel: str, grids, out_json=None) -> str:
     import json
     res = {"kernel": kernel, "grids_x_workgroups": grids, "copy_bytes": 256 << 20}
@@ -97,6 +120,8 @@ if __name__ == "__main__":
     if len(sys.argv) >= 6 and sys.argv[1] == "traffic":
         print(traffic(sys.argv[2], sys.argv[3], sys.argv[4], [int(g) for g in sys.argv[5].split(",")],
                       sys.argv[6] if len(sys.argv) > 6 else None))
+    elif len(sys.argv) >= 3 and sys.argv[1] == "pivot":
+        print(pivot(sys.argv[2:]))
     elif len(sys.argv) == 5 and sys.argv[1] == "window":
         print(window(sys.argv[2], sys.argv[3], sys.argv[4]))
     elif len(sys.argv) == 3 and sys.argv[1] in ("kernels", "counters"):
