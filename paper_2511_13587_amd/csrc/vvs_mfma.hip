@@ -60,6 +60,7 @@ struct GemmEpi {
   float* x; bf16_t* xb; float* ss_out; const float* g_next; // EPI_RESID (g_next: gain of the norm that reads x next)
   bf16_t* q; bf16_t* kc; bf16_t* vc; const float* rope;    // EPI_QKV
   int T, d, dh, S_cap, rope_pos;
+  int row_owner;                                           // tile order of the direct-to-LDS kernel: 1 = an XCD owns row tiles
   size_t row_stride, head_stride;
   PosDesc pos;
   TreeDesc tree;
@@ -115,14 +116,18 @@ struct RowScale {
 //              to_lds() leaves slot, image index and factors in LDS for the epilogue, which so reads
 //              them with a few wide LDS loads instead of 16 scattered global loads per unit.
 constexpr int kRopeNpMax = 16;   // rotary pairs per position kept in LDS (head size 64); other head sizes read the table directly
-template <int BM, int BN, int EPI>
+template <int BM, int BN, int EPI, bool EARLY = true>
 struct EpiPre {
+  // EARLY = false (large tiles, where the early copies would not fit the register file): EPI_RESID reads the residual
+  // and the gain in the epilogue itself
   static constexpr int UR = (BM * (BN / 8) + 255) / 256;    // EPI_RESID units (row, 8 columns) per thread
+  static constexpr int URE = EARLY ? UR : 1;
   static constexpr int G = 256 / BM;                        // threads per tile row
   static constexpr int NR = 2 * kRopeNpMax / G / 2;         // float4 (two factor pairs) per thread
   int kv, ne, slot, img;
+  bool rope_lds = true;          // false: the epilogue reads the rotary table from memory (kernels that keep no per-row table in LDS)
   float4 rp[NR];
-  float4 x0[UR], x1[UR], g0[UR], g1[UR];
+  float4 x0[URE], x1[URE], g0[URE], g1[URE];
 
   // m / T for 0 <= m < 2^20 (the quotient of the rounded product cannot cross an integer: the exact
   // value is at least 0.5 / T away from one)
@@ -150,7 +155,7 @@ struct EpiPre {
         img = slot - ep.pos.prefix_len;
       }
       const int np = ep.dh >> 2;
-      if (n0 / ep.d < 2 && np == kRopeNpMax) {               // q and k columns are rotated
+      if (n0 / ep.d < 2 && np == kRopeNpMax && rope_lds) {   // q and k columns are rotated
         const int im = max(img, 0), gr = min(im / ep.pos.grid_w, ep.rope_pos - 1), gc = im % ep.pos.grid_w;
         // the row's 2 * np pairs, [grid row: np][grid column: np], are dealt to its G threads in order
         const int per = 2 * np / G, p0 = ((int)threadIdx.x / BM) * per;   // pairs per thread (even), first pair
@@ -160,7 +165,7 @@ struct EpiPre {
           rp[i] = *(const float4*)(ep.rope + ((size_t)pv * np + ip) * 2);
         }
       }
-    } else if constexpr (EPI == EPI_RESID) {
+    } else if constexpr (EPI == EPI_RESID && EARLY) {
 #pragma unroll
       for (int j = 0; j < UR; ++j) {
         const int u = threadIdx.x + 256 * j, row = min(u / (BN / 8), BM - 1), c8 = (u % (BN / 8)) * 8;
@@ -177,7 +182,7 @@ struct EpiPre {
     if constexpr (EPI == EPI_QKV) {
       const int row = threadIdx.x % BM, g = threadIdx.x / BM, np = ep.dh >> 2;
       if (g == 0) { s_pos[2 * row] = slot; s_pos[2 * row + 1] = img; }
-      if (np == kRopeNpMax) {
+      if (np == kRopeNpMax && rope_lds) {
         const int per = 2 * np / G, p0 = g * per;
 #pragma unroll
         for (int i = 0; i < NR; ++i)
@@ -189,9 +194,9 @@ struct EpiPre {
 
 // Epilogue of a BM x BN tile whose NP partial sums lie in LDS as red[NP][BM][BN + 4] (added in a fixed
 // order); rs holds the row factors.  Called by all 256 threads after a barrier.
-template <int BM, int BN, int NP, int EPI>
+template <int BM, int BN, int NP, int EPI, bool EARLY = true>
 __device__ __forceinline__ void tile_epilogue(const float* red, const float* rs, int tile_m, int tile_n, int M, int N, float* C,
-                                              const GemmEpi& ep, const EpiPre<BM, BN, EPI>& pre, const int* s_pos, const float2* s_rope) {
+                                              const GemmEpi& ep, const EpiPre<BM, BN, EPI, EARLY>& pre, const int* s_pos, const float2* s_rope) {
   constexpr int LDC = BN + 4;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   constexpr int PS = BM * LDC;   // stride between the partial tiles
@@ -244,11 +249,16 @@ __device__ __forceinline__ void tile_epilogue(const float* red, const float* rs,
       if (row < BM && m < M) {
         const float4 a = sum4(red + row * LDC + c8), b = sum4(red + row * LDC + c8 + 4);
         float* xp = ep.x + (size_t)m * N + n0 + c8;
-        const float4 xa = pre.x0[j], xb4 = pre.x1[j];
+        float4 xa, xb4, ga, gb;
+        if constexpr (EARLY) {
+          xa = pre.x0[j]; xb4 = pre.x1[j]; ga = pre.g0[j]; gb = pre.g1[j];
+        } else {
+          xa = *(const float4*)xp; xb4 = *(const float4*)(xp + 4);
+          ga = *(const float4*)(ep.g_next + n0 + c8); gb = *(const float4*)(ep.g_next + n0 + c8 + 4);
+        }
         float v[8] = {xa.x + a.x, xa.y + a.y, xa.z + a.z, xa.w + a.w, xb4.x + b.x, xb4.y + b.y, xb4.z + b.z, xb4.w + b.w};
         *(float4*)xp = make_float4(v[0], v[1], v[2], v[3]);
         *(float4*)(xp + 4) = make_float4(v[4], v[5], v[6], v[7]);
-        const float4 ga = pre.g0[j], gb = pre.g1[j];
         const float hv[8] = {v[0] * ga.x, v[1] * ga.y, v[2] * ga.z, v[3] * ga.w, v[4] * gb.x, v[5] * gb.y, v[6] * gb.z, v[7] * gb.w};
         store8(ep.xb, m, n0 + c8, N, hv);
 #pragma unroll
@@ -279,7 +289,7 @@ __device__ __forceinline__ void tile_epilogue(const float* red, const float* rs,
         const int img = s_pos[2 * row + 1];
         if (img >= 0) {
           float2 cs[8];
-          if (np == kRopeNpMax) {
+          if (np == kRopeNpMax && s_rope) {
             // 16 columns = 8 pairs inside one half of the head: 8 consecutive pairs of the row's LDS table
             const float4* t4 = (const float4*)(s_rope + row * 2 * kRopeNpMax + (e >> (dh_sh - 1)) * np + ((e & (half - 1)) >> 1));
 #pragma unroll
@@ -328,7 +338,7 @@ __device__ __forceinline__ void tile_epilogue(const float* red, const float* rs,
           const int eg = nd + c8, hd = eg >> dh_sh, e = eg & dh_mask;
           if (img >= 0) {
             float2 cs[4];
-            if (np == kRopeNpMax) {
+            if (np == kRopeNpMax && s_rope) {
               const float4* t4 = (const float4*)(s_rope + row * 2 * kRopeNpMax + (e >> (dh_sh - 1)) * np + ((e & (half - 1)) >> 1));
               const float4 c0 = t4[0], c1 = t4[1];
               cs[0] = make_float2(c0.x, c0.y); cs[1] = make_float2(c0.z, c0.w);
@@ -641,8 +651,7 @@ __device__ __forceinline__ void lds_dma16(const void* g, uint32_t lds_byte_addr)
 template <int WM, int WN, int NS, int EPI>
 __global__ __launch_bounds__(256) void k_gemm_shared_dma(const uint4* __restrict__ Ap, const uint4* __restrict__ Wp, float* __restrict__ C,
                                                          int M, int N, int K, const GemmEpi ep) {
-  static_assert(EPI == EPI_PARTIAL || EPI == EPI_SWIGLU, "epilogues without per-row LDS tables");
-  static_assert((NS & (NS - 1)) == 0 && NS >= 4, "slot index by masking");
+  static_assert(NS >= 4, "at least three stages in flight");
   constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32, LDC = BN + 4;
   constexpr int NA = 2 * (BM / 32), NBLK = NA + 2 * (BN / 32), PER = NBLK / 4;
   static_assert(NBLK % 4 == 0, "blocks of a stage are dealt to 4 waves");
@@ -655,19 +664,29 @@ __global__ __launch_bounds__(256) void k_gemm_shared_dma(const uint4* __restrict
   const int wr = wave >> 1, wc = wave & 1;
   const int MT = (M + BM - 1) / BM, NT = N / BN;
   int tile_m, tile_n;
-  {                                        // same XCD-aware order as k_gemm_direct
-    const int id = blockIdx.x, grp = id / (8 * MT), rem = id % (8 * MT);
+  if (!ep.row_owner) {                     // same XCD-aware order as k_gemm_direct: an XCD owns column tiles (weights fetched once,
+    const int id = blockIdx.x, grp = id / (8 * MT), rem = id % (8 * MT);   // the activation operand once per XCD)
     const int cols = min(8, NT - grp * 8);
     tile_m = rem / cols;
     tile_n = grp * 8 + rem % cols;
+  } else {                                 // the transposed order: an XCD owns row tiles (activations fetched once, the weights once
+    const int id = blockIdx.x, grp = id / (8 * NT), rem = id % (8 * NT);   // per XCD): for many rows and few columns the
+    const int rows = min(8, MT - grp * 8);                                 // activation operand is the larger one
+    tile_n = rem / rows;
+    tile_m = grp * 8 + rem % rows;
   }
   __shared__ float rs[BM];
-  EpiPre<BM, BN, EPI> pre;
+  __shared__ int s_pos[EPI == EPI_QKV ? 2 * BM : 2];    // EPI_QKV: (slot, image index) per tile row; the rotary factors are read from
+                                                        // their table in memory (an LDS copy per row would keep a second workgroup off the CU)
+  constexpr bool EARLY = EPI != EPI_RESID;   // the residual tile is read in the epilogue: early copies of a tile this size do not fit the registers
+  EpiPre<BM, BN, EPI, EARLY> pre;
+  pre.rope_lds = false;
   const int KB = K >> 4, nst = KB >> 1;
   const int last_rb = (M - 1) >> 5;
   RowScale<BM> rowscale;                   // the epilogue's inputs first: they are the oldest loads and so never wait behind a stage
+  pre.first(tile_m, M, ep);
   rowscale.load(tile_m, M, ep);
-  pre.start(tile_m, tile_n, M, N, ep);
+  if (EPI != EPI_QKV) pre.start(tile_m, tile_n, M, N, ep);
   __builtin_amdgcn_sched_barrier(0);
   const u32x4* src[PER];
 #pragma unroll
@@ -679,7 +698,7 @@ __global__ __launch_bounds__(256) void k_gemm_shared_dma(const uint4* __restrict
   // stage t -> slot t % NS; stages past the end repeat the last one (never read)
   auto request = [&](int t) {
     const size_t kk = (size_t)min(t, nst - 1) * 128;
-    const uint32_t slot = lds_base + (uint32_t)((t & (NS - 1)) * NBLK) * 1024u;
+    const uint32_t slot = lds_base + (uint32_t)((t % NS) * NBLK) * 1024u;
 #pragma unroll
     for (int i = 0; i < PER; ++i) lds_dma16(src[i] + kk, slot + (uint32_t)(wave + 4 * i) * 1024u);
   };
@@ -692,13 +711,18 @@ __global__ __launch_bounds__(256) void k_gemm_shared_dma(const uint4* __restrict
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 #pragma unroll
   for (int t = 0; t < NS - 1; ++t) request(t);
+  // EPI_QKV: the row's position depends on a loaded value (its cache length); it is turned into (slot, image index) only
+  // now, behind the first stage requests, so that this wait is not on the path to them.  (Loads the compiler issues are
+  // counted by the same counter as the stage loads: its waits and the hand-written ones below can only become stricter.)
+  if (EPI == EPI_QKV) pre.start(tile_m, tile_n, M, N, ep);
+  __builtin_amdgcn_sched_barrier(0);
   VVS_PHASE_MARK(1);
 #define VVS_WAIT_STAGES asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PER * (NS - 3)) : "memory")
   VVS_WAIT_STAGES;                         // stages 0 and 1 of this wave have landed
   __syncthreads();                         // ... and everybody else's
 #define VVS_S2F(FA, FB, T, KBO)                                                                                       \
   {                                                                                                                   \
-    const int sl = ((T) & (NS - 1)) * NBLK;                                                                           \
+    const int sl = ((T) % NS) * NBLK;                                                                                 \
     _Pragma("unroll") for (int t = 0; t < WM; ++t)                                                                    \
         FA[t] = __builtin_bit_cast(bf16x8, stage[(sl + (wr * WM + t) * 2 + (KBO)) * 64 + lane]);                      \
     _Pragma("unroll") for (int t = 0; t < WN; ++t)                                                                    \
@@ -727,6 +751,7 @@ __global__ __launch_bounds__(256) void k_gemm_shared_dma(const uint4* __restrict
 #undef VVS_MMA
 #undef VVS_S2F
   VVS_PHASE_MARK(2);
+  pre.to_lds(s_pos, nullptr, ep);
   rowscale.finish(rs, tile_m, M, ep);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the repeated last stages still in flight must land before the tile reuses their LDS
 #undef VVS_WAIT_STAGES
@@ -740,7 +765,7 @@ __global__ __launch_bounds__(256) void k_gemm_shared_dma(const uint4* __restrict
         red[((wr * WM + i) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * LDC + (wc * WN + j) * 32 + (lane & 31)] = acc[i][j][r];
   __syncthreads();
   VVS_PHASE_MARK(3);
-  tile_epilogue<BM, BN, 1, EPI>(red, rs, tile_m, tile_n, M, N, C, ep, pre, nullptr, nullptr);
+  tile_epilogue<BM, BN, 1, EPI, EARLY>(red, rs, tile_m, tile_n, M, N, C, ep, pre, s_pos, nullptr);
   VVS_PHASE_MARK(4);
 }
 
@@ -777,6 +802,11 @@ static void launch_gemm_direct(const bf16_t* A, const bf16_t* W, float* C, int M
 
 template <int EPI>
 static void gemm_dispatch(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, GemmPlan p, const GemmEpi& ep, hipStream_t s) {
+  if constexpr (EPI == EPI_QKV) {
+    // many rows (two or more full rounds of 128 x 128 tiles): the direct-to-LDS kernel, two workgroups per CU
+    const int tiles = ((M + 127) / 128) * (N / 128);
+    if (p.bm == 128 && p.bn == 128 && tiles >= 512) { launch_gemm_shared_dma<2, 2, 4, EPI>(A, W, C, M, N, K, ep, s); return; }
+  }
   if constexpr (EPI == EPI_PARTIAL || EPI == EPI_SWIGLU) {
     // the stages are loaded straight into LDS.  A single round of tiles (at most one workgroup per CU): 8 slots, 6
     // stages in flight.  Two or more full rounds: 4 slots, so that the LDS (the 68 KB of the output tile) lets two
@@ -817,6 +847,14 @@ void mfma_gemm_resid(Ctx* c, const bf16_t* A, const bf16_t* W, float* x, bf16_t*
                      hipStream_t s) {
   GemmEpi ep{};
   ep.x = x; ep.xb = xb; ep.ss_out = ss_out; ep.g_next = g_next; ep.NS = (c->d / 64 + 3) & ~3;
+  // many rows: 192 x 128 tiles with the operands shared through LDS (a quarter of the bytes per flop that 64 x 64 tiles pull
+  // through a CU's L1), when they give most CUs a tile - at d = 1280 and 3904 rows: 210 tiles, one round
+  if (c->d % 128 == 0 && K % 32 == 0 && ((M + 191) / 192) * (c->d / 128) >= 160) {
+    // fabric traffic of the two tile orders: the operand an XCD does not own is fetched by all 8 of them
+    ep.row_owner = (size_t)M + 8 * (size_t)c->d < 8 * (size_t)M + (size_t)c->d;
+    launch_gemm_shared_dma<3, 2, 6, EPI_RESID>(A, W, nullptr, M, c->d, K, ep, s);
+    return;
+  }
   launch_gemm_direct<2, 2, 6, EPI_RESID>(A, W, nullptr, M, c->d, K, 1, ep, s);
 }
 
@@ -855,17 +893,21 @@ void mfma_gemm_qkv(Ctx* c, int layer, const bf16_t* A, const bf16_t* Wqkv, const
 // by exactly one wave, so there is nothing to share through LDS; the 4 waves take 32-key steps
 // round-robin and merge their partial (max, sum, O) through LDS at the end.  Only the last T keys (the
 // block itself) are masked.
-template <int DH, int NQB, int NW, int PD>
-__global__ __launch_bounds__(NW * 64, (DH * NQB >= 256 ? 1 : 2)) void k_attn_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc,
+// QG > 1: the queries are dealt to QG groups of NW waves (group g takes queries g * NQB * 16 ...); every group runs over all
+// keys.  More than 32 queries per wave need more registers than leave room for a second workgroup on the CU, and a
+// lone workgroup pays its start-up (first requests, merge) with nothing to cover it; two groups of 32 queries keep
+// three workgroups resident, and the second group's K/V requests mostly hit the lines the first one brought in.
+template <int DH, int NQB, int NW, int PD, int QG = 1>
+__global__ __launch_bounds__(NW * QG * 64, (DH * NQB >= 256 ? 1 : 2)) void k_attn_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ kc,
                                                    const bf16_t* __restrict__ vc, bf16_t* __restrict__ out, TreeDesc tree,
                                                    PosDesc pos, int T, int d, size_t row_stride, size_t head_stride, float c_exp,
                                                    int cap_steps) {
   constexpr int KD = DH / 32, DT = DH / 16, NQ = NQB * 16;
-  __shared__ float s_m[NW - 1][NQ], s_l[NW - 1][NQ];
-  __shared__ float s_o[NW - 1][NQ][DH + 1];
+  __shared__ float s_m[QG][NW - 1][NQ], s_l[QG][NW - 1][NQ];
+  __shared__ float s_o[QG][NW - 1][NQ][DH + 1];
   VVS_PHASE_MARK(0);
   const int hd = blockIdx.x, r = blockIdx.y;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = (threadIdx.x >> 6) % NW, qg = (threadIdx.x >> 6) / NW, q0 = qg * NQ;
   const int g = lane >> 4, ql = lane & 15;
   const int S = pos.kv_len ? pos.kv_len[r >> 1] : pos.kv_base;
   const int n_keys = S + T;
@@ -879,7 +921,7 @@ __global__ __launch_bounds__(NW * 64, (DH * NQB >= 256 ? 1 : 2)) void k_attn_mfm
   for (int qb = 0; qb < NQB; ++qb) {
     // query rows past T repeat row T - 1: a query only ever touches its own lanes' columns and rows >= T
     // are not stored, so nothing has to be zeroed - and no load result is needed before the first MFMA
-    const int tq = min(qb * 16 + ql, T - 1);
+    const int tq = min(q0 + qb * 16 + ql, T - 1);
     mask[qb] = tree.anc[tq];
 #pragma unroll
     for (int kd = 0; kd < KD; ++kd)
@@ -997,11 +1039,11 @@ __global__ __launch_bounds__(NW * 64, (DH * NQB >= 256 ? 1 : 2)) void k_attn_mfm
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb) {
       const int qi = qb * 16 + ql;
-      if (g == 0) { s_m[wave - 1][qi] = m_run[qb]; s_l[wave - 1][qi] = l_run[qb]; }
+      if (g == 0) { s_m[qg][wave - 1][qi] = m_run[qb]; s_l[qg][wave - 1][qi] = l_run[qb]; }
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) s_o[wave - 1][qi][dt * 16 + 4 * g + rr] = o[qb][dt][rr];
+        for (int rr = 0; rr < 4; ++rr) s_o[qg][wave - 1][qi][dt * 16 + 4 * g + rr] = o[qb][dt][rr];
     }
   }
   __syncthreads();
@@ -1012,18 +1054,18 @@ __global__ __launch_bounds__(NW * 64, (DH * NQB >= 256 ? 1 : 2)) void k_attn_mfm
       const int qi = qb * 16 + ql;
       float m = m_run[qb];
 #pragma unroll
-      for (int w = 0; w < NW - 1; ++w) m = fmaxf(m, s_m[w][qi]);
+      for (int w = 0; w < NW - 1; ++w) m = fmaxf(m, s_m[qg][w][qi]);
       const float m_safe = m == -INFINITY ? 0.f : m;
       const float a0 = exp2f((m_run[qb] - m_safe) * c_exp);
       float l = l_run[qb] * a0;
       float aw[NW - 1];
 #pragma unroll
       for (int w = 0; w < NW - 1; ++w) {
-        aw[w] = exp2f((s_m[w][qi] - m_safe) * c_exp);
-        l += s_l[w][qi] * aw[w];
+        aw[w] = exp2f((s_m[qg][w][qi] - m_safe) * c_exp);
+        l += s_l[qg][w][qi] * aw[w];
       }
       const float inv = 1.0f / l;
-      if (qi < T) {
+      if (q0 + qi < T) {
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
           uint32_t pk[2];
@@ -1032,12 +1074,12 @@ __global__ __launch_bounds__(NW * 64, (DH * NQB >= 256 ? 1 : 2)) void k_attn_mfm
             float v0 = o[qb][dt][rr] * a0, v1 = o[qb][dt][rr + 1] * a0;
 #pragma unroll
             for (int w = 0; w < NW - 1; ++w) {
-              v0 += s_o[w][qi][dt * 16 + 4 * g + rr] * aw[w];
-              v1 += s_o[w][qi][dt * 16 + 4 * g + rr + 1] * aw[w];
+              v0 += s_o[qg][w][qi][dt * 16 + 4 * g + rr] * aw[w];
+              v1 += s_o[qg][w][qi][dt * 16 + 4 * g + rr + 1] * aw[w];
             }
             pk[rr >> 1] = pack2bf(v0 * inv, v1 * inv);
           }
-          *(uint2*)(out + pack_index(r * T + qi, hd * DH + dt * 16 + 4 * g, d)) = make_uint2(pk[0], pk[1]);   // O-projection operand layout
+          *(uint2*)(out + pack_index(r * T + q0 + qi, hd * DH + dt * 16 + 4 * g, d)) = make_uint2(pk[0], pk[1]);   // O-projection operand layout
         }
       }
     }
@@ -1053,15 +1095,15 @@ void mfma_attention(Ctx* c, int layer, const TreeDesc& tree, const PosDesc& pos,
   const float c_exp = 1.4426950408889634f / sqrtf((float)c->dh);
   dim3 grid(c->H, c->R);
   const int nqb = T <= 16 ? 1 : (T <= 32 ? 2 : 4);
-#define VVS_ATTN(DH, NQB, NW, PD)                                                                                                 \
-  hipLaunchKernelGGL((k_attn_mfma<DH, NQB, NW, PD>), grid, dim3(NW * 64), 0, s, q, kc, vc, out, tree, pos, T, c->d, c->kv_row_stride, \
+#define VVS_ATTN(DH, NQB, NW, PD, QG)                                                                                                  \
+  hipLaunchKernelGGL((k_attn_mfma<DH, NQB, NW, PD, QG>), grid, dim3(NW * QG * 64), 0, s, q, kc, vc, out, tree, pos, T, c->d, c->kv_row_stride, \
                      c->kv_head_stride, c_exp, c->S_cap >> 5)
   // 4 waves per workgroup keep the register footprint low enough for 2-3 workgroups per CU, so that
   // every (head, row) pair of a call is resident at once
   if (c->dh == 64) {
-    if (nqb == 1) VVS_ATTN(64, 1, 4, 2); else if (nqb == 2) VVS_ATTN(64, 2, 4, 2); else VVS_ATTN(64, 4, 4, 2);
+    if (nqb == 1) VVS_ATTN(64, 1, 4, 2, 1); else if (nqb == 2) VVS_ATTN(64, 2, 4, 2, 1); else VVS_ATTN(64, 2, 2, 2, 2);   // 33 .. 64 queries: two groups of 32
   } else {
-    if (nqb == 1) VVS_ATTN(128, 1, 4, 2); else VVS_ATTN(128, 2, 4, 2);   // T <= 32 is enforced at context creation for head size 128
+    if (nqb == 1) VVS_ATTN(128, 1, 4, 2, 1); else VVS_ATTN(128, 2, 4, 2, 1);   // T <= 32 is enforced at context creation for head size 128
   }
 #undef VVS_ATTN
 }
