@@ -234,6 +234,13 @@ def test_7b_slice_reduced(gc):
         show(f"7b-like n_forced={n_forced}", run_bf16_case(gc, shape, n_forced=n_forced, calls=2, gain_jitter=0.1))
 
 
+def test_head_size_128_with_a_tree_of_20_nodes(gc):
+    """Head size 128 with 21 query tokens per row (a 20-node depth-4 tree): the attention instantiation with two
+    16-query blocks per wave at that head size, whose merge buffers exceed 64 KB of LDS."""
+    shape = synth.SEVEN_B.replace(n_layers=2, d_model=2048, n_heads=16, d_ff=5504, n_nodes=20, tree_widths=(4, 6, 6, 4))
+    show("head size 128, 20-node tree", run_bf16_case(gc, shape, n_forced=40, calls=2))
+
+
 @pytest.mark.parametrize("kv_len", [64, 512, 1000])
 def test_7b_slice_full_width_two_layers(gc, kv_len):
     """Config 4 as specified - full width (d = 4096, 32 heads of 128, d_ff = 11008, 65536 ids with the 8192-id
