@@ -653,6 +653,9 @@ __global__ __launch_bounds__(256) void k_gemm_shared_dma(const uint4* __restrict
                                                          int M, int N, int K, const GemmEpi ep) {
   static_assert(NS >= 4, "at least three stages in flight");
   constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32, LDC = BN + 4;
+  // The output tile goes through LDS for the epilogue.  A tile too large for that (256 x 256) goes in RP = 2 passes of
+  // BM / 2 rows - the rows of one wave row - so that LDS only ever holds half of it.
+  constexpr int RP = (size_t)BM * LDC * sizeof(float) > 140 * 1024 ? 2 : 1, EM = BM / RP;
   constexpr int NA = 2 * (BM / 32), NBLK = NA + 2 * (BN / 32), PER = NBLK / 4;
   static_assert(NBLK % 4 == 0, "blocks of a stage are dealt to 4 waves");
   static_assert(PER * (NS - 1) <= 60, "the load counter has 6 bits");
@@ -679,14 +682,19 @@ __global__ __launch_bounds__(256) void k_gemm_shared_dma(const uint4* __restrict
   __shared__ int s_pos[EPI == EPI_QKV ? 2 * BM : 2];    // EPI_QKV: (slot, image index) per tile row; the rotary factors are read from
                                                         // their table in memory (an LDS copy per row would keep a second workgroup off the CU)
   constexpr bool EARLY = EPI != EPI_RESID;   // the residual tile is read in the epilogue: early copies of a tile this size do not fit the registers
-  EpiPre<BM, BN, EPI, EARLY> pre;
-  pre.rope_lds = false;
+  EpiPre<EM, BN, EPI, EARLY> pre[RP];        // epilogue inputs of each pass (a pass is a tile of EM rows at row tile tile_m * RP + p)
+#pragma unroll
+  for (int p = 0; p < RP; ++p) pre[p].rope_lds = false;
   const int KB = K >> 4, nst = KB >> 1;
   const int last_rb = (M - 1) >> 5;
   RowScale<BM> rowscale;                   // the epilogue's inputs first: they are the oldest loads and so never wait behind a stage
-  pre.first(tile_m, M, ep);
+#pragma unroll
+  for (int p = 0; p < RP; ++p) pre[p].first(tile_m * RP + p, M, ep);
   rowscale.load(tile_m, M, ep);
-  if (EPI != EPI_QKV) pre.start(tile_m, tile_n, M, N, ep);
+  if (EPI != EPI_QKV) {
+#pragma unroll
+    for (int p = 0; p < RP; ++p) pre[p].start(tile_m * RP + p, tile_n, M, N, ep);
+  }
   __builtin_amdgcn_sched_barrier(0);
   const u32x4* src[PER];
 #pragma unroll
@@ -714,7 +722,10 @@ __global__ __launch_bounds__(256) void k_gemm_shared_dma(const uint4* __restrict
   // EPI_QKV: the row's position depends on a loaded value (its cache length); it is turned into (slot, image index) only
   // now, behind the first stage requests, so that this wait is not on the path to them.  (Loads the compiler issues are
   // counted by the same counter as the stage loads: its waits and the hand-written ones below can only become stricter.)
-  if (EPI == EPI_QKV) pre.start(tile_m, tile_n, M, N, ep);
+  if (EPI == EPI_QKV) {
+#pragma unroll
+    for (int p = 0; p < RP; ++p) pre[p].start(tile_m * RP + p, tile_n, M, N, ep);
+  }
   __builtin_amdgcn_sched_barrier(0);
   VVS_PHASE_MARK(1);
 #define VVS_WAIT_STAGES asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PER * (NS - 3)) : "memory")
@@ -736,43 +747,90 @@ __global__ __launch_bounds__(256) void k_gemm_shared_dma(const uint4* __restrict
   }
   bf16x8 fa0[WM], fb0[WN], fa1[WM], fb1[WN];
   VVS_S2F(fa0, fb0, 0, 0)
+  // One stage = two groups of WM * WN MFMAs (contraction blocks 0 and 1).  A wave issues in order and an MFMA keeps its pipe
+  // for 32 clocks, during which the wave may issue other kinds of instructions for free - but only if they stand BETWEEN
+  // two MFMAs in program order.  So everything else a stage needs is dealt into the gaps, one or two items behind each MFMA:
+  //   group A (fragments of block 0, read during the previous stage): the LDS reads of block 1 of this stage, then the
+  //     stage requests for stage s + NS - 1 (into the slot stage s - 1 has left: everybody finished reading it before
+  //     the last barrier);
+  //   group B (block 1): the LDS reads of block 0 of stage s + 1 and, half way, the wait for this wave's part of stage
+  //     s + 2 and the barrier - a bare s_barrier: the only LDS reads that must be complete before a slot is overwritten
+  //     are those of stage s, and the MFMAs of group B have consumed them; waiting for the reads just issued (what
+  //     __syncthreads would add) would drain the MFMA pipe once per stage.
+  constexpr int NM = WM * WN, NR = WM + WN;
+  constexpr int IA = (NR + PER + NM - 1) / NM;          // items per gap in group A
+  constexpr int IB = (NR + NM - 1) / NM;                // items per gap in group B
+  auto lds_frag = [&](int t, int kbo, int i) {           // i-th fragment of a stage's block kbo: A rows first, then B rows
+    const int sl = (t % NS) * NBLK;
+    return __builtin_bit_cast(bf16x8, stage[(sl + (i < WM ? (wr * WM + i) * 2 : NA + (wc * WN + (i - WM)) * 2) + kbo) * 64 + lane]);
+  };
   for (int s = 0; s < nst; ++s) {
-    request(s + NS - 1);                   // into the slot of stage s - 1: everybody finished reading it before the last barrier
-    VVS_S2F(fa1, fb1, s, 1)
-    __builtin_amdgcn_sched_barrier(0);
-    VVS_MMA(fa0, fb0)
-    __builtin_amdgcn_sched_barrier(0);
-    VVS_S2F(fa0, fb0, s + 1, 0)
-    __builtin_amdgcn_sched_barrier(0);
-    VVS_MMA(fa1, fb1)
-    VVS_WAIT_STAGES;                       // this wave's part of stage s + 2
-    __syncthreads();
+    const size_t kk = (size_t)min(s + NS - 1, nst - 1) * 128;
+    const uint32_t slot = lds_base + (uint32_t)(((s + NS - 1) % NS) * NBLK) * 1024u;
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+      acc[m / WN][m % WN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[m / WN], fb0[m % WN], acc[m / WN][m % WN], 0, 0, 0);
+#pragma unroll
+      for (int it = m * IA; it < (m + 1) * IA; ++it) {
+        if (it < NR) {
+          if (it < WM) fa1[it] = lds_frag(s, 1, it); else fb1[it - WM] = lds_frag(s, 1, it);
+        } else if (it - NR < PER) {
+          const int i = it - NR;
+          lds_dma16(src[i] + kk, slot + (uint32_t)(wave + 4 * i) * 1024u);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+      acc[m / WN][m % WN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[m / WN], fb1[m % WN], acc[m / WN][m % WN], 0, 0, 0);
+#pragma unroll
+      for (int it = m * IB; it < (m + 1) * IB; ++it) {
+        if (it < NR) {
+          if (it < WM) fa0[it] = lds_frag(s + 1, 0, it); else fb0[it - WM] = lds_frag(s + 1, 0, it);
+        }
+      }
+      if (m == NM / 2) {
+        VVS_WAIT_STAGES;                   // this wave's part of stage s + 2
+        __builtin_amdgcn_s_barrier();      // ... and everybody else's; and everybody is done reading stage s
+        asm volatile("" ::: "memory");
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
 #undef VVS_MMA
 #undef VVS_S2F
   VVS_PHASE_MARK(2);
-  pre.to_lds(s_pos, nullptr, ep);
+#pragma unroll
+  for (int p = 0; p < RP; ++p) pre[p].to_lds(s_pos + p * 2 * EM, nullptr, ep);
   rowscale.finish(rs, tile_m, M, ep);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the repeated last stages still in flight must land before the tile reuses their LDS
 #undef VVS_WAIT_STAGES
   __syncthreads();                         // the stage buffers become the output tile
 #pragma unroll
-  for (int i = 0; i < WM; ++i)
+  for (int p = 0; p < RP; ++p) {
+    if (RP == 1 || wr == p) {              // RP == 2: pass p holds the rows of wave row p
 #pragma unroll
-    for (int j = 0; j < WN; ++j)
+      for (int i = 0; i < WM; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        red[((wr * WM + i) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * LDC + (wc * WN + j) * 32 + (lane & 31)] = acc[i][j][r];
-  __syncthreads();
-  VVS_PHASE_MARK(3);
-  tile_epilogue<BM, BN, 1, EPI, EARLY>(red, rs, tile_m, tile_n, M, N, C, ep, pre, s_pos, nullptr);
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            red[(((RP == 1 ? wr * WM : 0) + i) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * LDC + (wc * WN + j) * 32 + (lane & 31)] = acc[i][j][r];
+    }
+    __syncthreads();
+    VVS_PHASE_MARK(3);
+    tile_epilogue<EM, BN, 1, EPI, EARLY>(red, rs + p * EM, tile_m * RP + p, tile_n, M, N, C, ep, pre[p], s_pos + p * 2 * EM, nullptr);
+    if (p + 1 < RP) __syncthreads();       // the next pass overwrites the tile
+  }
   VVS_PHASE_MARK(4);
 }
 
 template <int WM, int WN, int NS, int EPI>
 static void launch_gemm_shared_dma(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, const GemmEpi& ep, hipStream_t s) {
   constexpr int BM = 2 * WM * 32, BN = 2 * WN * 32;
-  constexpr size_t lds_tile = (size_t)BM * (BN + 4) * sizeof(float), lds_stage = (size_t)NS * (2 * (BM + BN) / 32) * 1024;
+  constexpr size_t lds_full = (size_t)BM * (BN + 4) * sizeof(float), lds_tile = lds_full > 140 * 1024 ? lds_full / 2 : lds_full;   // two passes
+  constexpr size_t lds_stage = (size_t)NS * (2 * (BM + BN) / 32) * 1024;
   constexpr size_t lds = lds_tile > lds_stage ? lds_tile : lds_stage;
   allow_dynamic_lds(reinterpret_cast<const void*>(&k_gemm_shared_dma<WM, WN, NS, EPI>), lds);
   dim3 grid((N / BN) * ((M + BM - 1) / BM), 1, 1);
@@ -802,6 +860,16 @@ static void launch_gemm_direct(const bf16_t* A, const bf16_t* W, float* C, int M
 
 template <int EPI>
 static void gemm_dispatch(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, GemmPlan p, const GemmEpi& ep, hipStream_t s) {
+  if constexpr (EPI != EPI_RESID) {
+    // very many rows: 256 x 256 tiles (128 x 128 per wave, the accumulators fill the 256 AGPRs; half the operand bytes per
+    // flop of a 128 x 128 tile come through a CU's L1), when they give (nearly) every CU a tile.  EPI_QKV: a tile must lie
+    // inside one of the q / k / v thirds.
+    const int t256 = ((M + 255) / 256) * (N / 256);
+    if (p.bm == 128 && p.bn == 128 && N % 256 == 0 && t256 >= 224 && (EPI != EPI_QKV || ep.d % 256 == 0)) {
+      launch_gemm_shared_dma<4, 4, 4, EPI>(A, W, C, M, N, K, ep, s);
+      return;
+    }
+  }
   if constexpr (EPI == EPI_QKV) {
     // many rows (two or more full rounds of 128 x 128 tiles): the direct-to-LDS kernel, two workgroups per CU
     const int tiles = ((M + 127) / 128) * (N / 128);

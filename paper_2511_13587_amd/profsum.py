@@ -4,6 +4,7 @@
     python -m paper_2511_13587_amd.profsum kernels <results.db>
     python -m paper_2511_13587_amd.profsum counters <results.db>
     python -m paper_2511_13587_amd.profsum pivot <results.db> [<results.db> ...]
+    python -m paper_2511_13587_amd.profsum ratios <results.db> [<results.db> ...]
     python -m paper_2511_13587_amd.profsum window <results.db> <first kernel substring> <last kernel substring>
     python -m paper_2511_13587_amd.profsum traffic <fetch.db> <write.db> <kernel substring> <grid_x list, workgroups> [out.json]
 
@@ -14,6 +15,11 @@ call of the first kernel.
 `pivot`: one line per (hot kernel, grid) with every counter of the given --pmc runs as a column (average per
 dispatch, summed over the chip's instances as rocprofv3 reports them), for reading ratios such as MFMA-busy
 cycles per CU-busy cycle.
+
+`ratios`: the same dispatches as `pivot`, reduced to the ratios that say what a kernel waits for: MFMA-busy cycles per
+SIMD cycle of the busy CUs (SQ_VALU_MFMA_BUSY_CYCLES counts per SIMD, SQ_BUSY_CU_CYCLES per CU), the share of wave
+cycles spent waiting for any instruction / for LDS, VALU-active share, L2 hit rate, mean L1-to-L2 read latency in
+cycles, LDS bank-conflict cycles per LDS-active cycle.
 
 `traffic`: HBM bytes per launch of one kernel from a FETCH_SIZE run and a WRITE_SIZE run (KiB per
 dispatch), each scaled by what the same counter reads for the 256 MiB k_copy_bytes launches of the
@@ -91,6 +97,29 @@ def pivot(dbs) -> str:
     return "\n".join(out)
 
 
+def ratios(dbs) -> str:
+    table = {}
+    for db in dbs:
+        cur = sqlite3.connect(db).cursor()
+        rows = cur.execute("select kernel_name, grid_size_x / workgroup_size_x, grid_size_y / workgroup_size_y, grid_size_z / workgroup_size_z, "
+                           "counter_name, count(*), avg(value) from counters_collection where kernel_name like '%gemm%' or kernel_name like "
+                           "'%attn%' or kernel_name like '%accept_node%' or kernel_name like '%rmsnorm%' group by 1, 2, 3, 4, 5").fetchall()
+        for n, gx, gy, gz, cn, c, v in rows:
+            table.setdefault((short(n)[:44], gx, gy, gz), {"dispatches": c})[cn] = v
+    nan = float("nan")
+
+    def div(r, a, b, k=1.0):
+        return r[a] / (k * r[b]) if a in r and b in r and r[b] else nan
+
+    out = [f"{'kernel':44s} {'grid':>14s} {'disp':>6s} {'mfma_util':>9s} {'wait_any':>8s} {'wait_lds':>8s} {'valu':>6s} {'l2_hit':>6s} {'l1_l2_lat':>9s} {'bank_conf':>9s}"]
+    for (n, gx, gy, gz), r in sorted(table.items()):
+        out.append(f"{n:44s} {f'({gx},{gy},{gz})':>14s} {r['dispatches']:6d} {div(r, 'SQ_VALU_MFMA_BUSY_CYCLES', 'SQ_BUSY_CU_CYCLES', 4.0):9.2f} "
+                   f"{div(r, 'SQ_WAIT_INST_ANY', 'SQ_WAVE_CYCLES'):8.2f} {div(r, 'SQ_WAIT_INST_LDS', 'SQ_WAVE_CYCLES'):8.3f} "
+                   f"{div(r, 'SQ_ACTIVE_INST_VALU', 'SQ_WAVE_CYCLES'):6.2f} {div(r, 'TCC_HIT_sum', 'TCC_REQ_sum'):6.2f} "
+                   f"{div(r, 'TCP_TCC_READ_REQ_LATENCY_sum', 'TCP_TCC_READ_REQ_sum'):9.0f} {div(r, 'SQ_LDS_BANK_CONFLICT', 'SQ_LDS_IDX_ACTIVE'):9.2f}")
+    return "\n".join(out)
+
+
 def traffic(fetch_db: str, write_db: str, kernel: str, grids, out_json=None) -> str:
     import json
     res = {"kernel": kernel, "grids_x_workgroups": grids, "copy_bytes": 256 << 20}
@@ -120,8 +149,8 @@ if __name__ == "__main__":
     if len(sys.argv) >= 6 and sys.argv[1] == "traffic":
         print(traffic(sys.argv[2], sys.argv[3], sys.argv[4], [int(g) for g in sys.argv[5].split(",")],
                       sys.argv[6] if len(sys.argv) > 6 else None))
-    elif len(sys.argv) >= 3 and sys.argv[1] == "pivot":
-        print(pivot(sys.argv[2:]))
+    elif len(sys.argv) >= 3 and sys.argv[1] in ("pivot", "ratios"):
+        print(pivot(sys.argv[2:]) if sys.argv[1] == "pivot" else ratios(sys.argv[2:]))
     elif len(sys.argv) == 5 and sys.argv[1] == "window":
         print(window(sys.argv[2], sys.argv[3], sys.argv[4]))
     elif len(sys.argv) == 3 and sys.argv[1] in ("kernels", "counters"):

@@ -22,10 +22,12 @@ def bf16_round(a):
 # ------------------------------------------------------------------------------------------------ GEMM unit parity
 @pytest.mark.parametrize("m,n,k", [(48, 2304, 768), (432, 1280, 3456), (100, 128, 64), (1, 64, 64), (27, 3840, 1280), (28, 22016, 256),
                                    (300, 6912, 1280), (1024, 3840, 1280),
-                                   (432, 6912, 1280), (257, 20480, 64), (193, 20480, 448), (1000, 8192, 192)])
+                                   (432, 6912, 1280), (257, 20480, 64), (193, 20480, 448), (1000, 8192, 192),
+                                   (1800, 8192, 192), (2000, 7680, 64), (3904, 3840, 1280)])
 def test_gemm_bf16_mfma(gc, m, n, k):
     """Spans every tile shape and split-K plan of both GEMM kernels (per-wave operands; operands shared
-    through LDS: full groups of stages, tail stages only, both), ragged M, one row."""
+    through LDS: full groups of stages, tail stages only, both; 256 x 256 tiles with the two-pass epilogue,
+    ragged last row tile), ragged M, one row."""
     pair = gc.Pair(synth.B_SHAPE.replace(n_layers=1, n_prompts=1, vocab=1024, logit_hi=1024), with_oracle=False)
     rng = np.random.default_rng(m * 7 + n)
     a = bf16_round(rng.standard_normal((m, k)))
