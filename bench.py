@@ -165,6 +165,8 @@ def main():
                          "roofline.traffic is taken; without it traffic is null")
     ap.add_argument("--mode", choices=["strict", "relaxed"], default="strict")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--latency-calls", type=int, default=100,
+                    help="single calls timed with events, warm and with the caches flushed before each (0 = skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain 256 MiB copy kernel (k_copy_bytes) three times, for scaling hardware traffic counters")
     ap.add_argument("--graph", action="store_true",
@@ -348,6 +350,30 @@ def main():
         state = state_mid
     ctx.vvs_set_state(state)
 
+    # latency of single calls (set state + verify + commit), each bracketed by two events on the stream the library
+    # launches on: warm = back to back; cold = a 768 MiB fill before every call, which replaces the contents of the
+    # 8 x 4 MB L2 and of the 256 MB memory-side cache
+    per_call = None
+    if not args.graph and args.latency_calls > 0:
+        def timed_calls(n, flush):
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+            for i, (e0, e1) in enumerate(ev):
+                if flush is not None:
+                    flush.fill_(float(i))
+                e0.record()
+                step()
+                e1.record()
+            torch.cuda.synchronize()
+            return np.array([e0.elapsed_time(e1) for e0, e1 in ev])
+        warm_t = timed_calls(args.latency_calls, None)
+        flush = torch.empty(192 << 20, dtype=torch.float32, device=dev)
+        cold_t = timed_calls(args.latency_calls, flush)
+        del flush
+        per_call = {"calls": args.latency_calls, "cache_len": int(state0[0, 0]),
+                    "warm_ms": {"median": float(np.median(warm_t)), "p10": float(np.percentile(warm_t, 10)), "p90": float(np.percentile(warm_t, 90))},
+                    "cold_ms": {"median": float(np.median(cold_t)), "p10": float(np.percentile(cold_t, 10)), "p90": float(np.percentile(cold_t, 90))}}
+        ctx.vvs_set_state(state)
+
     # per-kernel-class durations from HIP events recorded by the library on this stream
     ctx.vvs_timing_enable(True)
     tsteps = min(args.steps, 10)
@@ -413,7 +439,7 @@ def main():
         "draft_noise_calibration": None if calibration is None else {str(k): v for k, v in calibration.items()},
         "at_draft_noise_1.0": {"tokens_per_forward": float(accept_low.mean()) + 1.0,
                                "verified_tokens_per_s": float(accept_low.sum() + len(accept_low)) / n_sets / (ms_per_step * 1e-3)},
-        "latency_by_cache_len": latency_by_cache, "caches": "warm (no flush between steps; the weights alone exceed every cache)", "scored_draft_tokens_per_s": B * N / (ms_per_step * 1e-3),
+        "latency_by_cache_len": latency_by_cache, "latency_per_call": per_call, "caches": "warm (no flush between steps; the weights alone exceed every cache)", "scored_draft_tokens_per_s": B * N / (ms_per_step * 1e-3),
         "whole_pass": {"algorithmic_GB": total_bytes / 1e9, "algorithmic_TFLOP": (cnt["gemm_flops"] + cnt["attn_flops"]) / 1e12,
                        "hbm_frac": total_bytes / (ms_per_step * 1e-3) / (HBM_PEAK_GBS * 1e9),
                        "mfma_frac": (cnt["gemm_flops"] + cnt["attn_flops"]) / (ms_per_step * 1e-3) / (MFMA_BF16_PEAK_TFLOPS * 1e12)},
