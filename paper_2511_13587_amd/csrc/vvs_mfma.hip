@@ -18,6 +18,26 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes as a n
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
+// Maximum / sum over the four lanes l % 16 + 16 j of a wave (the four 16-lane rows), left in all four, with gfx950's row
+// swaps: v_permlane16_swap exchanges the odd rows of its first operand with the even rows of its second, v_permlane32_swap
+// the upper half of the first with the lower half of the second - given the same value twice they return (x of the
+// even / lower partner, x of the odd / upper partner) in every lane.  Plain VALU instructions: the LDS crossbar that a
+// __shfl_xor goes through costs a round trip per step of these dependent chains.  Same order of additions as
+// x += xor16(x); x += xor32(x).
+typedef unsigned uintx2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float rows_max(float x) {
+  uintx2 p = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = fmaxf(__uint_as_float(p[0]), __uint_as_float(p[1]));
+  p = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(p[0]), __uint_as_float(p[1]));
+}
+__device__ __forceinline__ float rows_sum(float x) {
+  uintx2 p = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = __uint_as_float(p[0]) + __uint_as_float(p[1]);
+  p = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(p[0]) + __uint_as_float(p[1]);
+}
+
 // Phase marks: a profiling build may define VVS_PHASE_MARK(i) to record a time stamp at the i-th
 // point of a kernel (entry, operands requested, main loop done, tile in LDS, end); normally nothing.
 #ifndef VVS_PHASE_MARK
@@ -58,6 +78,7 @@ struct GemmEpi {
   const float* ss; int NS; float eps; int dnorm;           // row scale (ss == nullptr: no scaling); ss[M][NS]
   bf16_t* act; int F;                                      // EPI_SWIGLU
   float* x; bf16_t* xb; float* ss_out; const float* g_next; // EPI_RESID (g_next: gain of the norm that reads x next)
+  int xb_T;                                                // EPI_RESID: > 0 = xb in the row-padded layout (row m at (m / xb_T) * 32 + m % xb_T)
   bf16_t* q; bf16_t* kc; bf16_t* vc; const float* rope;    // EPI_QKV
   int T, d, dh, S_cap, rope_pos;
   int row_owner;                                           // tile order of the direct-to-LDS kernel: 1 = an XCD owns row tiles
@@ -260,7 +281,7 @@ __device__ __forceinline__ void tile_epilogue(const float* red, const float* rs,
         *(float4*)xp = make_float4(v[0], v[1], v[2], v[3]);
         *(float4*)(xp + 4) = make_float4(v[4], v[5], v[6], v[7]);
         const float hv[8] = {v[0] * ga.x, v[1] * ga.y, v[2] * ga.z, v[3] * ga.w, v[4] * gb.x, v[5] * gb.y, v[6] * gb.z, v[7] * gb.w};
-        store8(ep.xb, m, n0 + c8, N, hv);
+        store8(ep.xb, ep.xb_T > 0 ? (m / ep.xb_T) * 32 + m % ep.xb_T : m, n0 + c8, N, hv);
 #pragma unroll
         for (int i = 0; i < 8; ++i) sq += v[i] * v[i];
       }
@@ -912,9 +933,9 @@ void mfma_gemm_scaled(Ctx* c, const bf16_t* A, const bf16_t* W, float* C, const 
 
 // x += A W; also leaves bf16(x * g_next) packed and the per-slab sums of squares of the new x
 void mfma_gemm_resid(Ctx* c, const bf16_t* A, const bf16_t* W, float* x, bf16_t* xb, float* ss_out, const float* g_next, int M, int K,
-                     hipStream_t s) {
+                     hipStream_t s, int xb_T) {
   GemmEpi ep{};
-  ep.x = x; ep.xb = xb; ep.ss_out = ss_out; ep.g_next = g_next; ep.NS = (c->d / 64 + 3) & ~3;
+  ep.x = x; ep.xb = xb; ep.ss_out = ss_out; ep.g_next = g_next; ep.NS = (c->d / 64 + 3) & ~3; ep.xb_T = xb_T;
   // many rows: 192 x 128 tiles with the operands shared through LDS (a quarter of the bytes per flop that 64 x 64 tiles pull
   // through a CU's L1), when they give most CUs a tile - at d = 1280 and 3904 rows: 210 tiles, one round
   if (c->d % 128 == 0 && K % 32 == 0 && ((M + 191) / 192) * (c->d / 128) >= 160) {
@@ -950,6 +971,76 @@ void mfma_gemm_qkv(Ctx* c, int layer, const bf16_t* A, const bf16_t* Wqkv, const
   ep.pos = pos; ep.tree = tree;
   p.splits = 1;
   gemm_dispatch<EPI_QKV>(A, Wqkv, nullptr, c->R * T, 3 * c->d, c->d, p, ep, s);
+}
+
+// One 32-key step of the attention kernels for NQB blocks of 16 queries: scores S^T = K Q^T (lane = query l % 16, key
+// group g = l / 16, 8 consecutive keys per lane), online softmax, O^T += V^T P^T.  The tree mask only touches a step that
+// reaches past the cached length S (tail).
+// The softmax weights are not rounded to bf16 (the definition keeps them exact): each un-normalised weight e goes into the
+// P V product as the sum of two bf16 values, hi = bf16(e) and lo = bf16(e - hi) (e to 2^-17), with two MFMAs per V block -
+// the matrix cores idle in these kernels anyway - and the normaliser sums the fp32 weights themselves.
+template <int NQB, int KD, int DT>
+__device__ __forceinline__ void attn_step(const bf16x8 (&kf)[2][KD], const bf16x8 (&vf)[DT], const bf16x8 (&qf)[NQB][KD],
+                                          const uint64_t (&mask)[NQB], float (&m_run)[NQB], float (&l_run)[NQB], floatx4 (&o)[NQB][DT],
+                                          int key0, int S, int n_keys, bool tail, int g, float c_exp) {
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    floatx4 s2[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      s2[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int kd = 0; kd < KD; ++kd) s2[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[t][kd], qf[qb][kd], s2[t], 0, 0, 0);
+    }
+    float sv[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sv[i] = s2[i >> 2][i & 3];
+    if (tail) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int key = key0 + 8 * g + i;
+        bool vis = key < S;
+        if (!vis && key < n_keys) vis = (mask[qb] >> (key - S)) & 1ull;
+        if (!vis) sv[i] = -INFINITY;
+      }
+    }
+    float mx = sv[0];
+#pragma unroll
+    for (int i = 1; i < 8; ++i) mx = fmaxf(mx, sv[i]);
+    mx = rows_max(mx);
+    const float m_new = fmaxf(m_run[qb], mx);
+    const float m_safe = m_new == -INFINITY ? 0.f : m_new;
+    const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_safe) * c_exp);
+    const float mc = m_safe * c_exp;
+    uint32_t pk[4], pl[4];
+    float rs = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; i += 2) {
+      // hardware exp2 (arguments <= 0 up to the rounding of the fused multiply-add)
+      const float e0 = __builtin_amdgcn_exp2f(fmaf(sv[i], c_exp, -mc)), e1 = __builtin_amdgcn_exp2f(fmaf(sv[i + 1], c_exp, -mc));
+      const uint32_t pp = pack2bf(e0, e1);
+      rs += e0 + e1;
+      pk[i >> 1] = pp;
+      pl[i >> 1] = pack2bf(e0 - __uint_as_float(pp << 16), e1 - __uint_as_float(pp & 0xFFFF0000u));
+    }
+    rs = rows_sum(rs);
+    l_run[qb] = l_run[qb] * alpha + rs;
+    m_run[qb] = m_new;
+    const bf16x8 pf = as_bf16x8(make_uint4(pk[0], pk[1], pk[2], pk[3]));
+    const bf16x8 pfl = as_bf16x8(make_uint4(pl[0], pl[1], pl[2], pl[3]));
+    // the running maximum rarely moves after the first steps: the accumulators are only rescaled when some query's did
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) o[qb][dt][rr] *= alpha;
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      o[qb][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf, o[qb][dt], 0, 0, 0);
+      o[qb][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pfl, o[qb][dt], 0, 0, 0);
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------------ attention
@@ -1035,65 +1126,7 @@ __global__ __launch_bounds__(NW * QG * 64, (DH * NQB >= 256 ? 1 : 2)) void k_att
       if (step < nsteps) {
         const int key0 = step << 5;
         const bool tail = key0 + 32 > S;
-#pragma unroll
-        for (int qb = 0; qb < NQB; ++qb) {
-          floatx4 s2[2];
-#pragma unroll
-          for (int t = 0; t < 2; ++t) {
-            s2[t] = floatx4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int kd = 0; kd < KD; ++kd)
-              s2[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[p][t][kd], qf[qb][kd], s2[t], 0, 0, 0);
-          }
-          float sv[8];
-#pragma unroll
-          for (int i = 0; i < 8; ++i) sv[i] = s2[i >> 2][i & 3];
-          if (tail) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-              const int key = key0 + 8 * g + i;
-              bool vis = key < S;
-              if (!vis && key < n_keys) vis = (mask[qb] >> (key - S)) & 1ull;
-              if (!vis) sv[i] = -INFINITY;
-            }
-          }
-          float mx = sv[0];
-#pragma unroll
-          for (int i = 1; i < 8; ++i) mx = fmaxf(mx, sv[i]);
-          mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-          mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-          const float m_new = fmaxf(m_run[qb], mx);
-          const float m_safe = m_new == -INFINITY ? 0.f : m_new;
-          const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_safe) * c_exp);
-          // The softmax weights are not rounded to bf16 (the definition keeps them exact): each un-normalised
-          // weight e goes into the P V product as the sum of two bf16 values, hi = bf16(e) and lo = bf16(e - hi)
-          // (e to 2^-17), with two MFMAs per V block - the matrix cores idle in this kernel anyway - and the
-          // normaliser sums the fp32 weights themselves.
-          uint32_t pk[4], pl[4];
-          float rs = 0.f;
-#pragma unroll
-          for (int i = 0; i < 8; i += 2) {
-            // hardware exp2 (arguments <= 0)
-            const float e0 = __builtin_amdgcn_exp2f((sv[i] - m_safe) * c_exp), e1 = __builtin_amdgcn_exp2f((sv[i + 1] - m_safe) * c_exp);
-            const uint32_t pp = pack2bf(e0, e1);
-            rs += e0 + e1;
-            pk[i >> 1] = pp;
-            pl[i >> 1] = pack2bf(e0 - __uint_as_float(pp << 16), e1 - __uint_as_float(pp & 0xFFFF0000u));
-          }
-          rs += __shfl_xor(rs, 16, 64);
-          rs += __shfl_xor(rs, 32, 64);
-          l_run[qb] = l_run[qb] * alpha + rs;
-          m_run[qb] = m_new;
-          const bf16x8 pf = as_bf16x8(make_uint4(pk[0], pk[1], pk[2], pk[3]));
-          const bf16x8 pfl = as_bf16x8(make_uint4(pl[0], pl[1], pl[2], pl[3]));
-#pragma unroll
-          for (int dt = 0; dt < DT; ++dt) {
-#pragma unroll
-            for (int rr = 0; rr < 4; ++rr) o[qb][dt][rr] *= alpha;
-            o[qb][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[p][dt], pf, o[qb][dt], 0, 0, 0);
-            o[qb][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[p][dt], pfl, o[qb][dt], 0, 0, 0);
-          }
-        }
+        attn_step<NQB, KD, DT>(kf[p], vf[p], qf, mask, m_run, l_run, o, key0, S, n_keys, tail, g, c_exp);
       }
       VVS_ATTN_LOAD(min(step + PD * NW, nsteps - 1), kf[p], vf[p]);
       __builtin_amdgcn_sched_barrier(0);
@@ -1154,6 +1187,370 @@ __global__ __launch_bounds__(NW * QG * 64, (DH * NQB >= 256 ? 1 : 2)) void k_att
   }
   VVS_PHASE_MARK(4);
 }
+
+// ------------------------------------------------------------------------------------------------ q/k/v projection + attention in one launch
+// Verify calls with at most 32 block tokens per row and head size 64: one workgroup per (head, prompt) computes the head's
+// q, k and v columns for the prompt's two rows (conditional, unconditional) and goes straight on to their attention, so that
+// the layer has one launch less and attention does not start from a cold ramp of its own: q never leaves the CU, and k / v
+// are read back from the cache lines the same workgroup has just written.
+//   Projection: a 64 x 192 tile on the direct-to-LDS pipeline of k_gemm_shared_dma (2 x 2 waves of 32 x 96; a stage = 32
+//     contraction values = 16 KiB).  The activation operand comes in the ROW-PADDED packed layout - row-block r holds
+//     the T tokens of row r, so the tile's two row-blocks are 2b and 2b + 1 - and the weight blocks are the head's two
+//     32-row blocks inside each of the q, k and v thirds.  Tile rows t >= T are padding: every output row depends on its
+//     own operand row only, and those rows are never used.
+//   Epilogue: RMSNorm row factor, 2D rotary embedding of q and k; q goes to LDS (bf16), k and v into their cache slots.
+//   Attention: as k_attn_mfma with four waves per (head, row) - the workgroup has 8 waves: waves 0-3 run the projection,
+//     then even waves take the conditional row and odd waves the unconditional one - reading q fragments from LDS.  Waves
+//     4-7 have nothing to do during the projection but to meet its barriers, so they request the K / V operands of their
+//     first steps up front, where those steps lie wholly below the cache length (old keys).  Every other cache load stands
+//     behind the workgroup-scope fence and the barrier that follow the cache writes, and no line holding a slot of the
+//     block itself is read before them, so the L1 of the CU cannot hold a stale copy of the slots just written.
+template <int NSL, int NQB>
+__global__ __launch_bounds__(512) void k_qkv_attn(const uint4* __restrict__ Ap, const uint4* __restrict__ Wp, bf16_t* __restrict__ out,
+                                                  int K, const GemmEpi ep, float c_exp) {
+  constexpr int WM = 1, WN = 3, BM = 64, BN = 192, LDC = BN + 4, NA = 4, NBLK = 16, PER = 4;
+  constexpr int DH = 64, KD = DH / 32, DT = DH / 16, NQ = NQB * 16, PD = 2, NW = 4;
+  constexpr int QLD = DH + 8;              // bf16 per q row in LDS: 144 bytes, 16-byte aligned, rows spread over the banks
+  constexpr size_t kRing = (size_t)NSL * NBLK * 1024, kTile = (size_t)BM * LDC * sizeof(float);
+  constexpr size_t kFirst = kRing > kTile ? kRing : kTile;
+  static_assert(NSL >= 4 && PER * (NSL - 1) <= 60, "stages in flight / 6-bit load counter");
+  static_assert(kFirst >= (size_t)2 * (NW - 1) * NQ * (DH + 3) * sizeof(float), "the merge buffers reuse the tile");
+  extern __shared__ float red[];           // stage ring, then the 64 x 192 output tile, then the attention merge buffers; behind it q
+  u32x4* stage = (u32x4*)red;
+  bf16_t* q_s = (bf16_t*)((char*)red + kFirst);                // [2 rows][32 tokens][QLD]
+  float* s_o = red;                                            // [2 rows][NW - 1][NQ][DH + 1]
+  float* s_m = s_o + 2 * (NW - 1) * NQ * (DH + 1);             // [2 rows][NW - 1][NQ]
+  float* s_l = s_m + 2 * (NW - 1) * NQ;
+  __shared__ float rs[BM];
+  const uint32_t lds_base = (uint32_t)(uintptr_t)stage;
+  const int hd = blockIdx.x, b = blockIdx.y, T = ep.T, d = ep.d;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const bool gemm_wave = wave < 4;         // waves 0-3: 2 x 2 over the 64 x 192 tile
+  const int wr = (wave >> 1) & 1, wc = wave & 1;
+  const int ar = wave & 1, aw = wave >> 1; // attention: row of the pair, wave within the row (each row: two projection waves, two others)
+  const int KB = K >> 4, nst = KB >> 1;
+  // the prompt's cache length and emitted count: the oldest loads, back long before the epilogue
+  const int kv = ep.pos.kv_len[b], ne = ep.pos.n_emitted[b];
+  // row factor inputs: 4 lanes per tile row, each every 4th group of 4 slabs (as RowScale)
+  float4 rv[4];
+  if (gemm_wave) {
+    const int row = threadIdx.x >> 2, part = threadIdx.x & 3, nq = ep.NS >> 2;
+    const int m = (2 * b + (row >> 5)) * T + min(row & 31, T - 1);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      rv[i] = part + 4 * i < nq ? ((const float4*)(ep.ss + (size_t)m * ep.NS))[part + 4 * i] : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  // attention operands (see k_attn_mfma): K and V of a 32-key step straight into MFMA operand registers
+  const int r = 2 * b + ar;
+  const int g = lane >> 4, ql = lane & 15;
+  const int S = kv, n_keys = S + T, nsteps = (n_keys + 31) >> 5, cap_steps = ep.S_cap >> 5;
+  const bf16_t* kb = ep.kc + (size_t)r * ep.row_stride + (size_t)hd * ep.head_stride;
+  const bf16_t* vb = ep.vc + (size_t)r * ep.row_stride + (size_t)hd * ep.head_stride;
+#define VVS_ATTN_LOAD(STEP, KF, VF)                                                                                   \
+  {                                                                                                                   \
+    _Pragma("unroll") for (int t = 0; t < 2; ++t)                                                                     \
+        _Pragma("unroll") for (int kd = 0; kd < KD; ++kd)                                                             \
+            KF[t][kd] = as_bf16x8(*(const uint4*)(kb + ((((size_t)(STEP) * 2 + t) * KD + kd) * 64 + lane) * 8));      \
+    _Pragma("unroll") for (int dt = 0; dt < DT; ++dt)                                                                 \
+        VF[dt] = as_bf16x8(*(const uint4*)(vb + (((size_t)(STEP) * DT + dt) * 64 + lane) * 8));                       \
+  }
+  bf16x8 kf[PD][2][KD], vf[PD][DT];
+  bool early[PD];
+#pragma unroll
+  for (int p = 0; p < PD; ++p) {
+    early[p] = !gemm_wave && aw + p * NW < (S >> 5);     // wave-uniform; a step wholly below the cache length holds old keys only
+    if (early[p]) VVS_ATTN_LOAD(aw + p * NW, kf[p], vf[p]);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  floatx16 acc[WN];
+  if (gemm_wave) {
+  __builtin_amdgcn_sched_barrier(0);
+  const u32x4* src[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int j = wave + 4 * i;            // block of the stage: 0..3 activations (row-block, contraction half), 4..15 weights
+    const int wi = (j - NA) >> 1;          // weight block: third (q, k, v) = wi / 2, half of the head = wi % 2
+    const int rb = j < NA ? 2 * b + (j >> 1) : (wi >> 1) * (d >> 5) + 2 * hd + (wi & 1);
+    src[i] = (const u32x4*)(j < NA ? Ap : Wp) + ((size_t)rb * KB + (j & 1)) * 64 + lane;
+  }
+  auto request = [&](int t) {
+    const size_t kk = (size_t)min(t, nst - 1) * 128;
+    const uint32_t slot = lds_base + (uint32_t)((t % NSL) * NBLK) * 1024u;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) lds_dma16(src[i] + kk, slot + (uint32_t)(wave + 4 * i) * 1024u);
+  };
+#pragma unroll
+  for (int j = 0; j < WN; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+#pragma unroll
+  for (int t = 0; t < NSL - 1; ++t) request(t);
+  __builtin_amdgcn_sched_barrier(0);
+#define VVS_WAIT_STAGES asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PER * (NSL - 3)) : "memory")
+  VVS_WAIT_STAGES;                         // stages 0 and 1 of this wave have landed
+  __syncthreads();                         // ... and everybody else's
+  constexpr int NM = WM * WN, NR = WM + WN;
+  constexpr int IA = (NR + PER + NM - 1) / NM, IB = (NR + NM - 1) / NM;
+  auto lds_frag = [&](int t, int kbo, int i) {           // i-th fragment of a stage's block kbo: the A row-block first, then the B blocks
+    const int sl = (t % NSL) * NBLK;
+    return __builtin_bit_cast(bf16x8, stage[(sl + (i < WM ? wr * 2 : NA + (wc * WN + (i - WM)) * 2) + kbo) * 64 + lane]);
+  };
+  bf16x8 fa0, fb0[WN], fa1, fb1[WN];
+  fa0 = lds_frag(0, 0, 0);
+#pragma unroll
+  for (int j = 0; j < WN; ++j) fb0[j] = lds_frag(0, 0, WM + j);
+  // the main loop of k_gemm_shared_dma: everything but the MFMAs is dealt into the gaps between them
+  for (int s = 0; s < nst; ++s) {
+    const size_t kk = (size_t)min(s + NSL - 1, nst - 1) * 128;
+    const uint32_t slot = lds_base + (uint32_t)(((s + NSL - 1) % NSL) * NBLK) * 1024u;
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+      acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0, fb0[m], acc[m], 0, 0, 0);
+#pragma unroll
+      for (int it = m * IA; it < (m + 1) * IA; ++it) {
+        if (it < NR) {
+          if (it < WM) fa1 = lds_frag(s, 1, it); else fb1[it - WM] = lds_frag(s, 1, it);
+        } else if (it - NR < PER) {
+          const int i = it - NR;
+          lds_dma16(src[i] + kk, slot + (uint32_t)(wave + 4 * i) * 1024u);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int m = 0; m < NM; ++m) {
+      acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1, fb1[m], acc[m], 0, 0, 0);
+#pragma unroll
+      for (int it = m * IB; it < (m + 1) * IB; ++it) {
+        if (it < NR) {
+          if (it < WM) fa0 = lds_frag(s + 1, 0, it); else fb0[it - WM] = lds_frag(s + 1, 0, it);
+        }
+      }
+      if (m == NM / 2) {
+        VVS_WAIT_STAGES;                   // this wave's part of stage s + 2
+        __builtin_amdgcn_s_barrier();      // ... and everybody else's; and everybody is done reading stage s
+        asm volatile("" ::: "memory");
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the repeated last stages still in flight must land before the tile reuses their LDS
+  } else {                                 // waves 4-7 meet the barriers of the main loop
+    __syncthreads();
+    for (int s = 0; s < nst; ++s) __builtin_amdgcn_s_barrier();
+  }
+  if (gemm_wave) {                         // row factors
+    const int row = threadIdx.x >> 2, part = threadIdx.x & 3;
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) t += (rv[i].x + rv[i].y) + (rv[i].z + rv[i].w);
+    t += __shfl_xor(t, 1, 64);
+    t += __shfl_xor(t, 2, 64);
+    if (part == 0) rs[row] = 1.0f / sqrtf(t / (float)ep.dnorm + ep.eps);
+  }
+#undef VVS_WAIT_STAGES
+  __syncthreads();                         // the stage buffers become the output tile
+  if (gemm_wave) {
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int rr = 0; rr < 16; ++rr)
+        red[(wr * 32 + (rr >> 2) * 8 + (lane >> 5) * 4 + (rr & 3)) * LDC + (wc * WN + j) * 32 + (lane & 31)] = acc[j][rr];
+  }
+  __syncthreads();
+
+  // ---- epilogue: tile columns 0..63 q, 64..127 k, 128..191 v of head hd; tile row = 32 * (row of the pair) + token
+  constexpr int np = DH >> 2, half = DH >> 1;   // rotary pairs per grid axis; dims of the grid-row half
+  {                                        // q: one unit = (tile row, 16 consecutive dims) per thread of waves 0-3
+    const int row = (threadIdx.x >> 2) & 63, c0 = (threadIdx.x & 3) * 16, t = row & 31;
+    if (gemm_wave && t < T) {
+      const float4* p4 = (const float4*)(red + row * LDC + c0);
+      const float4 s0 = p4[0], s1 = p4[1], s2 = p4[2], s3 = p4[3];
+      float v[16] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w, s2.x, s2.y, s2.z, s2.w, s3.x, s3.y, s3.z, s3.w};
+#pragma unroll
+      for (int i = 0; i < 16; ++i) v[i] *= rs[row];
+      const int img = ne - 1 + ep.tree.depth[t];
+      if (img >= 0) {
+        const int gr = min(img / ep.pos.grid_w, ep.rope_pos - 1), gc = img % ep.pos.grid_w;
+        // 16 dims = 8 pairs inside one half of the head: 8 consecutive pairs of one table row
+        const float4* t4 = (const float4*)(ep.rope + ((size_t)(c0 >= half ? gc : gr) * np + ((c0 & (half - 1)) >> 1)) * 2);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float4 c4 = t4[i];
+          const float a0 = v[4 * i], b0 = v[4 * i + 1], a1 = v[4 * i + 2], b1 = v[4 * i + 3];
+          v[4 * i] = a0 * c4.x - b0 * c4.y;
+          v[4 * i + 1] = a0 * c4.y + b0 * c4.x;
+          v[4 * i + 2] = a1 * c4.z - b1 * c4.w;
+          v[4 * i + 3] = a1 * c4.w + b1 * c4.z;
+        }
+      }
+      uint4* dst = (uint4*)(q_s + ((row >> 5) * 32 + t) * QLD + c0);
+      dst[0] = make_uint4(pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]), pack2bf(v[6], v[7]));
+      dst[1] = make_uint4(pack2bf(v[8], v[9]), pack2bf(v[10], v[11]), pack2bf(v[12], v[13]), pack2bf(v[14], v[15]));
+    }
+  }
+  {                                        // k and v: a lane takes one tile row (token), the lanes of a wave consecutive tokens
+    const int row = threadIdx.x & 63, g4 = threadIdx.x >> 6, t = row & 31;
+    const int slot = kv + t;
+    if (t < T && slot >= 0 && slot < ep.S_cap) {
+      const float sc = rs[row];
+      const size_t region = (size_t)(2 * b + (row >> 5)) * ep.row_stride + (size_t)hd * ep.head_stride;
+      bf16_t* kh = ep.kc + region;
+      bf16_t* vh = ep.vc + region;
+      const int img = ne - 1 + ep.tree.depth[t];
+      const int gr = min(max(img, 0) / ep.pos.grid_w, ep.rope_pos - 1), gc = max(img, 0) % ep.pos.grid_w;
+#pragma unroll
+      for (int c8 = g4 * 8; c8 < DH; c8 += 64) {         // k: 8-dim pieces, one 16-byte store each
+        const float4 a = *(const float4*)(red + row * LDC + DH + c8), bq = *(const float4*)(red + row * LDC + DH + c8 + 4);
+        float v[8] = {a.x * sc, a.y * sc, a.z * sc, a.w * sc, bq.x * sc, bq.y * sc, bq.z * sc, bq.w * sc};
+        if (img >= 0) {
+          const float4* t4 = (const float4*)(ep.rope + ((size_t)(c8 >= half ? gc : gr) * np + ((c8 & (half - 1)) >> 1)) * 2);
+          const float4 c0 = t4[0], c1 = t4[1];
+          const float x0 = v[0], x1 = v[1], x2 = v[2], x3 = v[3], x4 = v[4], x5 = v[5], x6 = v[6], x7 = v[7];
+          v[0] = x0 * c0.x - x1 * c0.y; v[1] = x0 * c0.y + x1 * c0.x;
+          v[2] = x2 * c0.z - x3 * c0.w; v[3] = x2 * c0.w + x3 * c0.z;
+          v[4] = x4 * c1.x - x5 * c1.y; v[5] = x4 * c1.y + x5 * c1.x;
+          v[6] = x6 * c1.z - x7 * c1.w; v[7] = x6 * c1.w + x7 * c1.z;
+        }
+        *(uint4*)(kh + k_index(slot, c8, DH)) = make_uint4(pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]), pack2bf(v[6], v[7]));
+      }
+#pragma unroll
+      for (int c4 = g4 * 4; c4 < DH; c4 += 32) {         // v: 4 dims per step; a store instruction covers runs of consecutive slots
+        const float4 v = *(const float4*)(red + row * LDC + 2 * DH + c4);
+        vh[v_index(slot, c4, DH)] = f2bf(v.x * sc);
+        vh[v_index(slot, c4 + 1, DH)] = f2bf(v.y * sc);
+        vh[v_index(slot, c4 + 2, DH)] = f2bf(v.z * sc);
+        vh[v_index(slot, c4 + 3, DH)] = f2bf(v.w * sc);
+      }
+    }
+  }
+  // the cache writes have reached L2 (the L1 is write-through) and q is in LDS before anybody goes on
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+  __syncthreads();
+
+  // ---- attention of (head hd, row 2b + ar) by its four waves (see k_attn_mfma)
+  bf16x8 qf[NQB][KD];
+  uint64_t mask[NQB];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int tq = min(qb * 16 + ql, T - 1);           // query rows past T repeat row T - 1 and are not stored
+    mask[qb] = ep.tree.anc[tq];
+#pragma unroll
+    for (int kd = 0; kd < KD; ++kd) qf[qb][kd] = as_bf16x8(*(const uint4*)(q_s + (ar * 32 + tq) * QLD + kd * 32 + g * 8));
+  }
+  float m_run[NQB], l_run[NQB];
+  floatx4 o[NQB][DT];
+#pragma unroll
+  for (int qb = 0; qb < NQB; ++qb) {
+    m_run[qb] = -INFINITY;
+    l_run[qb] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) o[qb][dt] = floatx4{0.f, 0.f, 0.f, 0.f};
+  }
+#pragma unroll
+  for (int p = 0; p < PD; ++p) {
+    if (!early[p]) VVS_ATTN_LOAD(min(aw + p * NW, cap_steps - 1), kf[p], vf[p]);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  for (int base = aw; base < nsteps; base += NW * PD) {
+#pragma unroll
+    for (int p = 0; p < PD; ++p) {
+      const int step = base + p * NW;
+      if (step < nsteps) {
+        const int key0 = step << 5;
+        const bool tail = key0 + 32 > S;
+        attn_step<NQB, KD, DT>(kf[p], vf[p], qf, mask, m_run, l_run, o, key0, S, n_keys, tail, g, c_exp);
+      }
+      VVS_ATTN_LOAD(min(step + PD * NW, nsteps - 1), kf[p], vf[p]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+#undef VVS_ATTN_LOAD
+  // merge the waves' partial results (waves 1.. of a row publish, wave 0 combines and writes); the buffers lie where
+  // the output tile was: everybody is past the epilogue's reads of it (the barrier in front of the attention)
+  if (aw > 0) {
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      const int qi = qb * 16 + ql, ui = (ar * (NW - 1) + aw - 1) * NQ + qi;
+      if (g == 0) { s_m[ui] = m_run[qb]; s_l[ui] = l_run[qb]; }
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) s_o[ui * (DH + 1) + dt * 16 + 4 * g + rr] = o[qb][dt][rr];
+    }
+  }
+  __syncthreads();
+  if (aw == 0) {
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+      const int qi = qb * 16 + ql;
+      float m = m_run[qb];
+#pragma unroll
+      for (int w = 0; w < NW - 1; ++w) m = fmaxf(m, s_m[(ar * (NW - 1) + w) * NQ + qi]);
+      const float m_safe = m == -INFINITY ? 0.f : m;
+      const float a0 = exp2f((m_run[qb] - m_safe) * c_exp);
+      float l = l_run[qb] * a0;
+      float awt[NW - 1];
+#pragma unroll
+      for (int w = 0; w < NW - 1; ++w) {
+        awt[w] = exp2f((s_m[(ar * (NW - 1) + w) * NQ + qi] - m_safe) * c_exp);
+        l += s_l[(ar * (NW - 1) + w) * NQ + qi] * awt[w];
+      }
+      const float inv = 1.0f / l;
+      if (qi < T) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          uint32_t pk[2];
+#pragma unroll
+          for (int rr = 0; rr < 4; rr += 2) {
+            float v0 = o[qb][dt][rr] * a0, v1 = o[qb][dt][rr + 1] * a0;
+#pragma unroll
+            for (int w = 0; w < NW - 1; ++w) {
+              const float* so = s_o + ((ar * (NW - 1) + w) * NQ + qi) * (DH + 1) + dt * 16 + 4 * g + rr;
+              v0 += so[0] * awt[w];
+              v1 += so[1] * awt[w];
+            }
+            pk[rr >> 1] = pack2bf(v0 * inv, v1 * inv);
+          }
+          *(uint2*)(out + pack_index(r * T + qi, hd * DH + dt * 16 + 4 * g, d)) = make_uint2(pk[0], pk[1]);   // O-projection operand layout
+        }
+      }
+    }
+  }
+}
+
+// True when a verify call of T block tokens per row takes the fused projection + attention kernel.
+bool mfma_qkv_attention_ok(const Ctx* c, const PosDesc& pos, int T) {
+  return c->cfg.dtype == VVS_BF16 && c->dh == 64 && T <= 32 && pos.kv_len && pos.n_emitted && c->d % 64 == 0 && c->d / 64 <= 64;
+}
+
+// q/k/v projection of the row-padded operand A, rotary embedding, cache write and attention in one launch; the result is the
+// packed operand of the O projection.
+void mfma_qkv_attention(Ctx* c, int layer, const bf16_t* A, const bf16_t* Wqkv, const float* ss, const TreeDesc& tree, const PosDesc& pos,
+                        int T, hipStream_t s) {
+  GemmEpi ep{};
+  set_scale(ep, c, ss);
+  ep.kc = (bf16_t*)c->kv + c->kv_layer_stride * layer;
+  ep.vc = (bf16_t*)c->kv + c->kv_v_off + c->kv_layer_stride * layer;
+  ep.rope = (const float*)(c->ws + c->w.rope_tab);
+  ep.T = T; ep.d = c->d; ep.dh = c->dh; ep.S_cap = c->S_cap; ep.rope_pos = c->rope_pos;
+  ep.row_stride = c->kv_row_stride; ep.head_stride = c->kv_head_stride;
+  ep.pos = pos; ep.tree = tree;
+  bf16_t* out = (bf16_t*)(c->ws + c->w.attn);
+  const float c_exp = 1.4426950408889634f / sqrtf((float)c->dh);
+  constexpr int NSL = 6;                   // 5 stages of 16 KiB in flight (8 slots measured the same, 4 slots 5 % slower)
+  constexpr size_t ring = (size_t)NSL * 16 * 1024, tile = (size_t)64 * 196 * sizeof(float), first = ring > tile ? ring : tile;
+  dim3 grid(c->H, c->B);
+  constexpr size_t lds = first + 2 * 32 * 72 * sizeof(bf16_t);   // ring / tile / merge buffers, then q
+  if (T <= 16) {
+    allow_dynamic_lds(reinterpret_cast<const void*>(&k_qkv_attn<NSL, 1>), lds);
+    hipLaunchKernelGGL((k_qkv_attn<NSL, 1>), grid, dim3(512), lds, s, (const uint4*)A, (const uint4*)Wqkv, out, c->d, ep, c_exp);
+  } else {
+    allow_dynamic_lds(reinterpret_cast<const void*>(&k_qkv_attn<NSL, 2>), lds);
+    hipLaunchKernelGGL((k_qkv_attn<NSL, 2>), grid, dim3(512), lds, s, (const uint4*)A, (const uint4*)Wqkv, out, c->d, ep, c_exp);
+  }
+}
+
 
 void mfma_attention(Ctx* c, int layer, const TreeDesc& tree, const PosDesc& pos, int T, hipStream_t s) {
   const bf16_t* q = (const bf16_t*)(c->ws + c->w.q);
