@@ -1201,49 +1201,51 @@ __global__ __launch_bounds__(NW * QG * 64, (DH * NQB >= 256 ? 1 : 2)) void k_att
 //   Epilogue: RMSNorm row factor, 2D rotary embedding of q and k; q goes to LDS (bf16), k and v into their cache slots.
 //   Attention: as k_attn_mfma with four waves per (head, row) - the workgroup has 8 waves: waves 0-3 run the projection,
 //     then even waves take the conditional row and odd waves the unconditional one - reading q fragments from LDS.  Waves
-//     4-7 have nothing to do during the projection but to meet its barriers, so they request the K / V operands of their
-//     first steps up front, where those steps lie wholly below the cache length (old keys).  Every other cache load stands
+//     4-7 have no MFMAs during the projection: they take half of the stage requests and meet the barriers, and when the
+//     last stage has landed they request the K / V operands of their first steps, where those steps lie wholly below the
+//     cache length (old keys), so that these arrive while the tile goes through the epilogue.  Every other cache load stands
 //     behind the workgroup-scope fence and the barrier that follow the cache writes, and no line holding a slot of the
 //     block itself is read before them, so the L1 of the CU cannot hold a stale copy of the slots just written.
+//   Measured with time stamps at the end of the image (55 k cycles): start-up 3 k, projection main loop 24 k (16 KiB per
+//     600 cycles: the L1 fill rate of a CU), tile to LDS 2.5 k, epilogue + fence 5 k, attention steps 17 k (VALU-bound: 8
+//     waves share 4 SIMDs), merge + store 3 k.
 template <int NSL, int NQB>
 __global__ __launch_bounds__(512) void k_qkv_attn(const uint4* __restrict__ Ap, const uint4* __restrict__ Wp, bf16_t* __restrict__ out,
                                                   int K, const GemmEpi ep, float c_exp) {
-  constexpr int WM = 1, WN = 3, BM = 64, BN = 192, LDC = BN + 4, NA = 4, NBLK = 16, PER = 4;
+  constexpr int GW = 4;                    // projection waves: 4 = 2 x 2 of 32 x 96 (2 = 1 x 2 of 64 x 96 measured 3 % slower per step)
+  constexpr int DW = 8;                    // waves that request stage blocks (the projection waves among them)
+  static_assert(DW >= GW && 16 % DW == 0, "stage blocks are dealt to the requesting waves");
+  constexpr int WM = 4 / GW, WN = 3, BM = 64, BN = 192, LDC = BN + 4, NA = 4, NBLK = 16, PER = NBLK / DW;
   constexpr int DH = 64, KD = DH / 32, DT = DH / 16, NQ = NQB * 16, PD = 2, NW = 4;
   constexpr int QLD = DH + 8;              // bf16 per q row in LDS: 144 bytes, 16-byte aligned, rows spread over the banks
   constexpr size_t kRing = (size_t)NSL * NBLK * 1024, kTile = (size_t)BM * LDC * sizeof(float);
   constexpr size_t kFirst = kRing > kTile ? kRing : kTile;
   static_assert(NSL >= 4 && PER * (NSL - 1) <= 60, "stages in flight / 6-bit load counter");
-  static_assert(kFirst >= (size_t)2 * (NW - 1) * NQ * (DH + 3) * sizeof(float), "the merge buffers reuse the tile");
+  static_assert(kFirst >= (size_t)2 * NW * NQ * (DH + 3) * sizeof(float), "the merge buffers reuse the tile");
   extern __shared__ float red[];           // stage ring, then the 64 x 192 output tile, then the attention merge buffers; behind it q
   u32x4* stage = (u32x4*)red;
   bf16_t* q_s = (bf16_t*)((char*)red + kFirst);                // [2 rows][32 tokens][QLD]
-  float* s_o = red;                                            // [2 rows][NW - 1][NQ][DH + 1]
-  float* s_m = s_o + 2 * (NW - 1) * NQ * (DH + 1);             // [2 rows][NW - 1][NQ]
-  float* s_l = s_m + 2 * (NW - 1) * NQ;
+  float* s_o = red;                                            // [2 rows][NW][NQ][DH + 1]
+  float* s_m = s_o + 2 * NW * NQ * (DH + 1);                   // [2 rows][NW][NQ]
+  float* s_l = s_m + 2 * NW * NQ;
   __shared__ float rs[BM];
   const uint32_t lds_base = (uint32_t)(uintptr_t)stage;
+  VVS_PHASE_MARK(0);
   const int hd = blockIdx.x, b = blockIdx.y, T = ep.T, d = ep.d;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const bool gemm_wave = wave < 4;         // waves 0-3: 2 x 2 over the 64 x 192 tile
-  const int wr = (wave >> 1) & 1, wc = wave & 1;
+  const bool gemm_wave = wave < GW, dma_wave = wave < DW, lo4 = wave < 4;   // lo4: the 256 threads that own the row factors and the q epilogue
+  const int wr = GW == 4 ? (wave >> 1) & 1 : 0, wc = wave & 1;
   const int ar = wave & 1, aw = wave >> 1; // attention: row of the pair, wave within the row (each row: two projection waves, two others)
   const int KB = K >> 4, nst = KB >> 1;
-  // the prompt's cache length and emitted count: the oldest loads, back long before the epilogue
-  const int kv = ep.pos.kv_len[b], ne = ep.pos.n_emitted[b];
-  // row factor inputs: 4 lanes per tile row, each every 4th group of 4 slabs (as RowScale)
-  float4 rv[4];
-  if (gemm_wave) {
-    const int row = threadIdx.x >> 2, part = threadIdx.x & 3, nq = ep.NS >> 2;
-    const int m = (2 * b + (row >> 5)) * T + min(row & 31, T - 1);
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      rv[i] = part + 4 * i < nq ? ((const float4*)(ep.ss + (size_t)m * ep.NS))[part + 4 * i] : make_float4(0.f, 0.f, 0.f, 0.f);
-  }
+  // The prompt's cache length and emitted count come from memory (a scalar load that shares its counter with the
+  // kernel-argument loads): the projection waves ask for them only behind their first stage requests, so that nothing
+  // on the way to those requests waits for memory.
+  int kv, ne;
+  float4 rv[4];                            // row factor inputs
   // attention operands (see k_attn_mfma): K and V of a 32-key step straight into MFMA operand registers
   const int r = 2 * b + ar;
   const int g = lane >> 4, ql = lane & 15;
-  const int S = kv, n_keys = S + T, nsteps = (n_keys + 31) >> 5, cap_steps = ep.S_cap >> 5;
+  const int cap_steps = ep.S_cap >> 5;
   const bf16_t* kb = ep.kc + (size_t)r * ep.row_stride + (size_t)hd * ep.head_stride;
   const bf16_t* vb = ep.vc + (size_t)r * ep.row_stride + (size_t)hd * ep.head_stride;
 #define VVS_ATTN_LOAD(STEP, KF, VF)                                                                                   \
@@ -1256,19 +1258,18 @@ __global__ __launch_bounds__(512) void k_qkv_attn(const uint4* __restrict__ Ap, 
   }
   bf16x8 kf[PD][2][KD], vf[PD][DT];
   bool early[PD];
+  floatx16 acc[WM][WN];
+  auto load_rv = [&]() {                   // row factor inputs: 4 lanes per tile row, each every 4th group of 4 slabs (as RowScale)
+    const int row = threadIdx.x >> 2, part = threadIdx.x & 3, nq = ep.NS >> 2;
+    const int m = (2 * b + (row >> 5)) * T + min(row & 31, T - 1);
 #pragma unroll
-  for (int p = 0; p < PD; ++p) {
-    early[p] = !gemm_wave && aw + p * NW < (S >> 5);     // wave-uniform; a step wholly below the cache length holds old keys only
-    if (early[p]) VVS_ATTN_LOAD(aw + p * NW, kf[p], vf[p]);
-    __builtin_amdgcn_sched_barrier(0);
-  }
-  floatx16 acc[WN];
-  if (gemm_wave) {
-  __builtin_amdgcn_sched_barrier(0);
+    for (int i = 0; i < 4; ++i)
+      rv[i] = part + 4 * i < nq ? ((const float4*)(ep.ss + (size_t)m * ep.NS))[part + 4 * i] : make_float4(0.f, 0.f, 0.f, 0.f);
+  };
   const u32x4* src[PER];
 #pragma unroll
   for (int i = 0; i < PER; ++i) {
-    const int j = wave + 4 * i;            // block of the stage: 0..3 activations (row-block, contraction half), 4..15 weights
+    const int j = min(wave + DW * i, NBLK - 1);   // block of the stage: 0..3 activations (row-block, contraction half), 4..15 weights
     const int wi = (j - NA) >> 1;          // weight block: third (q, k, v) = wi / 2, half of the head = wi % 2
     const int rb = j < NA ? 2 * b + (j >> 1) : (wi >> 1) * (d >> 5) + 2 * hd + (wi & 1);
     src[i] = (const u32x4*)(j < NA ? Ap : Wp) + ((size_t)rb * KB + (j & 1)) * 64 + lane;
@@ -1277,26 +1278,40 @@ __global__ __launch_bounds__(512) void k_qkv_attn(const uint4* __restrict__ Ap, 
     const size_t kk = (size_t)min(t, nst - 1) * 128;
     const uint32_t slot = lds_base + (uint32_t)((t % NSL) * NBLK) * 1024u;
 #pragma unroll
-    for (int i = 0; i < PER; ++i) lds_dma16(src[i] + kk, slot + (uint32_t)(wave + 4 * i) * 1024u);
+    for (int i = 0; i < PER; ++i) lds_dma16(src[i] + kk, slot + (uint32_t)(wave + DW * i) * 1024u);
   };
+  if (lo4) load_rv();                      // addresses from kernel arguments only; older than the stage requests, so never waited for
+  __builtin_amdgcn_sched_barrier(0);
+  if (dma_wave) {
 #pragma unroll
-  for (int j = 0; j < WN; ++j)
+    for (int t = 0; t < NSL - 1; ++t) request(t);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  VVS_PHASE_MARK(1);
+  kv = ep.pos.kv_len[b];
+  ne = ep.pos.n_emitted[b];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
-#pragma unroll
-  for (int t = 0; t < NSL - 1; ++t) request(t);
+  for (int p = 0; p < PD; ++p) early[p] = false;
   __builtin_amdgcn_sched_barrier(0);
 #define VVS_WAIT_STAGES asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PER * (NSL - 3)) : "memory")
+  if (gemm_wave) {
+#pragma unroll
+  for (int i = 0; i < WM; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
   VVS_WAIT_STAGES;                         // stages 0 and 1 of this wave have landed
   __syncthreads();                         // ... and everybody else's
   constexpr int NM = WM * WN, NR = WM + WN;
   constexpr int IA = (NR + PER + NM - 1) / NM, IB = (NR + NM - 1) / NM;
   auto lds_frag = [&](int t, int kbo, int i) {           // i-th fragment of a stage's block kbo: the A row-block first, then the B blocks
     const int sl = (t % NSL) * NBLK;
-    return __builtin_bit_cast(bf16x8, stage[(sl + (i < WM ? wr * 2 : NA + (wc * WN + (i - WM)) * 2) + kbo) * 64 + lane]);
+    return __builtin_bit_cast(bf16x8, stage[(sl + (i < WM ? (wr * WM + i) * 2 : NA + (wc * WN + (i - WM)) * 2) + kbo) * 64 + lane]);
   };
-  bf16x8 fa0, fb0[WN], fa1, fb1[WN];
-  fa0 = lds_frag(0, 0, 0);
+  bf16x8 fa0[WM], fb0[WN], fa1[WM], fb1[WN];
+#pragma unroll
+  for (int i = 0; i < WM; ++i) fa0[i] = lds_frag(0, 0, i);
 #pragma unroll
   for (int j = 0; j < WN; ++j) fb0[j] = lds_frag(0, 0, WM + j);
   // the main loop of k_gemm_shared_dma: everything but the MFMAs is dealt into the gaps between them
@@ -1305,25 +1320,25 @@ __global__ __launch_bounds__(512) void k_qkv_attn(const uint4* __restrict__ Ap, 
     const uint32_t slot = lds_base + (uint32_t)(((s + NSL - 1) % NSL) * NBLK) * 1024u;
 #pragma unroll
     for (int m = 0; m < NM; ++m) {
-      acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0, fb0[m], acc[m], 0, 0, 0);
+      acc[m / WN][m % WN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[m / WN], fb0[m % WN], acc[m / WN][m % WN], 0, 0, 0);
 #pragma unroll
       for (int it = m * IA; it < (m + 1) * IA; ++it) {
         if (it < NR) {
-          if (it < WM) fa1 = lds_frag(s, 1, it); else fb1[it - WM] = lds_frag(s, 1, it);
+          if (it < WM) fa1[it] = lds_frag(s, 1, it); else fb1[it - WM] = lds_frag(s, 1, it);
         } else if (it - NR < PER) {
           const int i = it - NR;
-          lds_dma16(src[i] + kk, slot + (uint32_t)(wave + 4 * i) * 1024u);
+          lds_dma16(src[i] + kk, slot + (uint32_t)(wave + DW * i) * 1024u);
         }
       }
       __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
     for (int m = 0; m < NM; ++m) {
-      acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1, fb1[m], acc[m], 0, 0, 0);
+      acc[m / WN][m % WN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[m / WN], fb1[m % WN], acc[m / WN][m % WN], 0, 0, 0);
 #pragma unroll
       for (int it = m * IB; it < (m + 1) * IB; ++it) {
         if (it < NR) {
-          if (it < WM) fa0 = lds_frag(s + 1, 0, it); else fb0[it - WM] = lds_frag(s + 1, 0, it);
+          if (it < WM) fa0[it] = lds_frag(s + 1, 0, it); else fb0[it - WM] = lds_frag(s + 1, 0, it);
         }
       }
       if (m == NM / 2) {
@@ -1335,11 +1350,29 @@ __global__ __launch_bounds__(512) void k_qkv_attn(const uint4* __restrict__ Ap, 
     }
   }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the repeated last stages still in flight must land before the tile reuses their LDS
-  } else {                                 // waves 4-7 meet the barriers of the main loop
+  } else {                                 // the other waves: their share of the stage requests and the barriers of the main loop
+    if (dma_wave) VVS_WAIT_STAGES;
     __syncthreads();
-    for (int s = 0; s < nst; ++s) __builtin_amdgcn_s_barrier();
+    for (int s = 0; s < nst; ++s) {
+      if (dma_wave) {                      // into the slot stage s - 1 has left: everybody finished reading it before the last barrier
+        request(s + NSL - 1);
+        VVS_WAIT_STAGES;
+      }
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+    }
+    if (dma_wave) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // before the tile reuses the ring
+    // the K / V operands of this wave's first steps, where they lie wholly below the cache length (old keys only): they
+    // arrive while the tile goes through the epilogue
+#pragma unroll
+    for (int p = 0; p < PD; ++p) {
+      early[p] = aw + p * NW < (kv >> 5);  // wave-uniform
+      if (early[p]) VVS_ATTN_LOAD(aw + p * NW, kf[p], vf[p]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
-  if (gemm_wave) {                         // row factors
+  const int S = kv, n_keys = S + T, nsteps = (n_keys + 31) >> 5;
+  if (lo4) {                               // row factors
     const int row = threadIdx.x >> 2, part = threadIdx.x & 3;
     float t = 0.f;
 #pragma unroll
@@ -1349,21 +1382,25 @@ __global__ __launch_bounds__(512) void k_qkv_attn(const uint4* __restrict__ Ap, 
     if (part == 0) rs[row] = 1.0f / sqrtf(t / (float)ep.dnorm + ep.eps);
   }
 #undef VVS_WAIT_STAGES
+  VVS_PHASE_MARK(2);
   __syncthreads();                         // the stage buffers become the output tile
   if (gemm_wave) {
 #pragma unroll
-    for (int j = 0; j < WN; ++j)
+    for (int i = 0; i < WM; ++i)
 #pragma unroll
-      for (int rr = 0; rr < 16; ++rr)
-        red[(wr * 32 + (rr >> 2) * 8 + (lane >> 5) * 4 + (rr & 3)) * LDC + (wc * WN + j) * 32 + (lane & 31)] = acc[j][rr];
+      for (int j = 0; j < WN; ++j)
+#pragma unroll
+        for (int rr = 0; rr < 16; ++rr)
+          red[((wr * WM + i) * 32 + (rr >> 2) * 8 + (lane >> 5) * 4 + (rr & 3)) * LDC + (wc * WN + j) * 32 + (lane & 31)] = acc[i][j][rr];
   }
   __syncthreads();
+  VVS_PHASE_MARK(3);
 
   // ---- epilogue: tile columns 0..63 q, 64..127 k, 128..191 v of head hd; tile row = 32 * (row of the pair) + token
   constexpr int np = DH >> 2, half = DH >> 1;   // rotary pairs per grid axis; dims of the grid-row half
   {                                        // q: one unit = (tile row, 16 consecutive dims) per thread of waves 0-3
     const int row = (threadIdx.x >> 2) & 63, c0 = (threadIdx.x & 3) * 16, t = row & 31;
-    if (gemm_wave && t < T) {
+    if (lo4 && t < T) {
       const float4* p4 = (const float4*)(red + row * LDC + c0);
       const float4 s0 = p4[0], s1 = p4[1], s2 = p4[2], s3 = p4[3];
       float v[16] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w, s2.x, s2.y, s2.z, s2.w, s3.x, s3.y, s3.z, s3.w};
@@ -1427,6 +1464,7 @@ __global__ __launch_bounds__(512) void k_qkv_attn(const uint4* __restrict__ Ap, 
   // the cache writes have reached L2 (the L1 is write-through) and q is in LDS before anybody goes on
   __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
   __syncthreads();
+  VVS_PHASE_MARK(4);
 
   // ---- attention of (head hd, row 2b + ar) by its four waves (see k_attn_mfma)
   bf16x8 qf[NQB][KD];
@@ -1466,57 +1504,43 @@ __global__ __launch_bounds__(512) void k_qkv_attn(const uint4* __restrict__ Ap, 
     }
   }
 #undef VVS_ATTN_LOAD
-  // merge the waves' partial results (waves 1.. of a row publish, wave 0 combines and writes); the buffers lie where
-  // the output tile was: everybody is past the epilogue's reads of it (the barrier in front of the attention)
-  if (aw > 0) {
+  VVS_PHASE_MARK(5);
+  // merge the partial results of a row's four waves: every wave publishes (running maximum, sum, accumulators), then
+  // wave aw combines and writes the 16 dims of block dt = aw for all queries.  The buffers lie where the output tile was:
+  // everybody is past the epilogue's reads of it (the barrier in front of the attention).
+  static_assert(DT == NW, "one 16-dim block per wave of the row");
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-      const int qi = qb * 16 + ql, ui = (ar * (NW - 1) + aw - 1) * NQ + qi;
-      if (g == 0) { s_m[ui] = m_run[qb]; s_l[ui] = l_run[qb]; }
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int qi = qb * 16 + ql, ui = (ar * NW + aw) * NQ + qi;
+    if (g == 0) { s_m[ui] = m_run[qb]; s_l[ui] = l_run[qb]; }
 #pragma unroll
-      for (int dt = 0; dt < DT; ++dt)
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) s_o[ui * (DH + 1) + dt * 16 + 4 * g + rr] = o[qb][dt][rr];
-    }
+      for (int rr = 0; rr < 4; ++rr) s_o[ui * (DH + 1) + dt * 16 + 4 * g + rr] = o[qb][dt][rr];
   }
   __syncthreads();
-  if (aw == 0) {
+  VVS_PHASE_MARK(6);
 #pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-      const int qi = qb * 16 + ql;
-      float m = m_run[qb];
+  for (int qb = 0; qb < NQB; ++qb) {
+    const int qi = qb * 16 + ql;
+    float mw[NW], m = -INFINITY;
 #pragma unroll
-      for (int w = 0; w < NW - 1; ++w) m = fmaxf(m, s_m[(ar * (NW - 1) + w) * NQ + qi]);
-      const float m_safe = m == -INFINITY ? 0.f : m;
-      const float a0 = exp2f((m_run[qb] - m_safe) * c_exp);
-      float l = l_run[qb] * a0;
-      float awt[NW - 1];
+    for (int w = 0; w < NW; ++w) { mw[w] = s_m[(ar * NW + w) * NQ + qi]; m = fmaxf(m, mw[w]); }
+    const float m_safe = m == -INFINITY ? 0.f : m;
+    float l = 0.f, v[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int w = 0; w < NW - 1; ++w) {
-        awt[w] = exp2f((s_m[(ar * (NW - 1) + w) * NQ + qi] - m_safe) * c_exp);
-        l += s_l[(ar * (NW - 1) + w) * NQ + qi] * awt[w];
-      }
-      const float inv = 1.0f / l;
-      if (qi < T) {
+    for (int w = 0; w < NW; ++w) {         // fixed order: waves 0, 1, 2, 3
+      const float wt = exp2f((mw[w] - m_safe) * c_exp);
+      l += s_l[(ar * NW + w) * NQ + qi] * wt;
+      const float* so = s_o + ((ar * NW + w) * NQ + qi) * (DH + 1) + aw * 16 + 4 * g;
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          uint32_t pk[2];
-#pragma unroll
-          for (int rr = 0; rr < 4; rr += 2) {
-            float v0 = o[qb][dt][rr] * a0, v1 = o[qb][dt][rr + 1] * a0;
-#pragma unroll
-            for (int w = 0; w < NW - 1; ++w) {
-              const float* so = s_o + ((ar * (NW - 1) + w) * NQ + qi) * (DH + 1) + dt * 16 + 4 * g + rr;
-              v0 += so[0] * awt[w];
-              v1 += so[1] * awt[w];
-            }
-            pk[rr >> 1] = pack2bf(v0 * inv, v1 * inv);
-          }
-          *(uint2*)(out + pack_index(r * T + qi, hd * DH + dt * 16 + 4 * g, d)) = make_uint2(pk[0], pk[1]);   // O-projection operand layout
-        }
-      }
+      for (int rr = 0; rr < 4; ++rr) v[rr] += so[rr] * wt;
     }
+    const float inv = 1.0f / l;
+    if (qi < T)                            // O-projection operand layout
+      *(uint2*)(out + pack_index(r * T + qi, hd * DH + aw * 16 + 4 * g, d)) = make_uint2(pack2bf(v[0] * inv, v[1] * inv), pack2bf(v[2] * inv, v[3] * inv));
   }
+  VVS_PHASE_MARK(7);
 }
 
 // True when a verify call of T block tokens per row takes the fused projection + attention kernel.
