@@ -391,12 +391,23 @@ def main():
     ctx.vvs_timing_enable(False)
     S_mean = float(state0[0].mean())
     cnt = algorithmic_counts(shape, S_mean)
+    if not ctx.vvs_plan_is_fused(N + 1):
+        layer_plan = "separate normalisation kernels (7 launches per layer)"
+    elif classes["attention"]["launches_per_step"] == 0:
+        layer_plan = "fused (4 launches per layer: projection + attention in one)"
+    else:
+        layer_plan = "fused (5 launches per layer)"
     dom = max(("gemm", "attention"), key=lambda k: classes[k]["ms_per_step"])
     if dom == "gemm":
         n_launch = classes["gemm"]["launches_per_step"]
         t_launch = classes["gemm"]["ms_per_step"] * 1e-3 / n_launch
         bytes_launch, flops_launch = cnt["w_bytes"] / n_launch, cnt["gemm_flops"] / n_launch
         kernel = "k_gemm_direct + k_gemm_shared (all bf16 projection GEMMs of one verify call)"
+        if classes["attention"]["launches_per_step"] == 0:
+            # the q/k/v projection and attention run in one launch (k_qkv_attn): its cache traffic and flops belong to these launches
+            bytes_launch += (cnt["kv_read"] + cnt["kv_write"]) / n_launch
+            flops_launch += cnt["attn_flops"] / n_launch
+            kernel = "k_qkv_attn + k_gemm_direct + k_gemm_shared (all projection launches of one verify call; attention runs inside the first)"
     else:
         n_launch = classes["attention"]["launches_per_step"]
         t_launch = classes["attention"]["ms_per_step"] * 1e-3 / n_launch
@@ -430,7 +441,7 @@ def main():
                    "cache_len_mean": S_mean, "mode": args.mode, "draft_noise_std": noise,
                    "draft_noise_calibrated_to_tokens_per_forward": target_tpf if calibration is not None else None,
                    "launch": "hip graph replay" if args.graph else "eager", "post_verified_tokens": args.post,
-                   "draft_sets": n_sets, "layer_plan": "fused (5 kernels)" if ctx.vvs_plan_is_fused(N + 1) else "separate normalisation kernels"},
+                   "draft_sets": n_sets, "layer_plan": layer_plan},
         "shape": {"layers": shape.n_layers, "d_model": shape.d_model, "heads": shape.n_heads, "d_ff": shape.d_ff,
                   "allowed_ids": shape.v_eff, "grid": [shape.grid_h, shape.grid_w], "prefix_len": shape.prefix_len},
         "verify_latency_ms": ms_per_step, "mean_accept_len": float(accept.mean()),

@@ -130,9 +130,11 @@ def traffic(fetch_db: str, write_db: str, kernel: str, grids, out_json=None) -> 
         cal = cur.execute("select avg(value) from counters_collection where kernel_name like '%k_copy_bytes%' and counter_name = ?",
                           (name,)).fetchone()[0]
         factor = (256 << 10) / cal            # the copy reads and writes 262144 KiB
-        q = ("select count(*), avg(value) from counters_collection where kernel_name like ? and counter_name = ? "
-             "and grid_size_x / workgroup_size_x in (%s)" % ",".join(str(int(g)) for g in grids))
-        n, avg = cur.execute(q, (f"%{kernel}%", name)).fetchone()
+        names = [k for k in kernel.split(",") if k]      # several kernel-name substrings, comma-separated
+        q = ("select count(*), avg(value) from counters_collection where (%s) and counter_name = ? "
+             "and grid_size_x / workgroup_size_x in (%s)" % (" or ".join("kernel_name like ?" for _ in names),
+                                                            ",".join(str(int(g)) for g in grids)))
+        n, avg = cur.execute(q, tuple(f"%{k}%" for k in names) + (name,)).fetchone()
         res[name] = {"copy_kernel_reads_KiB": cal, "scale_factor": factor, "dispatches": n, "avg_KiB_per_dispatch": avg,
                      "scaled_bytes_per_launch": avg * 1024 * factor}
         total += avg * 1024 * factor
