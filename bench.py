@@ -181,6 +181,7 @@ def main():
     ap.add_argument("--norm-mode", choices=["auto", "separate"], default="auto",
                     help="vvs_config.norm_mode: separate = always the normalisation kernels that round where the definition does")
     ap.add_argument("--layers", type=int, default=0, help="override depth (debugging only; the result is then not the named workload)")
+    ap.add_argument("--prompts", type=int, default=0, help="override the number of prompts (debugging only; the result is then not the named workload)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; prompts shard across GPUs without any collective, which is not "
@@ -194,6 +195,8 @@ def main():
     shape = synth.SHAPES[args.workload]
     if args.layers:
         shape = shape.replace(n_layers=args.layers)
+    if args.prompts:
+        shape = shape.replace(n_prompts=args.prompts)
     if args.post:
         shape = shape.replace(n_nodes=shape.n_nodes + args.post)
     n_emitted = shape.grid // 2 if args.image_tokens < 0 else args.image_tokens

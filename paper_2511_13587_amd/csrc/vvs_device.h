@@ -164,8 +164,8 @@ inline void allow_dynamic_lds(const void* kernel, size_t bytes) {
 void mfma_gemm(const bf16_t* A, const bf16_t* W, float* C, int M, int N, int K, GemmPlan p, hipStream_t s);
 void mfma_gemm_scaled(Ctx* c, const bf16_t* A, const bf16_t* W, float* C, const float* ss, int M, int N, int K, GemmPlan p, hipStream_t s);
 void mfma_gemm_resid(Ctx* c, const bf16_t* A, const bf16_t* W, float* x, bf16_t* xb, float* ss_out, const float* g_next, int M, int K,
-                     hipStream_t s, int xb_T = 0 /* > 0: xb row-padded to 32 rows per xb_T tokens */);
-bool mfma_qkv_attention_ok(const Ctx* c, const PosDesc& pos, int T);
+                     hipStream_t s, int xb_T = 0, int xb_pad = 0 /* xb_T > 0: xb row-padded to xb_pad rows per xb_T tokens */);
+int mfma_qkv_attention_rows(const Ctx* c, const PosDesc& pos, int T);
 void mfma_qkv_attention(Ctx* c, int layer, const bf16_t* A, const bf16_t* Wqkv, const float* ss, const TreeDesc& tree, const PosDesc& pos,
                         int T, hipStream_t s);
 void mfma_gemm_swiglu(Ctx* c, const bf16_t* A, const bf16_t* Wgu, bf16_t* act, const float* ss, int M, int F, int K, GemmPlan p,

@@ -202,10 +202,10 @@ __global__ void k_embed(float* __restrict__ x, const T* __restrict__ embed, cons
 // other slabs 0).
 __global__ __launch_bounds__(256) void k_embed_packed(float* __restrict__ x, bf16_t* __restrict__ xb, float* __restrict__ ss, int NS,
                                                       const bf16_t* __restrict__ embed, const bf16_t* __restrict__ prefix_tab,
-                                                      const float* __restrict__ g, EmbedArgs a, int pad_T) {
+                                                      const float* __restrict__ g, EmbedArgs a, int pad_T, int pad) {
   __shared__ float red[16];
   const int m = blockIdx.x;
-  const int mp = pad_T > 0 ? (m / pad_T) * 32 + m % pad_T : m;   // row of the packed operand (row-padded layout: 32 rows per pad_T tokens)
+  const int mp = pad_T > 0 ? (m / pad_T) * pad + m % pad_T : m;   // row of the packed operand (row-padded layout: pad rows per pad_T tokens)
   const bf16_t* src = embed_source(embed, prefix_tab, a, m);
   float sq = 0.f;
   for (int k0 = threadIdx.x * 8; k0 < a.d; k0 += 256 * 8) {
@@ -482,17 +482,18 @@ static void forward_fused(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int 
                n_forced, forced};
   const float* g_first = (const float*)(c->pw + c->p.layer0 + c->p.g1);   // gain of the first layer's first norm
   const float* gf = (const float*)(c->pw + c->p.gf);
-  // verify calls of up to 32 tokens per row: projection + attention in one launch, fed by the row-padded operand layout
-  const bool qa = mfma_qkv_attention_ok(c, pos, Tq);
+  // verify calls of up to 64 tokens per row at head size 64: projection + attention in one launch, fed by the row-padded operand layout
+  const int pad = mfma_qkv_attention_rows(c, pos, Tq);
+  const bool qa = pad > 0;
   const int pad_T = qa ? Tq : 0;
   if (from_din) {             // drafter: x = [embedding ; feature] W_fc, through the residual epilogue on a zeroed x
     launch_fill_zero(x, sizeof(float) * (size_t)M * d, s);
     Timed timed(c, VVS_K_GEMM, s);
-    mfma_gemm_resid(c, (const bf16_t*)(c->ws + c->w.din), (const bf16_t*)(c->pw + c->p.fc), x, xb, ss, g_first, M, 2 * d, s, pad_T);
+    mfma_gemm_resid(c, (const bf16_t*)(c->ws + c->w.din), (const bf16_t*)(c->pw + c->p.fc), x, xb, ss, g_first, M, 2 * d, s, pad_T, pad);
   } else {
     Timed timed(c, VVS_K_ELEMENTWISE, s);
     hipLaunchKernelGGL(k_embed_packed, dim3(M), dim3(256), 0, s, x, xb, ss, NS, (const bf16_t*)(c->pw + c->p.embed),
-                       (const bf16_t*)(c->pw + c->p.prefix_embed), g_first, ea, pad_T);
+                       (const bf16_t*)(c->pw + c->p.prefix_embed), g_first, ea, pad_T, pad);
   }
   const GemmPlan pq = plan_gemm(c, M, 3 * d, d), pg = plan_gemm(c, M, 2 * F, d);
   for (int l = 0; l < c->L; ++l) {
@@ -517,7 +518,7 @@ static void forward_fused(Ctx* c, const TreeDesc& tree, const PosDesc& pos, int 
     { Timed timed(c, VVS_K_GEMM, s);
       // the next reader of x is the next layer's first norm, or the final norm
       const float* g_next = l + 1 < c->L ? (const float*)(lw + c->p.layer_stride + c->p.g1) : gf;
-      mfma_gemm_resid(c, act, (const bf16_t*)(lw + c->p.wd), x, xb, ss, g_next, M, F, s, l + 1 < c->L ? pad_T : 0);
+      mfma_gemm_resid(c, act, (const bf16_t*)(lw + c->p.wd), x, xb, ss, g_next, M, F, s, l + 1 < c->L ? pad_T : 0, pad);
     }
   }
   if (logits_mode == 0) return;

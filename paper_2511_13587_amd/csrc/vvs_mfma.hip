@@ -78,7 +78,7 @@ struct GemmEpi {
   const float* ss; int NS; float eps; int dnorm;           // row scale (ss == nullptr: no scaling); ss[M][NS]
   bf16_t* act; int F;                                      // EPI_SWIGLU
   float* x; bf16_t* xb; float* ss_out; const float* g_next; // EPI_RESID (g_next: gain of the norm that reads x next)
-  int xb_T;                                                // EPI_RESID: > 0 = xb in the row-padded layout (row m at (m / xb_T) * 32 + m % xb_T)
+  int xb_T, xb_pad;                                        // EPI_RESID: xb_T > 0 = xb in the row-padded layout (row m at (m / xb_T) * xb_pad + m % xb_T)
   bf16_t* q; bf16_t* kc; bf16_t* vc; const float* rope;    // EPI_QKV
   int T, d, dh, S_cap, rope_pos;
   int row_owner;                                           // tile order of the direct-to-LDS kernel: 1 = an XCD owns row tiles
@@ -281,7 +281,7 @@ __device__ __forceinline__ void tile_epilogue(const float* red, const float* rs,
         *(float4*)xp = make_float4(v[0], v[1], v[2], v[3]);
         *(float4*)(xp + 4) = make_float4(v[4], v[5], v[6], v[7]);
         const float hv[8] = {v[0] * ga.x, v[1] * ga.y, v[2] * ga.z, v[3] * ga.w, v[4] * gb.x, v[5] * gb.y, v[6] * gb.z, v[7] * gb.w};
-        store8(ep.xb, ep.xb_T > 0 ? (m / ep.xb_T) * 32 + m % ep.xb_T : m, n0 + c8, N, hv);
+        store8(ep.xb, ep.xb_T > 0 ? (m / ep.xb_T) * ep.xb_pad + m % ep.xb_T : m, n0 + c8, N, hv);
 #pragma unroll
         for (int i = 0; i < 8; ++i) sq += v[i] * v[i];
       }
@@ -933,9 +933,9 @@ void mfma_gemm_scaled(Ctx* c, const bf16_t* A, const bf16_t* W, float* C, const 
 
 // x += A W; also leaves bf16(x * g_next) packed and the per-slab sums of squares of the new x
 void mfma_gemm_resid(Ctx* c, const bf16_t* A, const bf16_t* W, float* x, bf16_t* xb, float* ss_out, const float* g_next, int M, int K,
-                     hipStream_t s, int xb_T) {
+                     hipStream_t s, int xb_T, int xb_pad) {
   GemmEpi ep{};
-  ep.x = x; ep.xb = xb; ep.ss_out = ss_out; ep.g_next = g_next; ep.NS = (c->d / 64 + 3) & ~3; ep.xb_T = xb_T;
+  ep.x = x; ep.xb = xb; ep.ss_out = ss_out; ep.g_next = g_next; ep.NS = (c->d / 64 + 3) & ~3; ep.xb_T = xb_T; ep.xb_pad = xb_pad;
   // many rows: 192 x 128 tiles with the operands shared through LDS (a quarter of the bytes per flop that 64 x 64 tiles pull
   // through a CU's L1), when they give most CUs a tile - at d = 1280 and 3904 rows: 210 tiles, one round
   if (c->d % 128 == 0 && K % 32 == 0 && ((M + 191) / 192) * (c->d / 128) >= 160) {
@@ -1189,57 +1189,67 @@ __global__ __launch_bounds__(NW * QG * 64, (DH * NQB >= 256 ? 1 : 2)) void k_att
 }
 
 // ------------------------------------------------------------------------------------------------ q/k/v projection + attention in one launch
-// Verify calls with at most 32 block tokens per row and head size 64: one workgroup per (head, prompt) computes the head's
+// Verify calls with at most 64 block tokens per row and head size 64: one workgroup per (head, prompt) computes the head's
 // q, k and v columns for the prompt's two rows (conditional, unconditional) and goes straight on to their attention, so that
 // the layer has one launch less and attention does not start from a cold ramp of its own: q never leaves the CU, and k / v
 // are read back from the cache lines the same workgroup has just written.
-//   Projection: a 64 x 192 tile on the direct-to-LDS pipeline of k_gemm_shared_dma (2 x 2 waves of 32 x 96; a stage = 32
-//     contraction values = 16 KiB).  The activation operand comes in the ROW-PADDED packed layout - row-block r holds
-//     the T tokens of row r, so the tile's two row-blocks are 2b and 2b + 1 - and the weight blocks are the head's two
+//   TR = 32 or 64: tile rows per row of the pair (T <= TR).
+//   Projection: a (2 TR) x 192 tile on the direct-to-LDS pipeline of k_gemm_shared_dma (2 x 2 waves of TR x 96; a stage = 32
+//     contraction values = 16 or 20 KiB).  The activation operand comes in the ROW-PADDED packed layout - row r starts at
+//     packed row r * TR, so the tile's row-blocks are those of rows 2b and 2b + 1 - and the weight blocks are the head's two
 //     32-row blocks inside each of the q, k and v thirds.  Tile rows t >= T are padding: every output row depends on its
 //     own operand row only, and those rows are never used.
 //   Epilogue: RMSNorm row factor, 2D rotary embedding of q and k; q goes to LDS (bf16), k and v into their cache slots.
 //   Attention: as k_attn_mfma with four waves per (head, row) - the workgroup has 8 waves: waves 0-3 run the projection,
-//     then even waves take the conditional row and odd waves the unconditional one - reading q fragments from LDS.  Waves
-//     4-7 have no MFMAs during the projection: they take half of the stage requests and meet the barriers, and when the
-//     last stage has landed they request the K / V operands of their first steps, where those steps lie wholly below the
-//     cache length (old keys), so that these arrive while the tile goes through the epilogue.  Every other cache load stands
-//     behind the workgroup-scope fence and the barrier that follow the cache writes, and no line holding a slot of the
-//     block itself is read before them, so the L1 of the CU cannot hold a stale copy of the slots just written.
-//   Measured with time stamps at the end of the image (55 k cycles): start-up 3 k, projection main loop 24 k (16 KiB per
-//     600 cycles: the L1 fill rate of a CU), tile to LDS 2.5 k, epilogue + fence 5 k, attention steps 17 k (VALU-bound: 8
+//     then even waves take the conditional row and odd waves the unconditional one - reading q fragments from LDS.  With
+//     TR = 64 a row's waves form two groups of two, one per 32 queries (64 queries per wave would not fit the registers).
+//     Waves 4-7 have no MFMAs during the projection: they take their share of the stage requests (TR = 32) and meet the
+//     barriers, and when the last stage has landed they request the K / V operands of their first steps, where those steps
+//     lie wholly below the cache length (old keys), so that these arrive while the tile goes through the epilogue.  Every
+//     other cache load stands behind the workgroup-scope fence and the barrier that follow the cache writes, and no line
+//     holding a slot of the block itself is read before them, so the L1 of the CU cannot hold a stale copy of the slots
+//     just written.
+//   Measured with time stamps at the end of the image (TR = 32, 55 k cycles): start-up 3 k, projection main loop 24 k (16 KiB
+//     per 600 cycles: the L1 fill rate of a CU), tile to LDS 2.5 k, epilogue + fence 5 k, attention steps 17 k (VALU-bound: 8
 //     waves share 4 SIMDs), merge + store 3 k.
-template <int NSL, int NQB>
+template <int NSL, int TR, int NQB>
 __global__ __launch_bounds__(512) void k_qkv_attn(const uint4* __restrict__ Ap, const uint4* __restrict__ Wp, bf16_t* __restrict__ out,
                                                   int K, const GemmEpi ep, float c_exp) {
-  constexpr int GW = 4;                    // projection waves: 4 = 2 x 2 of 32 x 96 (2 = 1 x 2 of 64 x 96 measured 3 % slower per step)
-  constexpr int DW = 8;                    // waves that request stage blocks (the projection waves among them)
-  static_assert(DW >= GW && 16 % DW == 0, "stage blocks are dealt to the requesting waves");
-  constexpr int WM = 4 / GW, WN = 3, BM = 64, BN = 192, LDC = BN + 4, NA = 4, NBLK = 16, PER = NBLK / DW;
-  constexpr int DH = 64, KD = DH / 32, DT = DH / 16, NQ = NQB * 16, PD = 2, NW = 4;
+  constexpr int GW = 4;                    // projection waves: 2 x 2 of TR x 96 (1 x 2 of 64 x 96 at TR = 32 measured 3 % slower per step)
+  constexpr int RB = TR / 32;              // 32-row blocks per row of the pair
+  constexpr int WM = RB, WN = 3, BM = 2 * TR, BN = 192, LDC = BN + 4, NA = 2 * (BM / 32), NBLK = NA + 12;
+  constexpr int DW = NBLK % 8 == 0 ? 8 : 4;   // waves that request stage blocks (the projection waves among them)
+  constexpr int PER = NBLK / DW;
+  static_assert(TR == 32 || TR == 64, "one or two row-blocks per row");
+  static_assert(NBLK % DW == 0, "stage blocks are dealt to the requesting waves");
+  constexpr int DH = 64, KD = DH / 32, DT = DH / 16, NQ = NQB * 16, PD = 2;
+  constexpr int QG = RB, NW = 4 / QG;      // query groups of 32 per row, waves per group
+  static_assert(NQ * QG >= TR || (TR == 32 && NQB == 1), "every query has a lane");
   constexpr int QLD = DH + 8;              // bf16 per q row in LDS: 144 bytes, 16-byte aligned, rows spread over the banks
   constexpr size_t kRing = (size_t)NSL * NBLK * 1024, kTile = (size_t)BM * LDC * sizeof(float);
   constexpr size_t kFirst = kRing > kTile ? kRing : kTile;
   static_assert(NSL >= 4 && PER * (NSL - 1) <= 60, "stages in flight / 6-bit load counter");
-  static_assert(kFirst >= (size_t)2 * NW * NQ * (DH + 3) * sizeof(float), "the merge buffers reuse the tile");
-  extern __shared__ float red[];           // stage ring, then the 64 x 192 output tile, then the attention merge buffers; behind it q
+  static_assert(kFirst >= (size_t)2 * 4 * NQ * (DH + 3) * sizeof(float), "the merge buffers reuse the tile");
+  extern __shared__ float red[];           // stage ring, then the output tile, then the attention merge buffers; behind it q
   u32x4* stage = (u32x4*)red;
-  bf16_t* q_s = (bf16_t*)((char*)red + kFirst);                // [2 rows][32 tokens][QLD]
-  float* s_o = red;                                            // [2 rows][NW][NQ][DH + 1]
-  float* s_m = s_o + 2 * NW * NQ * (DH + 1);                   // [2 rows][NW][NQ]
-  float* s_l = s_m + 2 * NW * NQ;
+  bf16_t* q_s = (bf16_t*)((char*)red + kFirst);                // [2 rows][TR tokens][QLD]
+  float* s_o = red;                                            // [2 rows][4 waves][NQ][DH + 1]
+  float* s_m = s_o + 2 * 4 * NQ * (DH + 1);                    // [2 rows][4 waves][NQ]
+  float* s_l = s_m + 2 * 4 * NQ;
   __shared__ float rs[BM];
   const uint32_t lds_base = (uint32_t)(uintptr_t)stage;
   VVS_PHASE_MARK(0);
   const int hd = blockIdx.x, b = blockIdx.y, T = ep.T, d = ep.d;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const bool gemm_wave = wave < GW, dma_wave = wave < DW, lo4 = wave < 4;   // lo4: the 256 threads that own the row factors and the q epilogue
-  const int wr = GW == 4 ? (wave >> 1) & 1 : 0, wc = wave & 1;
-  const int ar = wave & 1, aw = wave >> 1; // attention: row of the pair, wave within the row (each row: two projection waves, two others)
+  const bool gemm_wave = wave < GW, dma_wave = wave < DW;
+  const bool rs_thread = (int)threadIdx.x < BM * 4;   // the threads that own the row factors: 4 lanes per tile row
+  const int wr = (wave >> 1) & 1, wc = wave & 1;
+  // attention: row of the pair, wave within the row (each row: two projection waves, two others), query group, wave within the group
+  const int ar = wave & 1, ai = wave >> 1, qg = ai / NW, aw = ai % NW, q0 = qg * 32;
   const int KB = K >> 4, nst = KB >> 1;
   // The prompt's cache length and emitted count come from memory (a scalar load that shares its counter with the
-  // kernel-argument loads): the projection waves ask for them only behind their first stage requests, so that nothing
-  // on the way to those requests waits for memory.
+  // kernel-argument loads): they are asked for only behind the first stage requests, so that nothing on the way to those
+  // requests waits for memory.
   int kv, ne;
   float4 rv[4];                            // row factor inputs
   // attention operands (see k_attn_mfma): K and V of a 32-key step straight into MFMA operand registers
@@ -1259,19 +1269,20 @@ __global__ __launch_bounds__(512) void k_qkv_attn(const uint4* __restrict__ Ap, 
   bf16x8 kf[PD][2][KD], vf[PD][DT];
   bool early[PD];
   floatx16 acc[WM][WN];
-  auto load_rv = [&]() {                   // row factor inputs: 4 lanes per tile row, each every 4th group of 4 slabs (as RowScale)
-    const int row = threadIdx.x >> 2, part = threadIdx.x & 3, nq = ep.NS >> 2;
-    const int m = (2 * b + (row >> 5)) * T + min(row & 31, T - 1);
+  if (rs_thread) {                         // row factor inputs (as RowScale): each lane every 4th group of 4 slabs; addresses from
+    const int row = threadIdx.x >> 2, part = threadIdx.x & 3, nq = ep.NS >> 2;   // kernel arguments only, older than the stage requests
+    const int m = (2 * b + row / TR) * T + min(row % TR, T - 1);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       rv[i] = part + 4 * i < nq ? ((const float4*)(ep.ss + (size_t)m * ep.NS))[part + 4 * i] : make_float4(0.f, 0.f, 0.f, 0.f);
-  };
+  }
+  __builtin_amdgcn_sched_barrier(0);
   const u32x4* src[PER];
 #pragma unroll
   for (int i = 0; i < PER; ++i) {
-    const int j = min(wave + DW * i, NBLK - 1);   // block of the stage: 0..3 activations (row-block, contraction half), 4..15 weights
+    const int j = min(wave + DW * i, NBLK - 1);   // block of the stage: 0 .. NA-1 activations (row-block, contraction half), then 12 weight blocks
     const int wi = (j - NA) >> 1;          // weight block: third (q, k, v) = wi / 2, half of the head = wi % 2
-    const int rb = j < NA ? 2 * b + (j >> 1) : (wi >> 1) * (d >> 5) + 2 * hd + (wi & 1);
+    const int rb = j < NA ? 2 * b * RB + (j >> 1) : (wi >> 1) * (d >> 5) + 2 * hd + (wi & 1);
     src[i] = (const u32x4*)(j < NA ? Ap : Wp) + ((size_t)rb * KB + (j & 1)) * 64 + lane;
   }
   auto request = [&](int t) {
@@ -1280,8 +1291,6 @@ __global__ __launch_bounds__(512) void k_qkv_attn(const uint4* __restrict__ Ap, 
 #pragma unroll
     for (int i = 0; i < PER; ++i) lds_dma16(src[i] + kk, slot + (uint32_t)(wave + DW * i) * 1024u);
   };
-  if (lo4) load_rv();                      // addresses from kernel arguments only; older than the stage requests, so never waited for
-  __builtin_amdgcn_sched_barrier(0);
   if (dma_wave) {
 #pragma unroll
     for (int t = 0; t < NSL - 1; ++t) request(t);
@@ -1296,59 +1305,59 @@ __global__ __launch_bounds__(512) void k_qkv_attn(const uint4* __restrict__ Ap, 
 #define VVS_WAIT_STAGES asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PER * (NSL - 3)) : "memory")
   if (gemm_wave) {
 #pragma unroll
-  for (int i = 0; i < WM; ++i)
+    for (int i = 0; i < WM; ++i)
 #pragma unroll
-    for (int j = 0; j < WN; ++j)
+      for (int j = 0; j < WN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-  VVS_WAIT_STAGES;                         // stages 0 and 1 of this wave have landed
-  __syncthreads();                         // ... and everybody else's
-  constexpr int NM = WM * WN, NR = WM + WN;
-  constexpr int IA = (NR + PER + NM - 1) / NM, IB = (NR + NM - 1) / NM;
-  auto lds_frag = [&](int t, int kbo, int i) {           // i-th fragment of a stage's block kbo: the A row-block first, then the B blocks
-    const int sl = (t % NSL) * NBLK;
-    return __builtin_bit_cast(bf16x8, stage[(sl + (i < WM ? (wr * WM + i) * 2 : NA + (wc * WN + (i - WM)) * 2) + kbo) * 64 + lane]);
-  };
-  bf16x8 fa0[WM], fb0[WN], fa1[WM], fb1[WN];
+        for (int rr = 0; rr < 16; ++rr) acc[i][j][rr] = 0.f;
+    VVS_WAIT_STAGES;                       // stages 0 and 1 of this wave have landed
+    __syncthreads();                       // ... and everybody else's
+    constexpr int NM = WM * WN, NR = WM + WN;
+    constexpr int IA = (NR + PER + NM - 1) / NM, IB = (NR + NM - 1) / NM;
+    auto lds_frag = [&](int t, int kbo, int i) {         // i-th fragment of a stage's block kbo: the A row-blocks first, then the B blocks
+      const int sl = (t % NSL) * NBLK;
+      return __builtin_bit_cast(bf16x8, stage[(sl + (i < WM ? (wr * WM + i) * 2 : NA + (wc * WN + (i - WM)) * 2) + kbo) * 64 + lane]);
+    };
+    bf16x8 fa0[WM], fb0[WN], fa1[WM], fb1[WN];
 #pragma unroll
-  for (int i = 0; i < WM; ++i) fa0[i] = lds_frag(0, 0, i);
+    for (int i = 0; i < WM; ++i) fa0[i] = lds_frag(0, 0, i);
 #pragma unroll
-  for (int j = 0; j < WN; ++j) fb0[j] = lds_frag(0, 0, WM + j);
-  // the main loop of k_gemm_shared_dma: everything but the MFMAs is dealt into the gaps between them
-  for (int s = 0; s < nst; ++s) {
-    const size_t kk = (size_t)min(s + NSL - 1, nst - 1) * 128;
-    const uint32_t slot = lds_base + (uint32_t)(((s + NSL - 1) % NSL) * NBLK) * 1024u;
+    for (int j = 0; j < WN; ++j) fb0[j] = lds_frag(0, 0, WM + j);
+    // the main loop of k_gemm_shared_dma: everything but the MFMAs is dealt into the gaps between them
+    for (int s = 0; s < nst; ++s) {
+      const size_t kk = (size_t)min(s + NSL - 1, nst - 1) * 128;
+      const uint32_t slot = lds_base + (uint32_t)(((s + NSL - 1) % NSL) * NBLK) * 1024u;
 #pragma unroll
-    for (int m = 0; m < NM; ++m) {
-      acc[m / WN][m % WN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[m / WN], fb0[m % WN], acc[m / WN][m % WN], 0, 0, 0);
+      for (int m = 0; m < NM; ++m) {
+        acc[m / WN][m % WN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa0[m / WN], fb0[m % WN], acc[m / WN][m % WN], 0, 0, 0);
 #pragma unroll
-      for (int it = m * IA; it < (m + 1) * IA; ++it) {
-        if (it < NR) {
-          if (it < WM) fa1[it] = lds_frag(s, 1, it); else fb1[it - WM] = lds_frag(s, 1, it);
-        } else if (it - NR < PER) {
-          const int i = it - NR;
-          lds_dma16(src[i] + kk, slot + (uint32_t)(wave + DW * i) * 1024u);
+        for (int it = m * IA; it < (m + 1) * IA; ++it) {
+          if (it < NR) {
+            if (it < WM) fa1[it] = lds_frag(s, 1, it); else fb1[it - WM] = lds_frag(s, 1, it);
+          } else if (it - NR < PER) {
+            const int i = it - NR;
+            lds_dma16(src[i] + kk, slot + (uint32_t)(wave + DW * i) * 1024u);
+          }
         }
+        __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_sched_barrier(0);
-    }
 #pragma unroll
-    for (int m = 0; m < NM; ++m) {
-      acc[m / WN][m % WN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[m / WN], fb1[m % WN], acc[m / WN][m % WN], 0, 0, 0);
+      for (int m = 0; m < NM; ++m) {
+        acc[m / WN][m % WN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa1[m / WN], fb1[m % WN], acc[m / WN][m % WN], 0, 0, 0);
 #pragma unroll
-      for (int it = m * IB; it < (m + 1) * IB; ++it) {
-        if (it < NR) {
-          if (it < WM) fa0[it] = lds_frag(s + 1, 0, it); else fb0[it - WM] = lds_frag(s + 1, 0, it);
+        for (int it = m * IB; it < (m + 1) * IB; ++it) {
+          if (it < NR) {
+            if (it < WM) fa0[it] = lds_frag(s + 1, 0, it); else fb0[it - WM] = lds_frag(s + 1, 0, it);
+          }
         }
+        if (m == NM / 2) {
+          VVS_WAIT_STAGES;                 // this wave's part of stage s + 2
+          __builtin_amdgcn_s_barrier();    // ... and everybody else's; and everybody is done reading stage s
+          asm volatile("" ::: "memory");
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
-      if (m == NM / 2) {
-        VVS_WAIT_STAGES;                   // this wave's part of stage s + 2
-        __builtin_amdgcn_s_barrier();      // ... and everybody else's; and everybody is done reading stage s
-        asm volatile("" ::: "memory");
-      }
-      __builtin_amdgcn_sched_barrier(0);
     }
-  }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the repeated last stages still in flight must land before the tile reuses their LDS
   } else {                                 // the other waves: their share of the stage requests and the barriers of the main loop
     if (dma_wave) VVS_WAIT_STAGES;
@@ -1372,7 +1381,7 @@ __global__ __launch_bounds__(512) void k_qkv_attn(const uint4* __restrict__ Ap, 
     }
   }
   const int S = kv, n_keys = S + T, nsteps = (n_keys + 31) >> 5;
-  if (lo4) {                               // row factors
+  if (rs_thread) {                         // row factors
     const int row = threadIdx.x >> 2, part = threadIdx.x & 3;
     float t = 0.f;
 #pragma unroll
@@ -1396,11 +1405,12 @@ __global__ __launch_bounds__(512) void k_qkv_attn(const uint4* __restrict__ Ap, 
   __syncthreads();
   VVS_PHASE_MARK(3);
 
-  // ---- epilogue: tile columns 0..63 q, 64..127 k, 128..191 v of head hd; tile row = 32 * (row of the pair) + token
+  // ---- epilogue: tile columns 0..63 q, 64..127 k, 128..191 v of head hd; tile row = TR * (row of the pair) + token
   constexpr int np = DH >> 2, half = DH >> 1;   // rotary pairs per grid axis; dims of the grid-row half
-  {                                        // q: one unit = (tile row, 16 consecutive dims) per thread of waves 0-3
-    const int row = (threadIdx.x >> 2) & 63, c0 = (threadIdx.x & 3) * 16, t = row & 31;
-    if (lo4 && t < T) {
+#pragma unroll
+  for (int u = threadIdx.x; u < BM * 4; u += 512) {     // q: one unit = (tile row, 16 consecutive dims)
+    const int row = u >> 2, c0 = (u & 3) * 16, t = row % TR;
+    if (t < T) {
       const float4* p4 = (const float4*)(red + row * LDC + c0);
       const float4 s0 = p4[0], s1 = p4[1], s2 = p4[2], s3 = p4[3];
       float v[16] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w, s2.x, s2.y, s2.z, s2.w, s3.x, s3.y, s3.z, s3.w};
@@ -1421,44 +1431,47 @@ __global__ __launch_bounds__(512) void k_qkv_attn(const uint4* __restrict__ Ap, 
           v[4 * i + 3] = a1 * c4.w + b1 * c4.z;
         }
       }
-      uint4* dst = (uint4*)(q_s + ((row >> 5) * 32 + t) * QLD + c0);
+      uint4* dst = (uint4*)(q_s + row * QLD + c0);
       dst[0] = make_uint4(pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]), pack2bf(v[6], v[7]));
       dst[1] = make_uint4(pack2bf(v[8], v[9]), pack2bf(v[10], v[11]), pack2bf(v[12], v[13]), pack2bf(v[14], v[15]));
     }
   }
-  {                                        // k and v: a lane takes one tile row (token), the lanes of a wave consecutive tokens
-    const int row = threadIdx.x & 63, g4 = threadIdx.x >> 6, t = row & 31;
+  // k and v: a lane takes one tile row (token), the lanes of a wave consecutive tokens
+#pragma unroll
+  for (int u = threadIdx.x; u < BM * 8; u += 512) {     // k: one unit = (tile row, 8 dims), one 16-byte store each
+    const int row = u % BM, c8 = (u / BM) * 8, t = row % TR;
     const int slot = kv + t;
     if (t < T && slot >= 0 && slot < ep.S_cap) {
       const float sc = rs[row];
-      const size_t region = (size_t)(2 * b + (row >> 5)) * ep.row_stride + (size_t)hd * ep.head_stride;
-      bf16_t* kh = ep.kc + region;
-      bf16_t* vh = ep.vc + region;
+      bf16_t* kh = ep.kc + (size_t)(2 * b + row / TR) * ep.row_stride + (size_t)hd * ep.head_stride;
       const int img = ne - 1 + ep.tree.depth[t];
-      const int gr = min(max(img, 0) / ep.pos.grid_w, ep.rope_pos - 1), gc = max(img, 0) % ep.pos.grid_w;
-#pragma unroll
-      for (int c8 = g4 * 8; c8 < DH; c8 += 64) {         // k: 8-dim pieces, one 16-byte store each
-        const float4 a = *(const float4*)(red + row * LDC + DH + c8), bq = *(const float4*)(red + row * LDC + DH + c8 + 4);
-        float v[8] = {a.x * sc, a.y * sc, a.z * sc, a.w * sc, bq.x * sc, bq.y * sc, bq.z * sc, bq.w * sc};
-        if (img >= 0) {
-          const float4* t4 = (const float4*)(ep.rope + ((size_t)(c8 >= half ? gc : gr) * np + ((c8 & (half - 1)) >> 1)) * 2);
-          const float4 c0 = t4[0], c1 = t4[1];
-          const float x0 = v[0], x1 = v[1], x2 = v[2], x3 = v[3], x4 = v[4], x5 = v[5], x6 = v[6], x7 = v[7];
-          v[0] = x0 * c0.x - x1 * c0.y; v[1] = x0 * c0.y + x1 * c0.x;
-          v[2] = x2 * c0.z - x3 * c0.w; v[3] = x2 * c0.w + x3 * c0.z;
-          v[4] = x4 * c1.x - x5 * c1.y; v[5] = x4 * c1.y + x5 * c1.x;
-          v[6] = x6 * c1.z - x7 * c1.w; v[7] = x6 * c1.w + x7 * c1.z;
-        }
-        *(uint4*)(kh + k_index(slot, c8, DH)) = make_uint4(pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]), pack2bf(v[6], v[7]));
+      const float4 a = *(const float4*)(red + row * LDC + DH + c8), bq = *(const float4*)(red + row * LDC + DH + c8 + 4);
+      float v[8] = {a.x * sc, a.y * sc, a.z * sc, a.w * sc, bq.x * sc, bq.y * sc, bq.z * sc, bq.w * sc};
+      if (img >= 0) {
+        const int gr = min(img / ep.pos.grid_w, ep.rope_pos - 1), gc = img % ep.pos.grid_w;
+        const float4* t4 = (const float4*)(ep.rope + ((size_t)(c8 >= half ? gc : gr) * np + ((c8 & (half - 1)) >> 1)) * 2);
+        const float4 c0 = t4[0], c1 = t4[1];
+        const float x0 = v[0], x1 = v[1], x2 = v[2], x3 = v[3], x4 = v[4], x5 = v[5], x6 = v[6], x7 = v[7];
+        v[0] = x0 * c0.x - x1 * c0.y; v[1] = x0 * c0.y + x1 * c0.x;
+        v[2] = x2 * c0.z - x3 * c0.w; v[3] = x2 * c0.w + x3 * c0.z;
+        v[4] = x4 * c1.x - x5 * c1.y; v[5] = x4 * c1.y + x5 * c1.x;
+        v[6] = x6 * c1.z - x7 * c1.w; v[7] = x6 * c1.w + x7 * c1.z;
       }
+      *(uint4*)(kh + k_index(slot, c8, DH)) = make_uint4(pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]), pack2bf(v[6], v[7]));
+    }
+  }
 #pragma unroll
-      for (int c4 = g4 * 4; c4 < DH; c4 += 32) {         // v: 4 dims per step; a store instruction covers runs of consecutive slots
-        const float4 v = *(const float4*)(red + row * LDC + 2 * DH + c4);
-        vh[v_index(slot, c4, DH)] = f2bf(v.x * sc);
-        vh[v_index(slot, c4 + 1, DH)] = f2bf(v.y * sc);
-        vh[v_index(slot, c4 + 2, DH)] = f2bf(v.z * sc);
-        vh[v_index(slot, c4 + 3, DH)] = f2bf(v.w * sc);
-      }
+  for (int u = threadIdx.x; u < BM * 16; u += 512) {    // v: one unit = (tile row, 4 dims); a store instruction covers runs of consecutive slots
+    const int row = u % BM, c4 = (u / BM) * 4, t = row % TR;
+    const int slot = kv + t;
+    if (t < T && slot >= 0 && slot < ep.S_cap) {
+      const float sc = rs[row];
+      bf16_t* vh = ep.vc + (size_t)(2 * b + row / TR) * ep.row_stride + (size_t)hd * ep.head_stride;
+      const float4 v = *(const float4*)(red + row * LDC + 2 * DH + c4);
+      vh[v_index(slot, c4, DH)] = f2bf(v.x * sc);
+      vh[v_index(slot, c4 + 1, DH)] = f2bf(v.y * sc);
+      vh[v_index(slot, c4 + 2, DH)] = f2bf(v.z * sc);
+      vh[v_index(slot, c4 + 3, DH)] = f2bf(v.w * sc);
     }
   }
   // the cache writes have reached L2 (the L1 is write-through) and q is in LDS before anybody goes on
@@ -1466,15 +1479,15 @@ __global__ __launch_bounds__(512) void k_qkv_attn(const uint4* __restrict__ Ap, 
   __syncthreads();
   VVS_PHASE_MARK(4);
 
-  // ---- attention of (head hd, row 2b + ar) by its four waves (see k_attn_mfma)
+  // ---- attention of (head hd, row 2b + ar), queries q0 .. q0 + NQ - 1, by the NW waves of the group (see k_attn_mfma)
   bf16x8 qf[NQB][KD];
   uint64_t mask[NQB];
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
-    const int tq = min(qb * 16 + ql, T - 1);           // query rows past T repeat row T - 1 and are not stored
+    const int tq = min(q0 + qb * 16 + ql, T - 1);      // query rows past T repeat row T - 1 and are not stored
     mask[qb] = ep.tree.anc[tq];
 #pragma unroll
-    for (int kd = 0; kd < KD; ++kd) qf[qb][kd] = as_bf16x8(*(const uint4*)(q_s + (ar * 32 + tq) * QLD + kd * 32 + g * 8));
+    for (int kd = 0; kd < KD; ++kd) qf[qb][kd] = as_bf16x8(*(const uint4*)(q_s + (ar * TR + tq) * QLD + kd * 32 + g * 8));
   }
   float m_run[NQB], l_run[NQB];
   floatx4 o[NQB][DT];
@@ -1505,13 +1518,12 @@ __global__ __launch_bounds__(512) void k_qkv_attn(const uint4* __restrict__ Ap, 
   }
 #undef VVS_ATTN_LOAD
   VVS_PHASE_MARK(5);
-  // merge the partial results of a row's four waves: every wave publishes (running maximum, sum, accumulators), then
-  // wave aw combines and writes the 16 dims of block dt = aw for all queries.  The buffers lie where the output tile was:
-  // everybody is past the epilogue's reads of it (the barrier in front of the attention).
-  static_assert(DT == NW, "one 16-dim block per wave of the row");
+  // merge the partial results of a group's waves: every wave publishes (running maximum, sum, accumulators), then wave aw
+  // combines and writes the 16-dim blocks dt = aw, aw + NW, ... for all queries of the group.  The buffers lie where the
+  // output tile was: everybody is past the epilogue's reads of it (the barrier in front of the attention).
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
-    const int qi = qb * 16 + ql, ui = (ar * NW + aw) * NQ + qi;
+    const int qi = qb * 16 + ql, ui = (ar * 4 + ai) * NQ + qi;
     if (g == 0) { s_m[ui] = m_run[qb]; s_l[ui] = l_run[qb]; }
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -1522,30 +1534,45 @@ __global__ __launch_bounds__(512) void k_qkv_attn(const uint4* __restrict__ Ap, 
   VVS_PHASE_MARK(6);
 #pragma unroll
   for (int qb = 0; qb < NQB; ++qb) {
-    const int qi = qb * 16 + ql;
+    const int qi = qb * 16 + ql, w0 = ar * 4 + qg * NW;   // the group's waves are w0 .. w0 + NW - 1
     float mw[NW], m = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) { mw[w] = s_m[(ar * NW + w) * NQ + qi]; m = fmaxf(m, mw[w]); }
+    for (int w = 0; w < NW; ++w) { mw[w] = s_m[(w0 + w) * NQ + qi]; m = fmaxf(m, mw[w]); }
     const float m_safe = m == -INFINITY ? 0.f : m;
-    float l = 0.f, v[4] = {0.f, 0.f, 0.f, 0.f};
+    float wt[NW], l = 0.f;
 #pragma unroll
-    for (int w = 0; w < NW; ++w) {         // fixed order: waves 0, 1, 2, 3
-      const float wt = exp2f((mw[w] - m_safe) * c_exp);
-      l += s_l[(ar * NW + w) * NQ + qi] * wt;
-      const float* so = s_o + ((ar * NW + w) * NQ + qi) * (DH + 1) + aw * 16 + 4 * g;
-#pragma unroll
-      for (int rr = 0; rr < 4; ++rr) v[rr] += so[rr] * wt;
+    for (int w = 0; w < NW; ++w) {         // fixed order
+      wt[w] = exp2f((mw[w] - m_safe) * c_exp);
+      l += s_l[(w0 + w) * NQ + qi] * wt[w];
     }
     const float inv = 1.0f / l;
-    if (qi < T)                            // O-projection operand layout
-      *(uint2*)(out + pack_index(r * T + qi, hd * DH + aw * 16 + 4 * g, d)) = make_uint2(pack2bf(v[0] * inv, v[1] * inv), pack2bf(v[2] * inv, v[3] * inv));
+#pragma unroll
+    for (int dt = aw; dt < DT; dt += NW) {
+      float v[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        const float* so = s_o + ((w0 + w) * NQ + qi) * (DH + 1) + dt * 16 + 4 * g;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) v[rr] += so[rr] * wt[w];
+      }
+      if (q0 + qi < T)                     // O-projection operand layout
+        *(uint2*)(out + pack_index(r * T + q0 + qi, hd * DH + dt * 16 + 4 * g, d)) =
+            make_uint2(pack2bf(v[0] * inv, v[1] * inv), pack2bf(v[2] * inv, v[3] * inv));
+    }
   }
   VVS_PHASE_MARK(7);
 }
 
-// True when a verify call of T block tokens per row takes the fused projection + attention kernel.
-bool mfma_qkv_attention_ok(const Ctx* c, const PosDesc& pos, int T) {
-  return c->cfg.dtype == VVS_BF16 && c->dh == 64 && T <= 32 && pos.kv_len && pos.n_emitted && c->d % 64 == 0 && c->d / 64 <= 64;
+// Tile rows per row of a pair in the fused projection + attention kernel (the padding of its activation operand), or 0
+// when a verify call of T block tokens per row does not take that kernel.
+int mfma_qkv_attention_rows(const Ctx* c, const PosDesc& pos, int T) {
+  if (c->cfg.dtype != VVS_BF16 || c->dh != 64 || T > 64 || !pos.kv_len || !pos.n_emitted || c->d % 64 || c->d / 64 > 64) return 0;
+  // 33 .. 64 tokens per row: a workgroup fills a CU (141 KB of LDS), so (head, prompt) pairs beyond the 256 CUs run in rounds,
+  // and a poorly filled third round loses to the separate kernels.  Measured at 20 heads, 61 tokens, ms per step fused /
+  // separate: 8 prompts 3.99 / 4.30, 12: 4.94 / 5.78, 16: 7.25 / 7.32, 24: 8.73 / 9.02, 28: 10.10 / 9.65, 32: 10.63 / 10.25.
+  // (Up to 32 tokens a workgroup is smaller and the fused launch never lost: 13 .. 32 prompts at 27 tokens.)
+  if (T > 32 && c->H * c->B > 512) return 0;
+  return T <= 32 ? 32 : 64;
 }
 
 // q/k/v projection of the row-padded operand A, rotary embedding, cache write and attention in one launch; the result is the
@@ -1562,17 +1589,17 @@ void mfma_qkv_attention(Ctx* c, int layer, const bf16_t* A, const bf16_t* Wqkv, 
   ep.pos = pos; ep.tree = tree;
   bf16_t* out = (bf16_t*)(c->ws + c->w.attn);
   const float c_exp = 1.4426950408889634f / sqrtf((float)c->dh);
-  constexpr int NSL = 6;                   // 5 stages of 16 KiB in flight (8 slots measured the same, 4 slots 5 % slower)
-  constexpr size_t ring = (size_t)NSL * 16 * 1024, tile = (size_t)64 * 196 * sizeof(float), first = ring > tile ? ring : tile;
+  constexpr int NSL = 6;                   // 5 stages in flight (TR = 32: 8 slots measured the same, 4 slots 5 % slower)
   dim3 grid(c->H, c->B);
-  constexpr size_t lds = first + 2 * 32 * 72 * sizeof(bf16_t);   // ring / tile / merge buffers, then q
-  if (T <= 16) {
-    allow_dynamic_lds(reinterpret_cast<const void*>(&k_qkv_attn<NSL, 1>), lds);
-    hipLaunchKernelGGL((k_qkv_attn<NSL, 1>), grid, dim3(512), lds, s, (const uint4*)A, (const uint4*)Wqkv, out, c->d, ep, c_exp);
-  } else {
-    allow_dynamic_lds(reinterpret_cast<const void*>(&k_qkv_attn<NSL, 2>), lds);
-    hipLaunchKernelGGL((k_qkv_attn<NSL, 2>), grid, dim3(512), lds, s, (const uint4*)A, (const uint4*)Wqkv, out, c->d, ep, c_exp);
+#define VVS_QA(TR, NQB)                                                                                                       \
+  {                                                                                                                           \
+    constexpr size_t ring = (size_t)NSL * (4 * (TR / 32) + 12) * 1024, tile = (size_t)2 * TR * 196 * sizeof(float);          \
+    constexpr size_t lds = (ring > tile ? ring : tile) + (size_t)2 * TR * 72 * sizeof(bf16_t); /* ring / tile / merge, then q */ \
+    allow_dynamic_lds(reinterpret_cast<const void*>(&k_qkv_attn<NSL, TR, NQB>), lds);                                         \
+    hipLaunchKernelGGL((k_qkv_attn<NSL, TR, NQB>), grid, dim3(512), lds, s, (const uint4*)A, (const uint4*)Wqkv, out, c->d, ep, c_exp); \
   }
+  if (T <= 16) VVS_QA(32, 1) else if (T <= 32) VVS_QA(32, 2) else VVS_QA(64, 2)
+#undef VVS_QA
 }
 
 

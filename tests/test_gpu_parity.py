@@ -244,6 +244,17 @@ def test_head_size_128_with_a_tree_of_20_nodes(gc):
     show("head size 128, 20-node tree", run_bf16_case(gc, shape, n_forced=40, calls=2))
 
 
+@pytest.mark.parametrize("n_nodes,widths,n_forced", [(40, (6, 8, 8, 8, 6, 4), 45), (12, (4, 4, 4), 20), (63, (8, 12, 12, 10, 9, 8, 4), 201)])
+def test_projection_and_attention_in_one_launch(gc, n_nodes, widths, n_forced):
+    """The launch that runs the q/k/v projection and the attention of a layer together (head size 64, up to 64 tokens
+    per row), at its three instantiations: 41 tokens per row (64 tile rows per row, the second group of 32 queries
+    partly filled), 13 tokens (one block of 16 queries), 64 tokens (every tile row in use); XL width, 2 layers, 3
+    prompts, a cache length that is not a multiple of 32 so that the block's own slots share a 32-key step with old
+    keys."""
+    shape = synth.XL_TREE.replace(n_layers=2, n_prompts=3, n_nodes=n_nodes, tree_widths=widths)
+    show(f"projection + attention, {n_nodes + 1} tokens per row", run_bf16_case(gc, shape, n_forced=n_forced, calls=2))
+
+
 @pytest.mark.parametrize("kv_len", [64, 512, 1000])
 def test_7b_slice_full_width_two_layers(gc, kv_len):
     """Config 4 as specified - full width (d = 4096, 32 heads of 128, d_ff = 11008, 65536 ids with the 8192-id
