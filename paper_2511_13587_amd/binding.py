@@ -78,6 +78,7 @@ def _load():
         "vvs_debug_gemm_scratch_bytes": (sz, [vp, i32, i32, i32]),
         "vvs_debug_gemm": (i32, [vp, i32, i32, i32, vp, vp, vp, vp, vp]),
         "vvs_debug_copy": (i32, [vp, vp, vp, sz, vp]),
+        "vvs_debug_fill_probe": (i32, [vp, vp, sz, i32, i32, i32, i32, vp, vp]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)
@@ -337,6 +338,12 @@ class Context:
         nbytes = src.numel() * src.element_size()
         assert dst.numel() * dst.element_size() == nbytes
         self._check(lib.vvs_debug_copy(self.h, _ptr(dst), _ptr(src), nbytes, _stream()))
+
+    def vvs_debug_fill_probe(self, src: torch.Tensor, reps: int, mode: int, n_workgroups: int, waves: int) -> torch.Tensor:
+        sink = torch.zeros(n_workgroups, dtype=torch.int32, device=self.device)
+        self._check(lib.vvs_debug_fill_probe(self.h, _ptr(src), src.numel() * src.element_size(), reps, mode, n_workgroups, waves,
+                                             _ptr(sink), _stream()))
+        return sink
 
     def vvs_debug_gemm(self, a: torch.Tensor, w: torch.Tensor, m: int, n: int, k: int) -> torch.Tensor:
         nbytes = lib.vvs_debug_gemm_scratch_bytes(self.h, m, n, k)

@@ -275,3 +275,29 @@ def test_hip_graph_replay_of_a_whole_step_bf16(gc):
             assert np.array_equal(a, b)
     dctx.close()
     pair.close()
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_fill_probe_reads_the_region_it_is_given(gc, mode):
+    """The L1 fill probe (a measurement aid): its checksum says that thread 0 of every workgroup read exactly the blocks
+    the declaration describes, for a region that is not a multiple of the 8 blocks x waves in flight; the direct-to-LDS
+    variant leaves 0; arguments out of range are refused before any launch."""
+    vb = gc.vb
+    ctx = vb.Context(vb.make_config(synth.TINY))
+    n_blocks, waves, reps, wgs = 40, 3, 2, 5                  # 40 KiB: 24 blocks per round, then 16
+    words = np.random.default_rng(7).integers(0, 2**32, size=n_blocks * 256, dtype=np.uint64).astype(np.uint32)
+    src = torch.from_numpy(words.view(np.int32)).to(ctx.device)
+    sink = ctx.vvs_debug_fill_probe(src, reps, mode, wgs, waves).cpu().numpy().view(np.uint32)
+    want = 0
+    if mode == 0:
+        for _ in range(reps):
+            for blk in range(0, n_blocks, waves * 8):
+                for u in range(8):
+                    b = min(blk + u * waves, n_blocks - 1)
+                    want = (want + int(words[b * 256] ^ words[b * 256 + 3])) & 0xFFFFFFFF
+    assert (sink == want).all()
+    with pytest.raises(vb.VvsError):
+        ctx.vvs_debug_fill_probe(src, reps, mode, wgs, 17)
+    with pytest.raises(vb.VvsError):
+        ctx.vvs_debug_fill_probe(src[:1000], reps, mode, wgs, waves)
+    ctx.close()
