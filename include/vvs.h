@@ -338,13 +338,14 @@ vvs_status vvs_debug_gemm(vvs_ctx* ctx, int32_t m, int32_t n, int32_t k, const v
 vvs_status vvs_debug_copy(vvs_ctx* ctx, void* d_dst, const void* d_src, size_t bytes, vvs_stream s);
 
 /* Measures how fast a compute unit pulls bytes through its L1 - the figure that bounds the projection kernels of this
- * library.  Launches `n_workgroups` workgroups of `waves` waves (1..16); each workgroup reads the same `region_bytes`
- * (a multiple of 8192, 16-byte aligned; small regions stay in L2) `reps` times, its waves taking 1 KiB blocks round-robin,
- * 8 blocks in flight per wave.  mode 0: 16-byte loads into registers; mode 1: direct-to-LDS loads (the staging path of the
+ * library.  Launches `n_workgroups` workgroups of `waves` waves (1..16); workgroup w reads the `region_bytes` (a multiple of
+ * 8192) at d_src + w * wg_stride_bytes (16-byte aligned; stride 0: every workgroup reads the same region, which then stays
+ * in L2 when it is small; the caller's buffer must hold (n_workgroups - 1) * wg_stride_bytes + region_bytes) `reps` times,
+ * its waves taking 1 KiB blocks round-robin, 8 blocks in flight per wave.  mode 0: 16-byte loads into registers; mode 1: direct-to-LDS loads (the staging path of the
  * tiled GEMMs).  d_sink: uint32 [n_workgroups]; mode 0 leaves a checksum of what thread 0 of each workgroup read (the sum
- * over its loads of word 0 xor word 3), mode 1 leaves 0 - it only keeps the loads alive.  The caller times the launch;
+ * over its loads of the xor of the four words), mode 1 leaves 0 - it only keeps the loads alive.  The caller times the launch;
  * bytes through the L1 of a CU = region_bytes * reps.  VVS_EINVAL for arguments out of these ranges. */
-vvs_status vvs_debug_fill_probe(vvs_ctx* ctx, const void* d_src, size_t region_bytes, int32_t reps, int32_t mode,
+vvs_status vvs_debug_fill_probe(vvs_ctx* ctx, const void* d_src, size_t region_bytes, size_t wg_stride_bytes, int32_t reps, int32_t mode,
                                 int32_t n_workgroups, int32_t waves, uint32_t* d_sink, vvs_stream s);
 
 #ifdef __cplusplus

@@ -78,7 +78,7 @@ def _load():
         "vvs_debug_gemm_scratch_bytes": (sz, [vp, i32, i32, i32]),
         "vvs_debug_gemm": (i32, [vp, i32, i32, i32, vp, vp, vp, vp, vp]),
         "vvs_debug_copy": (i32, [vp, vp, vp, sz, vp]),
-        "vvs_debug_fill_probe": (i32, [vp, vp, sz, i32, i32, i32, i32, vp, vp]),
+        "vvs_debug_fill_probe": (i32, [vp, vp, sz, sz, i32, i32, i32, i32, vp, vp]),
     }
     for name, (res, args) in sigs.items():
         fn = getattr(lib, name)
@@ -339,9 +339,14 @@ class Context:
         assert dst.numel() * dst.element_size() == nbytes
         self._check(lib.vvs_debug_copy(self.h, _ptr(dst), _ptr(src), nbytes, _stream()))
 
-    def vvs_debug_fill_probe(self, src: torch.Tensor, reps: int, mode: int, n_workgroups: int, waves: int) -> torch.Tensor:
+    def vvs_debug_fill_probe(self, src: torch.Tensor, reps: int, mode: int, n_workgroups: int, waves: int,
+                             region_bytes: int = 0, wg_stride_bytes: int = 0) -> torch.Tensor:
+        """region_bytes 0: the whole of src, read by every workgroup; else workgroup w reads region_bytes at w * wg_stride_bytes"""
+        total = src.numel() * src.element_size()
+        region = region_bytes or total
+        assert (n_workgroups - 1) * wg_stride_bytes + region <= total
         sink = torch.zeros(n_workgroups, dtype=torch.int32, device=self.device)
-        self._check(lib.vvs_debug_fill_probe(self.h, _ptr(src), src.numel() * src.element_size(), reps, mode, n_workgroups, waves,
+        self._check(lib.vvs_debug_fill_probe(self.h, _ptr(src), region, wg_stride_bytes, reps, mode, n_workgroups, waves,
                                              _ptr(sink), _stream()))
         return sink
 

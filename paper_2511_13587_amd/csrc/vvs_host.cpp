@@ -721,15 +721,16 @@ vvs_status vvs_debug_copy(vvs_ctx* ctx, void* d_dst, const void* d_src, size_t b
   return check_launch(c, "debug_copy");
 }
 
-vvs_status vvs_debug_fill_probe(vvs_ctx* ctx, const void* d_src, size_t region_bytes, int32_t reps, int32_t mode, int32_t n_workgroups,
-                                int32_t waves, uint32_t* d_sink, vvs_stream s) {
+vvs_status vvs_debug_fill_probe(vvs_ctx* ctx, const void* d_src, size_t region_bytes, size_t wg_stride_bytes, int32_t reps, int32_t mode,
+                                int32_t n_workgroups, int32_t waves, uint32_t* d_sink, vvs_stream s) {
   Ctx* c = reinterpret_cast<Ctx*>(ctx);
   if (!c) return VVS_EINVAL;
-  if (!d_src || !d_sink || ((uintptr_t)d_src & 15) || region_bytes < 8192 || (region_bytes & 8191) || region_bytes > ((size_t)1 << 30))
-    return fail(&c->err, VVS_EINVAL, "debug_fill_probe: the region must be 16-byte aligned and a multiple of 8192 bytes, at most 1 GiB");
+  if (!d_src || !d_sink || ((uintptr_t)d_src & 15) || region_bytes < 8192 || (region_bytes & 8191) || region_bytes > ((size_t)1 << 30) ||
+      (wg_stride_bytes & 15) || wg_stride_bytes > ((size_t)1 << 30))
+    return fail(&c->err, VVS_EINVAL, "debug_fill_probe: the region must be 16-byte aligned and a multiple of 8192 bytes, region and stride at most 1 GiB");
   if (reps < 1 || reps > (1 << 20) || (mode != 0 && mode != 1) || n_workgroups < 1 || n_workgroups > 65536 || waves < 1 || waves > 16)
     return fail(&c->err, VVS_EINVAL, "debug_fill_probe: reps, mode, workgroups or waves out of range");
-  launch_fill_probe(d_src, region_bytes, reps, mode, n_workgroups, waves, d_sink, (hipStream_t)s);
+  launch_fill_probe(d_src, region_bytes, wg_stride_bytes, reps, mode, n_workgroups, waves, d_sink, (hipStream_t)s);
   return check_launch(c, "debug_fill_probe");
 }
 

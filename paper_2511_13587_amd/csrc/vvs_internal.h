@@ -135,7 +135,8 @@ void launch_read_state(Ctx* c, int32_t* d_state, hipStream_t s);
 void launch_set_state(Ctx* c, const int32_t* d_state, hipStream_t s);
 void launch_debug_logits(Ctx* c, float* raw, float* mixed, float* probs, hipStream_t s);
 void launch_debug_kv(Ctx* c, int layer, int row, int n_slots, float* dk, float* dv, hipStream_t s);
-void launch_fill_probe(const void* src, size_t region_bytes, int reps, int mode, int n_workgroups, int waves, uint32_t* sink, hipStream_t s);
+void launch_fill_probe(const void* src, size_t region_bytes, size_t wg_stride_bytes, int reps, int mode, int n_workgroups, int waves,
+                       uint32_t* sink, hipStream_t s);
 void launch_debug_gemm(Ctx* c, int m, int n, int k, const void* a, const void* w, void* scratch, float* out, hipStream_t s);
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

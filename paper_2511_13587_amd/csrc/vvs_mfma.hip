@@ -672,8 +672,10 @@ __device__ __forceinline__ void lds_dma16(const void* g, uint32_t lds_byte_addr)
 // L1 fill probe (vvs_debug_fill_probe): every workgroup reads the same region `reps` times; a wave takes 1 KiB blocks
 // round-robin, 8 in flight.  DMA: the blocks go straight to LDS (8 slots per wave), else into registers.
 template <bool DMA>
-__global__ __launch_bounds__(1024) void k_fill_probe(const uint4* __restrict__ src, int n_blocks, int reps, uint32_t* __restrict__ sink) {
+__global__ __launch_bounds__(1024) void k_fill_probe(const uint4* __restrict__ src0, size_t wg_stride16, int n_blocks, int reps,
+                                                     uint32_t* __restrict__ sink) {
   extern __shared__ float probe_lds[];     // DMA: 8 KiB per wave
+  const uint4* src = src0 + (size_t)blockIdx.x * wg_stride16;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
   const uint32_t slot0 = (uint32_t)(uintptr_t)probe_lds + (uint32_t)wave * 8192u;
   uint32_t acc = 0;
@@ -688,7 +690,7 @@ __global__ __launch_bounds__(1024) void k_fill_probe(const uint4* __restrict__ s
 #pragma unroll
         for (int u = 0; u < 8; ++u) v[u] = src[(size_t)min(blk + u * nw, n_blocks - 1) * 64 + lane];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) acc += v[u].x ^ v[u].w;
+        for (int u = 0; u < 8; ++u) acc += (v[u].x ^ v[u].y) ^ (v[u].z ^ v[u].w);   // all four words: the loads stay 16 bytes wide
       }
     }
   }
@@ -696,14 +698,15 @@ __global__ __launch_bounds__(1024) void k_fill_probe(const uint4* __restrict__ s
   if (threadIdx.x == 0) sink[blockIdx.x] = acc;
 }
 
-void launch_fill_probe(const void* src, size_t region_bytes, int reps, int mode, int n_workgroups, int waves, uint32_t* sink, hipStream_t s) {
+void launch_fill_probe(const void* src, size_t region_bytes, size_t wg_stride_bytes, int reps, int mode, int n_workgroups, int waves,
+                       uint32_t* sink, hipStream_t s) {
   const int n_blocks = (int)(region_bytes >> 10);
   if (mode == 1) {
     const size_t lds = (size_t)waves * 8192;
     allow_dynamic_lds(reinterpret_cast<const void*>(&k_fill_probe<true>), lds);
-    hipLaunchKernelGGL(k_fill_probe<true>, dim3(n_workgroups), dim3(waves * 64), lds, s, (const uint4*)src, n_blocks, reps, sink);
+    hipLaunchKernelGGL(k_fill_probe<true>, dim3(n_workgroups), dim3(waves * 64), lds, s, (const uint4*)src, wg_stride_bytes >> 4, n_blocks, reps, sink);
   } else {
-    hipLaunchKernelGGL(k_fill_probe<false>, dim3(n_workgroups), dim3(waves * 64), 0, s, (const uint4*)src, n_blocks, reps, sink);
+    hipLaunchKernelGGL(k_fill_probe<false>, dim3(n_workgroups), dim3(waves * 64), 0, s, (const uint4*)src, wg_stride_bytes >> 4, n_blocks, reps, sink);
   }
 }
 

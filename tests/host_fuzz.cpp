@@ -30,7 +30,7 @@ namespace vvs {
 static long g_launches = 0;
 void launch_fill_zero(void* p, size_t bytes, hipStream_t) { memset(p, 0, bytes); ++g_launches; }
 void launch_copy_bytes(void* dst, const void* src, size_t bytes, hipStream_t) { memmove(dst, src, bytes); ++g_launches; }
-void launch_fill_probe(const void*, size_t, int, int, int, int, uint32_t*, hipStream_t) { ++g_launches; }
+void launch_fill_probe(const void*, size_t, size_t, int, int, int, int, uint32_t*, hipStream_t) { ++g_launches; }
 void launch_pack_weights(Ctx*, const void* const*, hipStream_t) { ++g_launches; }
 void launch_forward(Ctx* c, const TreeDesc& tree, const PosDesc&, int T, const int32_t*, const void*, const void*, int, const int32_t*, int,
                     int, hipStream_t, bool from_din) {

@@ -287,15 +287,20 @@ def test_fill_probe_reads_the_region_it_is_given(gc, mode):
     n_blocks, waves, reps, wgs = 40, 3, 2, 5                  # 40 KiB: 24 blocks per round, then 16
     words = np.random.default_rng(7).integers(0, 2**32, size=n_blocks * 256, dtype=np.uint64).astype(np.uint32)
     src = torch.from_numpy(words.view(np.int32)).to(ctx.device)
+    def expected(first_block, blocks):
+        want = 0
+        if mode == 0:
+            for _ in range(reps):
+                for blk in range(0, blocks, waves * 8):
+                    for u in range(8):
+                        b = first_block + min(blk + u * waves, blocks - 1)
+                        want = (want + int(words[b * 256] ^ words[b * 256 + 1] ^ words[b * 256 + 2] ^ words[b * 256 + 3])) & 0xFFFFFFFF
+        return want
     sink = ctx.vvs_debug_fill_probe(src, reps, mode, wgs, waves).cpu().numpy().view(np.uint32)
-    want = 0
-    if mode == 0:
-        for _ in range(reps):
-            for blk in range(0, n_blocks, waves * 8):
-                for u in range(8):
-                    b = min(blk + u * waves, n_blocks - 1)
-                    want = (want + int(words[b * 256] ^ words[b * 256 + 3])) & 0xFFFFFFFF
-    assert (sink == want).all()
+    assert (sink == expected(0, n_blocks)).all()
+    # a region of 8 blocks of its own per workgroup
+    sink = ctx.vvs_debug_fill_probe(src, reps, mode, wgs, waves, region_bytes=8192, wg_stride_bytes=8192).cpu().numpy().view(np.uint32)
+    assert [int(v) for v in sink] == [expected(8 * w, 8) for w in range(wgs)]
     with pytest.raises(vb.VvsError):
         ctx.vvs_debug_fill_probe(src, reps, mode, wgs, 17)
     with pytest.raises(vb.VvsError):
