@@ -308,7 +308,9 @@ vvs_status vvs_set_state(vvs_ctx* ctx, const int32_t* d_state, vvs_stream s);
 /* Kernel-class timing for benchmarks.  While enabled, every kernel launch of prefill / verify /
  * commit is bracketed by HIP events recorded on the caller's stream (host objects; no device
  * memory).  vvs_timing_read waits for the recorded events and returns the number of launches and
- * their summed duration for one class since timing was enabled. */
+ * their summed duration for one class since timing was enabled.  Where a layer's q/k/v projection and its
+ * attention run as one launch (bf16, head size 64, up to 64 tokens per row), that launch counts as VVS_K_GEMM
+ * and the attention class stays empty. */
 enum { VVS_K_GEMM = 0, VVS_K_ATTENTION = 1, VVS_K_ACCEPT = 2, VVS_K_ELEMENTWISE = 3, VVS_K_COMMIT = 4, VVS_K_CLASSES = 5 };
 vvs_status vvs_timing_enable(vvs_ctx* ctx, int32_t on);
 vvs_status vvs_timing_read(vvs_ctx* ctx, int32_t kernel_class, int32_t* n_launches, float* total_ms);
