@@ -258,12 +258,13 @@ void launch_build_tokens(Ctx* c, int T, const int32_t* d_draft, hipStream_t s) {
 // ------------------------------------------------------------------------------------------------ residual add + RMSNorm
 // Output row i reads x row (i * in_stride + in_off): x_row += sum of GEMM partials (if any), then
 // h_row = x_row / sqrt(mean(x_row^2) + eps) * g, rounded to the operand type.
-template <typename T, int NCH>
-__global__ __launch_bounds__(256) void k_add_rmsnorm(float* __restrict__ x, const float* __restrict__ partial, int splits,
+template <typename T, int NCH, int NT>
+__global__ __launch_bounds__(NT) void k_add_rmsnorm(float* __restrict__ x, const float* __restrict__ partial, int splits,
                                                      size_t split_stride, int d, const float* __restrict__ g, float eps,
                                                      T* __restrict__ h, int in_stride, int in_off) {
-  // each thread owns NCH chunks of 8 consecutive values of the row (d <= NCH * 2048) and keeps them in
-  // registers between the sum of squares and the scaling
+  // each of the NT threads owns NCH chunks of 8 consecutive values of the row (d <= NCH * NT * 8) and keeps them in
+  // registers between the sum of squares and the scaling; one chunk per thread where the row allows it, so that
+  // everything a row needs is requested in one round trip to memory
   __shared__ float red[16];
   const size_t row = (size_t)blockIdx.x * in_stride + in_off;
   float* xr = x + row * d;
@@ -271,15 +272,34 @@ __global__ __launch_bounds__(256) void k_add_rmsnorm(float* __restrict__ x, cons
   float ss = 0.f;
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
-    const int k0 = (threadIdx.x + 256 * j) * 8;
+    const int k0 = (threadIdx.x + NT * j) * 8;
     if (k0 < d) {
       const float4 a = *(const float4*)(xr + k0), b = *(const float4*)(xr + k0 + 4);
       float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
       if (splits) {
-        for (int s = 0; s < splits; ++s) {
+        // all partial sums of the chunk are requested before the first is added (the planner makes at most 8 splits): one
+        // round trip to memory per chunk instead of one per split; added in the order of the splits
+        constexpr int kMaxSplits = 8;
+        float4 pa[kMaxSplits], pb[kMaxSplits];
+#pragma unroll
+        for (int s = 0; s < kMaxSplits; ++s) {
+          if (s < splits) {
+            const float* pr = partial + s * split_stride + row * d + k0;
+            pa[s] = *(const float4*)pr;
+            pb[s] = *(const float4*)(pr + 4);
+          }
+        }
+#pragma unroll
+        for (int s = 0; s < kMaxSplits; ++s) {
+          if (s < splits) {
+            v[0] += pa[s].x; v[1] += pa[s].y; v[2] += pa[s].z; v[3] += pa[s].w;
+            v[4] += pb[s].x; v[5] += pb[s].y; v[6] += pb[s].z; v[7] += pb[s].w;
+          }
+        }
+        for (int s = kMaxSplits; s < splits; ++s) {          // not reached with the planner's limit
           const float* pr = partial + s * split_stride + row * d + k0;
-          const float4 pa = *(const float4*)pr, pb = *(const float4*)(pr + 4);
-          v[0] += pa.x; v[1] += pa.y; v[2] += pa.z; v[3] += pa.w; v[4] += pb.x; v[5] += pb.y; v[6] += pb.z; v[7] += pb.w;
+          const float4 qa = *(const float4*)pr, qb = *(const float4*)(pr + 4);
+          v[0] += qa.x; v[1] += qa.y; v[2] += qa.z; v[3] += qa.w; v[4] += qb.x; v[5] += qb.y; v[6] += qb.z; v[7] += qb.w;
         }
         *(float4*)(xr + k0) = make_float4(v[0], v[1], v[2], v[3]);
         *(float4*)(xr + k0 + 4) = make_float4(v[4], v[5], v[6], v[7]);
@@ -295,7 +315,7 @@ __global__ __launch_bounds__(256) void k_add_rmsnorm(float* __restrict__ x, cons
   const float scale = 1.0f / sqrtf(ss / (float)d + eps);
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
-    const int k0 = (threadIdx.x + 256 * j) * 8;
+    const int k0 = (threadIdx.x + NT * j) * 8;
     if (k0 < d) {
       float gv[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
       if (g) {
@@ -314,11 +334,11 @@ template <typename T>
 static void launch_add_rmsnorm(int rows, float* x, const float* partial, int splits, size_t split_stride, int d, const float* g, float eps,
                                T* h, int in_stride, int in_off, hipStream_t s) {
   if (d <= 2048)
-    hipLaunchKernelGGL((k_add_rmsnorm<T, 1>), dim3(rows), dim3(256), 0, s, x, partial, splits, split_stride, d, g, eps, h, in_stride, in_off);
+    hipLaunchKernelGGL((k_add_rmsnorm<T, 1, 256>), dim3(rows), dim3(256), 0, s, x, partial, splits, split_stride, d, g, eps, h, in_stride, in_off);
   else if (d <= 4096)
-    hipLaunchKernelGGL((k_add_rmsnorm<T, 2>), dim3(rows), dim3(256), 0, s, x, partial, splits, split_stride, d, g, eps, h, in_stride, in_off);
+    hipLaunchKernelGGL((k_add_rmsnorm<T, 1, 512>), dim3(rows), dim3(512), 0, s, x, partial, splits, split_stride, d, g, eps, h, in_stride, in_off);
   else
-    hipLaunchKernelGGL((k_add_rmsnorm<T, 8>), dim3(rows), dim3(256), 0, s, x, partial, splits, split_stride, d, g, eps, h, in_stride, in_off);
+    hipLaunchKernelGGL((k_add_rmsnorm<T, 8, 256>), dim3(rows), dim3(256), 0, s, x, partial, splits, split_stride, d, g, eps, h, in_stride, in_off);
 }
 
 // ------------------------------------------------------------------------------------------------ RoPE + KV write
