@@ -1251,8 +1251,8 @@ __global__ __launch_bounds__(NW * QG * 64, (DH * NQB >= 256 ? 1 : 2)) void k_att
 //     holding a slot of the block itself is read before them, so the L1 of the CU cannot hold a stale copy of the slots
 //     just written.
 //   Measured with time stamps at the end of the image (TR = 32, 55 k cycles): start-up 3 k, projection main loop 24 k (16 KiB
-//     per 600 cycles: the L1 fill rate of a CU), tile to LDS 2.5 k, epilogue + fence 5 k, attention steps 17 k (VALU-bound: 8
-//     waves share 4 SIMDs), merge + store 3 k.
+//     per 600 cycles, paced by how fast the CU's address unit takes the stage requests: without them the loop takes 4.4 of
+//     its 10.4 us, without the MFMAs 10.2), tile to LDS 2.5 k, epilogue + fence 5 k, attention steps 17 k, merge + store 3 k.
 template <int NSL, int TR, int NQB>
 __global__ __launch_bounds__(512) void k_qkv_attn(const uint4* __restrict__ Ap, const uint4* __restrict__ Wp, bf16_t* __restrict__ out,
                                                   int K, const GemmEpi ep, float c_exp) {
