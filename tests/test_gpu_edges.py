@@ -306,3 +306,29 @@ def test_fill_probe_reads_the_region_it_is_given(gc, mode):
     with pytest.raises(vb.VvsError):
         ctx.vvs_debug_fill_probe(src[:1000], reps, mode, wgs, waves)
     ctx.close()
+
+
+@pytest.mark.parametrize("case", ["xl_27_tokens", "xl_61_tokens_few_prompts", "xl_61_tokens_many_prompts", "head_size_128"])
+def test_which_launches_a_layer_takes(gc, case):
+    """The launch plan is part of what the library promises to measure with (vvs_timing_read): a verify call runs the q/k/v
+    projection and the attention of a layer as one launch at head size 64 with up to 32 tokens per row, and with up to 64
+    tokens while there are at most 512 (head, prompt) pairs; otherwise, and at head size 128, as separate launches."""
+    vb = gc.vb
+    if case == "xl_27_tokens":
+        shape, fused_attention = synth.XL_TREE.replace(n_layers=2, n_prompts=2), True
+    elif case == "xl_61_tokens_few_prompts":
+        shape, fused_attention = synth.XL_STRESS.replace(n_layers=2, n_prompts=2), True
+    elif case == "xl_61_tokens_many_prompts":
+        shape, fused_attention = synth.XL_STRESS.replace(n_layers=1, n_prompts=26), False     # 520 pairs
+    else:
+        shape, fused_attention = synth.SEVEN_B.replace(n_layers=2, d_model=1024, n_heads=8, d_ff=2752), False
+    parent = synth.tree_parents(shape.tree_widths, shape.n_nodes)
+    pair = gc.Pair(shape, with_oracle=False)
+    pair.prefill(n_forced=10, run_oracle=False)
+    q, toks = synth.make_draft(shape, parent, 0)
+    u = synth.make_uniforms(shape, shape.n_nodes, 0)
+    pair.ctx.vvs_timing_enable(True)
+    pair.verify(parent, toks, q, u, run_oracle=False)
+    n_attention, _ = pair.ctx.vvs_timing_read(vb.VVS_K_ATTENTION)
+    pair.ctx.vvs_timing_enable(False)
+    assert n_attention == (0 if fused_attention else shape.n_layers)
